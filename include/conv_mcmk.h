@@ -1,0 +1,136 @@
+/*
+ * conv_mcmk.h -- C ABI of libconv_mcmk: multi-channel multi-kernel (MCMK) 2-D
+ * convolution on one AMD MI355X (gfx950), computed the kn2row way.
+ *
+ * The operation (paper Eq. 1-3): for every image n, kernel m and output
+ * position (q, p)
+ *
+ *     O[n][m][q][p] = sum_c sum_i sum_j  I[n][c][q - pad + i][p - pad + j] * K[m][c][i][j]
+ *
+ * with terms whose input coordinate falls outside the image dropped (zero
+ * padding), no kernel flip, stride 1.  Q = H + 2 pad - k + 1 rows and
+ * P = W + 2 pad - k + 1 columns.
+ *
+ * Conventions common to every entry point
+ *   - All tensors are dense, row-major, in DEVICE memory, 16-byte aligned, and
+ *     owned by the caller: I[N][C][H][W], K[M][C][k][k] (row tap i, then column
+ *     tap j), O[N][M][Q][P].  N = 1 is the paper's un-batched call.
+ *   - The library allocates nothing, never synchronises and launches only on the
+ *     stream handed in (`stream` is a hipStream_t passed as void*; NULL = the
+ *     default stream).  Results are ready when that stream reaches the end of
+ *     the call's work.
+ *   - O is completely overwritten.  I, K / Kp, O and the workspace must not overlap.
+ *   - Every argument is validated before anything is launched; errors are
+ *     return codes (CONV_MCMK_OK = 0), nothing throws or aborts.
+ *   - dtype CONV_MCMK_F32: I, packed kernel and O are float.
+ *     dtype CONV_MCMK_BF16: I and the packed kernel are bfloat16 (the upper 16
+ *     bits of a float, rounded to nearest even), accumulation and O are float.
+ */
+#ifndef CONV_MCMK_H
+#define CONV_MCMK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct conv_mcmk_desc {
+    int32_t n;       /* images in the batch, >= 1 */
+    int32_t c;       /* input channels, >= 1 */
+    int32_t h, w;    /* input rows, columns, >= 1 */
+    int32_t m;       /* kernels (output channels), >= 1 */
+    int32_t k;       /* kernel side, >= 1 (square kernels) */
+    int32_t pad;     /* zero padding on every side, >= 0 */
+    int32_t stride;  /* must be 1: the paper leaves strided convolution out (section II-A) */
+    int32_t dtype;   /* CONV_MCMK_F32 or CONV_MCMK_BF16 */
+} conv_mcmk_desc;
+
+enum { CONV_MCMK_F32 = 0, CONV_MCMK_BF16 = 1 };
+
+/* How the convolution is computed.  All four give the same O up to rounding order. */
+enum {
+    CONV_MCMK_KN2ROW       = 0, /* k*k 1x1 GEMMs on the unreplicated input, shift-add fused into the
+                                   accumulators (section III-A without the k*k-sized product matrix) */
+    CONV_MCMK_KN2ROW_2PASS = 1, /* section III-A as written: one GEMM [k*k*M x C].[C x HW] into the
+                                   workspace, then the shift-add post pass */
+    CONV_MCMK_IM2COL       = 2, /* section II-B: build the column matrix in the workspace, then one GEMM */
+    CONV_MCMK_DIRECT       = 3  /* the loop nest of Eq. 1-3, one output element per thread, no matrix cores */
+};
+
+enum {
+    CONV_MCMK_OK              = 0,
+    CONV_MCMK_ERR_NULL        = 1, /* a required pointer is NULL */
+    CONV_MCMK_ERR_SHAPE       = 2, /* a dimension < 1, pad < 0, empty output, or a tensor of 2^31 or more elements per image */
+    CONV_MCMK_ERR_UNSUPPORTED = 3, /* stride != 1, unknown dtype or variant, or a k / dtype the variant does not implement */
+    CONV_MCMK_ERR_WORKSPACE   = 4, /* workspace missing or smaller than conv_mcmk_workspace_bytes() */
+    CONV_MCMK_ERR_DEVICE      = 5, /* the HIP runtime refused a launch */
+    CONV_MCMK_ERR_ALIGN       = 6  /* a pointer is not 16-byte aligned */
+};
+
+/* Text for an error code; never NULL, static storage. */
+const char *conv_mcmk_strerror(int code);
+
+/* CONV_MCMK_OK if `variant` can run `desc`, else the error the compute call would return. */
+int conv_mcmk_check(const conv_mcmk_desc *desc, int variant);
+
+/*
+ * Bytes of caller-provided scratch a variant needs (0 for KN2ROW and DIRECT; 0 also for an invalid
+ * desc -- use conv_mcmk_check for the reason).
+ *   KN2ROW_2PASS: N * k*k*M * H*W floats -- the GEMM result of section III-A, per image
+ *                 T[t*M + m][y*W + x], t = i*k + j ("some increase in the size of the output").
+ *   IM2COL:       N * C*k*k * Q*P elements of the input's type -- the input-patch-matrix of
+ *                 section II-B, per image Ihat[(c*k + i)*k + j][q*P + p] (k*k times the input).
+ * After a 2PASS / IM2COL call the workspace holds exactly those matrices.
+ */
+size_t conv_mcmk_workspace_bytes(const conv_mcmk_desc *desc, int variant);
+
+/*
+ * Bytes of the re-ordered kernel a variant consumes (0 for DIRECT, which reads K as is, and for an
+ * invalid desc).  The re-ordering is the "made statically ahead of time" step of section III-A: the
+ * logical matrix is [k*k*M] x [C] for the kn2row variants (row t*M + m, channel innermost) and
+ * [M] x [C*k*k] for im2col (section II-B's kernel-patch-matrix).  Physically it is stored in the order
+ * the matrix-core instruction takes its operand, zero-padded to whole tiles:
+ *   rows in blocks of 16 (MB = ceil(M/16) blocks per tap), contraction index in groups of G
+ *   (G = 16 for F32, 32 for BF16; CG = ceil(Kc/G) groups; Kc = C for kn2row, C*k*k for im2col):
+ *     F32 : float  Kp[t][mb][cg][lane 0..63][v 0..3]  = A_t[mb*16 + lane%16][cg*16 + 4*v + lane/16]
+ *     BF16: bf16   Kp[t][mb][cg][lane 0..63][e 0..7]  = A_t[mb*16 + lane%16][cg*32 + 8*(lane/16) + e]
+ *   where A_t[m][c] = K[m][c][i][j] for kn2row (t = i*k + j) and, for im2col, t = 0 and
+ *   A_0[m][(c*k + i)*k + j] = K[m][c][i][j].  Entries beyond M or Kc are zero.
+ */
+size_t conv_mcmk_packed_kernel_bytes(const conv_mcmk_desc *desc, int variant);
+
+/*
+ * Re-order K (device, float, [M][C][k][k]) into Kp (device, conv_mcmk_packed_kernel_bytes() bytes)
+ * for `variant`; converts to bfloat16 when desc->dtype is CONV_MCMK_BF16.  Done once per layer and
+ * not part of the timed convolution (section III-A).  The KN2ROW and KN2ROW_2PASS packings are identical.
+ */
+int conv_mcmk_prepack(const conv_mcmk_desc *desc, int variant, const void *K_dev, void *Kp_dev, void *stream);
+
+/*
+ * The convolution itself, one entry point per variant, same signature.
+ *   I_dev   input, float or bfloat16 per desc->dtype
+ *   Kp_dev  kernel: the packed form from conv_mcmk_prepack(desc, <this variant>) --
+ *           except conv_mcmk_direct, which takes the plain float K[M][C][k][k]
+ *   O_dev   output, float
+ *   ws, ws_bytes  scratch of at least conv_mcmk_workspace_bytes(); may be NULL / 0 when that is 0
+ * conv_mcmk_kn2row implements k = 1, 3, 5, 7 (other k: CONV_MCMK_ERR_UNSUPPORTED; the other
+ * variants take any k >= 1).  conv_mcmk_direct implements CONV_MCMK_F32 only.
+ */
+int conv_mcmk_kn2row(const conv_mcmk_desc *desc, const void *I_dev, const void *Kp_dev, void *O_dev,
+                     void *ws, size_t ws_bytes, void *stream);
+int conv_mcmk_kn2row_2pass(const conv_mcmk_desc *desc, const void *I_dev, const void *Kp_dev, void *O_dev,
+                           void *ws, size_t ws_bytes, void *stream);
+int conv_mcmk_im2col(const conv_mcmk_desc *desc, const void *I_dev, const void *Kp_dev, void *O_dev,
+                     void *ws, size_t ws_bytes, void *stream);
+int conv_mcmk_direct(const conv_mcmk_desc *desc, const void *I_dev, const void *K_dev, void *O_dev,
+                     void *ws, size_t ws_bytes, void *stream);
+
+/* float -> bfloat16 (round to nearest even), `count` elements, device to device. */
+int conv_mcmk_cvt_f32_bf16(const void *src_dev, void *dst_dev, size_t count, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CONV_MCMK_H */

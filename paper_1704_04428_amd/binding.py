@@ -1,0 +1,165 @@
+"""Thin ctypes binding over libconv_mcmk.so: argument marshalling only.
+
+Every function here has the name and the meaning of the C entry point in
+include/conv_mcmk.h; torch tensors are used for device memory and streams and
+nothing else.  There is no CPU fallback: if the HIP library has not been built
+the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libconv_mcmk.so")
+
+F32, BF16 = 0, 1
+KN2ROW, KN2ROW_2PASS, IM2COL, DIRECT = 0, 1, 2, 3
+VARIANTS = {"kn2row": KN2ROW, "kn2row_2pass": KN2ROW_2PASS, "im2col": IM2COL, "direct": DIRECT}
+
+OK, ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_DEVICE, ERR_ALIGN = range(7)
+
+EXPORTS = (
+    "conv_mcmk_strerror", "conv_mcmk_check", "conv_mcmk_workspace_bytes", "conv_mcmk_packed_kernel_bytes",
+    "conv_mcmk_prepack", "conv_mcmk_kn2row", "conv_mcmk_kn2row_2pass", "conv_mcmk_im2col",
+    "conv_mcmk_direct", "conv_mcmk_cvt_f32_bf16",
+)
+
+
+class Desc(ctypes.Structure):
+    _fields_ = [(name, ctypes.c_int32) for name in ("n", "c", "h", "w", "m", "k", "pad", "stride", "dtype")]
+
+
+class ConvMcmkError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"conv_mcmk error {code}: {text}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """Load libconv_mcmk.so (built in-tree by paper_1704_04428_amd.build); raises when it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_1704_04428_amd.build` "
+                "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        dp = ctypes.POINTER(Desc)
+        vp, sz, i = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+        L.conv_mcmk_strerror.argtypes = [i]
+        L.conv_mcmk_strerror.restype = ctypes.c_char_p
+        L.conv_mcmk_check.argtypes = [dp, i]
+        L.conv_mcmk_check.restype = i
+        L.conv_mcmk_workspace_bytes.argtypes = [dp, i]
+        L.conv_mcmk_workspace_bytes.restype = sz
+        L.conv_mcmk_packed_kernel_bytes.argtypes = [dp, i]
+        L.conv_mcmk_packed_kernel_bytes.restype = sz
+        L.conv_mcmk_prepack.argtypes = [dp, i, vp, vp, vp]
+        L.conv_mcmk_prepack.restype = i
+        for name in ("conv_mcmk_kn2row", "conv_mcmk_kn2row_2pass", "conv_mcmk_im2col", "conv_mcmk_direct"):
+            fn = getattr(L, name)
+            fn.argtypes = [dp, vp, vp, vp, vp, sz, vp]
+            fn.restype = i
+        L.conv_mcmk_cvt_f32_bf16.argtypes = [vp, vp, sz, vp]
+        L.conv_mcmk_cvt_f32_bf16.restype = i
+        _lib = L
+    return _lib
+
+
+def desc(n, c, h, w, m, k, pad, stride=1, dtype=F32) -> Desc:
+    return Desc(n, c, h, w, m, k, pad, stride, dtype)
+
+
+def strerror(code: int) -> str:
+    return lib().conv_mcmk_strerror(code).decode()
+
+
+def _raise(code: int):
+    if code != OK:
+        raise ConvMcmkError(code, strerror(code))
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+
+def _stream(stream):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def conv_mcmk_check(d: Desc, variant: int) -> int:
+    return lib().conv_mcmk_check(ctypes.byref(d), variant)
+
+
+def conv_mcmk_workspace_bytes(d: Desc, variant: int) -> int:
+    return lib().conv_mcmk_workspace_bytes(ctypes.byref(d), variant)
+
+
+def conv_mcmk_packed_kernel_bytes(d: Desc, variant: int) -> int:
+    return lib().conv_mcmk_packed_kernel_bytes(ctypes.byref(d), variant)
+
+
+def conv_mcmk_prepack(d: Desc, variant: int, K, Kp, stream=None) -> None:
+    _raise(lib().conv_mcmk_prepack(ctypes.byref(d), variant, _ptr(K), _ptr(Kp), _stream(stream)))
+
+
+def _run(name, d, I, Kp, O, ws, stream):
+    ws_bytes = ws.numel() * ws.element_size() if ws is not None else 0
+    fn = getattr(lib(), name)
+    _raise(fn(ctypes.byref(d), _ptr(I), _ptr(Kp), _ptr(O), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def conv_mcmk_kn2row(d, I, Kp, O, ws=None, stream=None):
+    _run("conv_mcmk_kn2row", d, I, Kp, O, ws, stream)
+
+
+def conv_mcmk_kn2row_2pass(d, I, Kp, O, ws=None, stream=None):
+    _run("conv_mcmk_kn2row_2pass", d, I, Kp, O, ws, stream)
+
+
+def conv_mcmk_im2col(d, I, Kp, O, ws=None, stream=None):
+    _run("conv_mcmk_im2col", d, I, Kp, O, ws, stream)
+
+
+def conv_mcmk_direct(d, I, K, O, ws=None, stream=None):
+    _run("conv_mcmk_direct", d, I, K, O, ws, stream)
+
+
+def conv_mcmk_cvt_f32_bf16(src, dst, count=None, stream=None):
+    n = src.numel() if count is None else count
+    _raise(lib().conv_mcmk_cvt_f32_bf16(_ptr(src), _ptr(dst), n, _stream(stream)))
+
+
+RUNNERS = {KN2ROW: conv_mcmk_kn2row, KN2ROW_2PASS: conv_mcmk_kn2row_2pass, IM2COL: conv_mcmk_im2col,
+           DIRECT: conv_mcmk_direct}
+
+
+class Plan:
+    """Device buffers for one layer and one variant: packed kernel, workspace and output, allocated
+    once with torch; run() is a single library call on the current stream."""
+
+    def __init__(self, d: Desc, variant: int, K_dev):
+        import torch
+        _raise(conv_mcmk_check(d, variant))
+        self.d, self.variant = d, variant
+        dev = K_dev.device
+        if variant == DIRECT:
+            self.kernel = K_dev
+        else:
+            nbytes = conv_mcmk_packed_kernel_bytes(d, variant)
+            self.kernel = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+            conv_mcmk_prepack(d, variant, K_dev, self.kernel)
+        ws_bytes = conv_mcmk_workspace_bytes(d, variant)
+        self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev) if ws_bytes else None
+        q, p = d.h + 2 * d.pad - d.k + 1, d.w + 2 * d.pad - d.k + 1
+        self.out = torch.empty((d.n, d.m, q, p), dtype=torch.float32, device=dev)
+
+    def run(self, I_dev, stream=None):
+        RUNNERS[self.variant](self.d, I_dev, self.kernel, self.out, self.ws, stream)
+        return self.out

@@ -1,0 +1,314 @@
+// libconv_mcmk: C ABI and launch logic.  See include/conv_mcmk.h for the contract.
+#include "../../include/conv_mcmk.h"
+
+#include <hip/hip_runtime.h>
+
+#include "aux_kernels.h"
+#include "kn2row_tile.h"
+
+namespace {
+
+using namespace mcmk;
+
+constexpr int kNumCU = 256;   // MI355X
+
+inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
+
+struct Dims {
+    int q, p, mb, taps;
+};
+
+int validate(const conv_mcmk_desc *d, int variant, Dims *out)
+{
+    if (!d) return CONV_MCMK_ERR_NULL;
+    if (d->n < 1 || d->c < 1 || d->h < 1 || d->w < 1 || d->m < 1 || d->k < 1 || d->pad < 0)
+        return CONV_MCMK_ERR_SHAPE;
+    const long long q = (long long)d->h + 2LL * d->pad - d->k + 1;
+    const long long p = (long long)d->w + 2LL * d->pad - d->k + 1;
+    if (q < 1 || p < 1) return CONV_MCMK_ERR_SHAPE;
+    const long long lim = 1LL << 31;
+    const long long kk = (long long)d->k * d->k;
+    if ((long long)d->c * d->h * d->w >= lim || (long long)d->m * q * p >= lim ||
+        (long long)d->m * d->c * kk >= lim || (long long)d->c * kk * q * p >= lim * 4 ||
+        kk * d->m * d->h * d->w >= lim * 4 || q >= 65536 * 16 || p >= 65536 * 16)
+        return CONV_MCMK_ERR_SHAPE;
+    if (d->stride != 1) return CONV_MCMK_ERR_UNSUPPORTED;
+    if (d->dtype != CONV_MCMK_F32 && d->dtype != CONV_MCMK_BF16) return CONV_MCMK_ERR_UNSUPPORTED;
+    switch (variant) {
+    case CONV_MCMK_KN2ROW:
+        if (d->k != 1 && d->k != 3 && d->k != 5 && d->k != 7) return CONV_MCMK_ERR_UNSUPPORTED;
+        if (d->pad > 65535) return CONV_MCMK_ERR_SHAPE;
+        break;
+    case CONV_MCMK_KN2ROW_2PASS:
+    case CONV_MCMK_IM2COL:
+        break;
+    case CONV_MCMK_DIRECT:
+        if (d->dtype != CONV_MCMK_F32) return CONV_MCMK_ERR_UNSUPPORTED;
+        break;
+    default:
+        return CONV_MCMK_ERR_UNSUPPORTED;
+    }
+    if (d->dtype == CONV_MCMK_BF16) return CONV_MCMK_ERR_UNSUPPORTED;   // bf16 operands: not built yet
+    if (out) {
+        out->q = (int)q;
+        out->p = (int)p;
+        out->mb = ceil_div(d->m, 16);
+        out->taps = d->k * d->k;
+    }
+    return CONV_MCMK_OK;
+}
+
+inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+int launch_status()
+{
+    return hipGetLastError() == hipSuccess ? CONV_MCMK_OK : CONV_MCMK_ERR_DEVICE;
+}
+
+int grid_for(size_t total, int block)
+{
+    size_t g = (total + block - 1) / block;
+    const size_t cap = (size_t)kNumCU * 64;
+    return (int)(g < 1 ? 1 : (g > cap ? cap : g));
+}
+
+// ------------------------------------------------------------------------------------------
+// Tile-shape menu for the fused kernel and the cost estimate that picks from it.
+// cost = matrix-core block-steps on the busiest SIMD: workgroups per CU (ceil) x waves per SIMD x
+// blocks per wave.  Ties go to the larger row tile (fewer re-reads of the input tile).
+struct Candidate {
+    int th, tw, wm, wp;
+};
+
+template <int KS, int TH, int TW, int WM, int WP>
+int launch_tile(const conv_mcmk_desc *d, const Dims &dm, const float *in, const float *apk, float *out,
+                int in_c, int in_h, int in_w, int out_q, int out_p, int pad, int row_groups, hipStream_t st)
+{
+    using S = TileShape<KS, TH, TW, WM, WP>;
+    TileArgs a;
+    a.in = in;  a.apk = apk;  a.out = out;
+    a.n = d->n;  a.c = in_c;  a.h = in_h;  a.w = in_w;
+    a.q = out_q;  a.p = out_p;  a.pad = pad;
+    a.m = d->m;  a.mb_per_group = dm.mb;  a.row_groups = row_groups;
+    a.cg = ceil_div(in_c, 16);
+    a.tiles_x = ceil_div(out_p, TW);
+    a.tiles_y = ceil_div(out_q, TH);
+    a.row_tiles = ceil_div((long long)row_groups * dm.mb, WM);
+    const long long blocks = (long long)a.n * a.tiles_x * a.tiles_y * a.row_tiles;
+    if (blocks < 1 || blocks >= (1LL << 31)) return CONV_MCMK_ERR_SHAPE;
+    hipLaunchKernelGGL((kn2row_tile_f32<KS, TH, TW, WM, WP>), dim3((unsigned)blocks), dim3(S::kThreads),
+                       S::kLdsBytes, st, a);
+    return launch_status();
+}
+
+long long tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c)
+{
+    const long long wgs = (long long)d->n * ceil_div(dm.p, c.tw) * ceil_div(dm.q, c.th) * ceil_div(dm.mb, c.wm);
+    const int npb = ceil_div(c.th * c.tw, 16);
+    const int pbw = ceil_div(npb, c.wp);
+    const int waves_per_simd = ceil_div(c.wm * c.wp, 4);
+    return ((wgs + kNumCU - 1) / kNumCU) * waves_per_simd * pbw;
+}
+
+template <int KS>
+int launch_fused(const conv_mcmk_desc *d, const Dims &dm, const float *in, const float *apk, float *out,
+                 hipStream_t st)
+{
+    static const Candidate menu[] = {{14, 14, 4, 2}, {16, 16, 4, 2}, {14, 14, 1, 4}, {16, 16, 1, 4}};
+    int best = 0;
+    long long best_cost = -1;
+    for (int i = 0; i < 4; ++i) {
+        const long long c = tile_cost(d, dm, menu[i]);
+        if (best_cost < 0 || c < best_cost) { best_cost = c; best = i; }
+    }
+#define MCMK_GO(TH, TW, WM, WP) \
+    return launch_tile<KS, TH, TW, WM, WP>(d, dm, in, apk, out, d->c, d->h, d->w, dm.q, dm.p, d->pad, 1, st)
+    switch (best) {
+    case 0: MCMK_GO(14, 14, 4, 2);
+    case 1: MCMK_GO(16, 16, 4, 2);
+    case 2: MCMK_GO(14, 14, 1, 4);
+    default: MCMK_GO(16, 16, 1, 4);
+    }
+#undef MCMK_GO
+}
+
+// Plain GEMM [rows x kc] . [kc x cols] per image on the same tile kernel: a 1x1 "convolution" over a
+// 1 x cols image.
+int launch_gemm(const conv_mcmk_desc *d, const Dims &dm, const float *bmat, const float *apk, float *cmat,
+                int kc, long long cols, int row_groups, hipStream_t st)
+{
+    if (cols >= (1LL << 31)) return CONV_MCMK_ERR_SHAPE;
+    return launch_tile<1, 1, 256, 4, 2>(d, dm, bmat, apk, cmat, kc, 1, (int)cols, 1, (int)cols, 0, row_groups, st);
+}
+
+int common_ptr_checks(const void *I, const void *K, const void *O)
+{
+    if (!I || !K || !O) return CONV_MCMK_ERR_NULL;
+    if (misaligned(I) || misaligned(K) || misaligned(O)) return CONV_MCMK_ERR_ALIGN;
+    return CONV_MCMK_OK;
+}
+
+int workspace_check(const conv_mcmk_desc *d, int variant, const void *ws, size_t ws_bytes)
+{
+    const size_t need = conv_mcmk_workspace_bytes(d, variant);
+    if (need == 0) return CONV_MCMK_OK;
+    if (!ws || ws_bytes < need) return CONV_MCMK_ERR_WORKSPACE;
+    if (misaligned(ws)) return CONV_MCMK_ERR_ALIGN;
+    return CONV_MCMK_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *conv_mcmk_strerror(int code)
+{
+    switch (code) {
+    case CONV_MCMK_OK: return "ok";
+    case CONV_MCMK_ERR_NULL: return "a required pointer is NULL";
+    case CONV_MCMK_ERR_SHAPE: return "invalid shape (dimension < 1, negative pad, empty output or tensor too large)";
+    case CONV_MCMK_ERR_UNSUPPORTED: return "unsupported stride, dtype, variant or kernel size for this variant";
+    case CONV_MCMK_ERR_WORKSPACE: return "workspace missing or too small";
+    case CONV_MCMK_ERR_DEVICE: return "the HIP runtime refused a launch";
+    case CONV_MCMK_ERR_ALIGN: return "a pointer is not 16-byte aligned";
+    default: return "unknown error code";
+    }
+}
+
+int conv_mcmk_check(const conv_mcmk_desc *desc, int variant) { return validate(desc, variant, nullptr); }
+
+size_t conv_mcmk_workspace_bytes(const conv_mcmk_desc *d, int variant)
+{
+    Dims dm;
+    if (validate(d, variant, &dm) != CONV_MCMK_OK) return 0;
+    const size_t elt = d->dtype == CONV_MCMK_BF16 ? 2 : 4;
+    switch (variant) {
+    case CONV_MCMK_KN2ROW_2PASS: return (size_t)d->n * dm.taps * d->m * d->h * d->w * sizeof(float);
+    case CONV_MCMK_IM2COL: return (size_t)d->n * d->c * dm.taps * dm.q * dm.p * elt;
+    default: return 0;
+    }
+}
+
+size_t conv_mcmk_packed_kernel_bytes(const conv_mcmk_desc *d, int variant)
+{
+    Dims dm;
+    if (validate(d, variant, &dm) != CONV_MCMK_OK) return 0;
+    const int group = d->dtype == CONV_MCMK_BF16 ? 32 : 16;
+    const size_t elt = d->dtype == CONV_MCMK_BF16 ? 2 : 4;
+    switch (variant) {
+    case CONV_MCMK_KN2ROW:
+    case CONV_MCMK_KN2ROW_2PASS:
+        return (size_t)dm.taps * dm.mb * ceil_div(d->c, group) * 16 * group * elt;
+    case CONV_MCMK_IM2COL:
+        return (size_t)dm.mb * ceil_div((long long)d->c * dm.taps, group) * 16 * group * elt;
+    default: return 0;
+    }
+}
+
+int conv_mcmk_prepack(const conv_mcmk_desc *d, int variant, const void *K_dev, void *Kp_dev, void *stream)
+{
+    Dims dm;
+    int rc = validate(d, variant, &dm);
+    if (rc) return rc;
+    if (variant == CONV_MCMK_DIRECT) return CONV_MCMK_ERR_UNSUPPORTED;
+    if (!K_dev || !Kp_dev) return CONV_MCMK_ERR_NULL;
+    if (misaligned(K_dev) || misaligned(Kp_dev)) return CONV_MCMK_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool im2col = variant == CONV_MCMK_IM2COL;
+    const int taps = im2col ? 1 : dm.taps;
+    const int cg = im2col ? ceil_div((long long)d->c * dm.taps, 16) : ceil_div(d->c, 16);
+    const size_t total = (size_t)taps * dm.mb * cg * 256;
+    hipLaunchKernelGGL(prepack_f32_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st,
+                       static_cast<const float *>(K_dev), static_cast<float *>(Kp_dev),
+                       d->m, d->c, d->k, dm.mb, cg, taps, im2col);
+    return launch_status();
+}
+
+int conv_mcmk_kn2row(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_dev, void *O_dev,
+                     void *ws, size_t ws_bytes, void *stream)
+{
+    (void)ws; (void)ws_bytes;
+    Dims dm;
+    int rc = validate(d, CONV_MCMK_KN2ROW, &dm);
+    if (rc) return rc;
+    if ((rc = common_ptr_checks(I_dev, Kp_dev, O_dev))) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const float *in = static_cast<const float *>(I_dev);
+    const float *apk = static_cast<const float *>(Kp_dev);
+    float *out = static_cast<float *>(O_dev);
+    switch (d->k) {
+    case 1: return launch_fused<1>(d, dm, in, apk, out, st);
+    case 3: return launch_fused<3>(d, dm, in, apk, out, st);
+    case 5: return launch_fused<5>(d, dm, in, apk, out, st);
+    case 7: return launch_fused<7>(d, dm, in, apk, out, st);
+    default: return CONV_MCMK_ERR_UNSUPPORTED;
+    }
+}
+
+int conv_mcmk_kn2row_2pass(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_dev, void *O_dev,
+                           void *ws, size_t ws_bytes, void *stream)
+{
+    Dims dm;
+    int rc = validate(d, CONV_MCMK_KN2ROW_2PASS, &dm);
+    if (rc) return rc;
+    if ((rc = common_ptr_checks(I_dev, Kp_dev, O_dev))) return rc;
+    if ((rc = workspace_check(d, CONV_MCMK_KN2ROW_2PASS, ws, ws_bytes))) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float *T = static_cast<float *>(ws);
+    // pass 1: T[n][t*M+m][HW] = Kp[k*k*M x C] . I[n][C x HW]
+    rc = launch_gemm(d, dm, static_cast<const float *>(I_dev), static_cast<const float *>(Kp_dev), T,
+                     d->c, (long long)d->h * d->w, dm.taps, st);
+    if (rc) return rc;
+    // pass 2: shift-add of the k*k planes
+    const size_t total = (size_t)d->n * d->m * dm.q * dm.p;
+    hipLaunchKernelGGL(shift_add_f32_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, T,
+                       static_cast<float *>(O_dev), d->n, d->m, d->h, d->w, d->k, d->pad, dm.q, dm.p);
+    return launch_status();
+}
+
+int conv_mcmk_im2col(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_dev, void *O_dev,
+                     void *ws, size_t ws_bytes, void *stream)
+{
+    Dims dm;
+    int rc = validate(d, CONV_MCMK_IM2COL, &dm);
+    if (rc) return rc;
+    if ((rc = common_ptr_checks(I_dev, Kp_dev, O_dev))) return rc;
+    if ((rc = workspace_check(d, CONV_MCMK_IM2COL, ws, ws_bytes))) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float *cols = static_cast<float *>(ws);
+    const size_t total = (size_t)d->n * d->c * dm.taps * dm.q * dm.p;
+    hipLaunchKernelGGL(im2col_build_f32_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st,
+                       static_cast<const float *>(I_dev), cols, d->n, d->c, d->h, d->w, d->k, d->pad, dm.q, dm.p);
+    if ((rc = launch_status())) return rc;
+    return launch_gemm(d, dm, cols, static_cast<const float *>(Kp_dev), static_cast<float *>(O_dev),
+                       d->c * dm.taps, (long long)dm.q * dm.p, 1, st);
+}
+
+int conv_mcmk_direct(const conv_mcmk_desc *d, const void *I_dev, const void *K_dev, void *O_dev,
+                     void *ws, size_t ws_bytes, void *stream)
+{
+    (void)ws; (void)ws_bytes;
+    Dims dm;
+    int rc = validate(d, CONV_MCMK_DIRECT, &dm);
+    if (rc) return rc;
+    if ((rc = common_ptr_checks(I_dev, K_dev, O_dev))) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t total = (size_t)d->n * d->m * dm.q * dm.p;
+    hipLaunchKernelGGL(direct_f32_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st,
+                       static_cast<const float *>(I_dev), static_cast<const float *>(K_dev),
+                       static_cast<float *>(O_dev), d->n, d->c, d->h, d->w, d->m, d->k, d->pad, dm.q, dm.p);
+    return launch_status();
+}
+
+int conv_mcmk_cvt_f32_bf16(const void *src_dev, void *dst_dev, size_t count, void *stream)
+{
+    if (!src_dev || !dst_dev) return CONV_MCMK_ERR_NULL;
+    if (misaligned(src_dev) || misaligned(dst_dev)) return CONV_MCMK_ERR_ALIGN;
+    if (count == 0) return CONV_MCMK_OK;
+    hipLaunchKernelGGL(cvt_f32_bf16_kernel, dim3(grid_for(count, 256)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const float *>(src_dev),
+                       static_cast<uint16_t *>(dst_dev), count);
+    return launch_status();
+}
+
+}  // extern "C"

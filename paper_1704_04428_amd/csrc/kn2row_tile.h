@@ -1,0 +1,237 @@
+// Workgroup-tile kernel shared by every matrix-core variant (fp32 operands).
+//
+// One workgroup produces a tile of [16*WM rows] x [TH x TW output positions] of one image.
+// The contraction runs over (tap, channel): for every tap (i, j) of the KS x KS kernel the tile
+// receives the 1x1-convolution product  A_t[rows x C] . I[C x positions displaced by the tap]
+// (paper section III-A), accumulated in the same registers for all taps -- the shift-add of
+// kn2row happens as an address offset into the input tile held in LDS, so the k*k partial planes
+// never exist in memory.  With KS = 1 and TH = 1 the same kernel is a plain GEMM
+// [rows x C] . [C x columns], which is what the staged variants (kn2row two-pass, im2col) call.
+//
+// Operands
+//   A (kernel): pre-ordered in global memory exactly as v_mfma_f32_16x16x4_f32 takes it, so a wave
+//     loads its fragments with one coalesced 16-byte load per lane and tap, straight into VGPRs
+//     (double-buffered one tap row ahead).  No LDS traffic for A.
+//   B (input): a halo tile of 16 channels x (TH+KS-1) x (TW+KS-1), zero-filled outside the image,
+//     staged global -> registers -> LDS, double-buffered one 16-channel chunk ahead.
+//     Each lane keeps the LDS address of its output position; a tap is an immediate offset.
+//
+// MFMA 16x16x4 f32 layouts (lane l of 64):  A[row l%16][k l/16],  B[k l/16][col l%16],
+//   D[row 4*(l/16) + v][col l%16] for accumulator register v = 0..3.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <type_traits>
+
+namespace mcmk {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+struct TileArgs {
+    const float *in;      // [n][c][h][w]
+    const float *apk;     // packed A: [taps][mb_per_tap][cg][64][4]
+    float *out;           // [n][out_rows][q][p]
+    int n, c, h, w;       // input
+    int q, p;             // output plane
+    int pad;
+    int m;                // valid rows per row group
+    int mb_per_group;     // 16-row blocks per row group (= ceil(m/16))
+    int row_groups;       // 1 for a convolution; k*k when the rows are (tap, m) pairs
+    int cg;               // 16-channel groups (= ceil(c/16)) == number of chunks
+    int tiles_x, tiles_y; // spatial tiles per image
+    int row_tiles;        // ceil(row_groups*mb_per_group / WM)
+};
+
+template <int KS, int TH, int TW, int WM, int WP>
+struct TileShape {
+    static constexpr int kCC = 16;                       // channels per chunk
+    static constexpr int kThreads = 64 * WM * WP;
+    static constexpr int kHT = TH + KS - 1;
+    static constexpr int kWT = TW + KS - 1;
+    static constexpr int kPos = kHT * kWT;               // halo-tile positions per channel
+    // channel stride in LDS words: >= kPos and == 16 mod 32, so the four channels one B fragment
+    // touches start 16 banks apart
+    static constexpr int kCHS = ((kPos + 15) / 32) * 32 + 16;
+    static constexpr int kBuf = kCC * kCHS;              // words per LDS buffer
+    static constexpr int kNPB = (TH * TW + 15) / 16;     // 16-position blocks per tile
+    static constexpr int kPBW = (kNPB + WP - 1) / WP;    // blocks per wave
+    static constexpr int kSlots = (kCC * kPos + kThreads - 1) / kThreads;
+    static constexpr size_t kLdsBytes = 2 * (size_t)kBuf * sizeof(float);
+};
+
+template <int KS, int TH, int TW, int WM, int WP>
+__global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a)
+{
+    using S = TileShape<KS, TH, TW, WM, WP>;
+    constexpr int CC = S::kCC, NT = S::kThreads, WT = S::kWT, POS = S::kPos, CHS = S::kCHS;
+    constexpr int PBW = S::kPBW, NPB = S::kNPB, SLOTS = S::kSlots, BUF = S::kBuf;
+    // position blocks are dealt evenly to the WP waves: the first REM waves own PBW blocks, the
+    // others PBW-1 (all own PBW when the split is exact)
+    constexpr int REM = NPB % WP;
+    constexpr bool kRagged = REM != 0;
+    static_assert(NPB >= WP, "every wave needs at least one position block");
+
+    extern __shared__ float lds[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WM;
+    const int wp = wave / WM;
+
+    // ---- which tile
+    int bid = blockIdx.x;
+    const int rt = bid % a.row_tiles;  bid /= a.row_tiles;
+    const int tx = bid % a.tiles_x;    bid /= a.tiles_x;
+    const int ty = bid % a.tiles_y;    bid /= a.tiles_y;
+    const int img = bid;
+    const int x0 = tx * TW, y0 = ty * TH;
+
+    const int total_rb = a.row_groups * a.mb_per_group;
+    int rb = rt * WM + wm;                       // this wave's 16-row block
+    const bool rb_valid = rb < total_rb;
+    if (!rb_valid) rb = total_rb - 1;            // keep loads in bounds; nothing is stored
+    const int grp = rb / a.mb_per_group;         // row group (tap index when rows are (tap, m))
+    const int mbi = rb % a.mb_per_group;
+
+    // ---- staging plan: element e = tid + s*NT of the [CC][POS] halo tile
+    const size_t plane = (size_t)a.h * a.w;
+    const float *in_img = a.in + (size_t)img * a.c * plane;
+    int g_off[SLOTS];      // offset inside one channel plane, or -1 when outside the image
+    int l_off[SLOTS];      // word offset inside an LDS buffer, or -1 when the slot is unused
+    int s_ch[SLOTS];       // channel inside the chunk
+#pragma unroll
+    for (int s = 0; s < SLOTS; ++s) {
+        const int e = tid + s * NT;
+        const int cl = e / POS, pos = e % POS;
+        const int r = pos / WT, col = pos % WT;
+        const int gy = y0 - a.pad + r, gx = x0 - a.pad + col;
+        const bool used = e < CC * POS;
+        const bool inside = used && gy >= 0 && gy < a.h && gx >= 0 && gx < a.w;
+        g_off[s] = inside ? gy * a.w + gx : -1;
+        l_off[s] = used ? cl * CHS + r * WT + col : -1;
+        s_ch[s] = cl;
+    }
+
+    float stage[SLOTS];
+    auto load_chunk = [&](int chunk) {
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) {
+            const int ch = chunk * CC + s_ch[s];
+            float v = 0.0f;
+            if (g_off[s] >= 0 && ch < a.c) v = in_img[(size_t)ch * plane + g_off[s]];
+            stage[s] = v;
+        }
+    };
+    auto store_chunk = [&](float *buf) {
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s)
+            if (l_off[s] >= 0) buf[l_off[s]] = stage[s];
+    };
+
+    // ---- per-lane LDS offsets of this wave's output positions (B operand: k = lane/16, col = lane%16)
+    const int nb_wave = (!kRagged || wp < REM) ? PBW : PBW - 1;                  // wave-uniform
+    const int first_pb = kRagged ? wp * (PBW - 1) + min(wp, REM) : wp * PBW;     // first block owned
+    int b_off[PBW];
+#pragma unroll
+    for (int b = 0; b < PBW; ++b) {
+        int pp = (first_pb + b) * 16 + (lane & 15);
+        if (pp >= TH * TW) pp = 0;
+        b_off[b] = (lane >> 4) * CHS + (pp / TW) * WT + (pp % TW);
+    }
+
+    // ---- A fragments: one f32x4 per lane per tap covers a 16-channel chunk
+    const f32x4 *apk = reinterpret_cast<const f32x4 *>(a.apk);
+    auto load_a_row = [&](int chunk, int i, f32x4 (&dst)[KS]) {
+#pragma unroll
+        for (int j = 0; j < KS; ++j) {
+            // conv: tap planes are [tap][mb][cg]; row-group GEMM: KS == 1 and grp picks the plane
+            const size_t tap = (size_t)(i * KS + j) + grp;
+            dst[j] = apk[((tap * a.mb_per_group + mbi) * a.cg + chunk) * 64 + lane];
+        }
+    };
+
+    f32x4 acc[PBW];
+#pragma unroll
+    for (int b = 0; b < PBW; ++b) acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    f32x4 a_next[KS];
+    load_chunk(0);
+    load_a_row(0, 0, a_next);
+    store_chunk(lds);
+    __syncthreads();
+
+    // One chunk of matrix-core work for NB position blocks (NB is PBW, or PBW-1 for the wave that
+    // owns the ragged last share); straight-line code, every LDS offset an immediate.
+    auto compute_chunk = [&](auto nb_tag, int chunk, bool more) {
+        constexpr int NB = decltype(nb_tag)::value;
+        constexpr int STEPS = KS * 4;              // per tap row: (column tap j, channel quad v)
+        const float *bsrc = lds + (chunk & 1) * BUF;
+        float bq[2][NB];                           // B fragments: this step's and the next one's
+#pragma unroll
+        for (int b = 0; b < NB; ++b) bq[0][b] = bsrc[b_off[b]];
+#pragma unroll
+        for (int i = 0; i < KS; ++i) {
+            f32x4 a_cur[KS];
+#pragma unroll
+            for (int j = 0; j < KS; ++j) a_cur[j] = a_next[j];
+            if (i + 1 < KS) load_a_row(chunk, i + 1, a_next);
+            else if (more) load_a_row(chunk + 1, 0, a_next);
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) {
+                const int j = s / 4, v = s % 4;
+                const int g = i * STEPS + s;       // step number inside the chunk
+                // fetch the next step's fragments while this step's products run
+                const int s1 = (s + 1) % STEPS, i1 = (s + 1 < STEPS) ? i : i + 1;
+                if (i1 < KS) {
+#pragma unroll
+                    for (int b = 0; b < NB; ++b)
+                        bq[(g + 1) & 1][b] = bsrc[b_off[b] + (4 * (s1 % 4)) * CHS + i1 * WT + s1 / 4];
+                }
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+                    acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[j][v], bq[g & 1][b], acc[b], 0, 0, 0);
+                // keep the steps in program order: reads for step g+1 stay ahead of the products of
+                // step g and never drift further
+                if (i1 < KS) {
+#pragma unroll
+                    for (int b = 0; b < NB; ++b) {
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read ...
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // ... then one MFMA
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    };
+
+    const int nchunks = a.cg;
+    for (int chunk = 0; chunk < nchunks; ++chunk) {
+        const bool more = chunk + 1 < nchunks;
+        if (more) load_chunk(chunk + 1);
+        if (kRagged && nb_wave != PBW) compute_chunk(std::integral_constant<int, kRagged ? PBW - 1 : PBW>{}, chunk, more);
+        else compute_chunk(std::integral_constant<int, PBW>{}, chunk, more);
+        if (more) store_chunk(lds + ((chunk + 1) & 1) * BUF);
+        __syncthreads();
+    }
+
+    // ---- write the tile: accumulator register v of lane l is row 4*(l/16)+v, position l%16
+    if (!rb_valid) return;
+    const size_t oplane = (size_t)a.q * a.p;
+    const int out_rows = a.row_groups * a.m;
+    float *out_img = a.out + (size_t)img * out_rows * oplane;
+#pragma unroll
+    for (int b = 0; b < PBW; ++b) {
+        if (b >= nb_wave) continue;
+        const int pp = (first_pb + b) * 16 + (lane & 15);
+        const int y = y0 + pp / TW, x = x0 + pp % TW;
+        if (pp >= TH * TW || y >= a.q || x >= a.p) continue;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int mrow = mbi * 16 + 4 * (lane >> 4) + v;
+            if (mrow < a.m) out_img[(size_t)(grp * a.m + mrow) * oplane + (size_t)y * a.p + x] = acc[b][v];
+        }
+    }
+}
+
+}  // namespace mcmk

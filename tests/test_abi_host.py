@@ -1,0 +1,97 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and validates descriptors before touching the device."""
+import os
+import re
+
+import pytest
+
+from paper_1704_04428_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_1704_04428_amd import build
+        build.build()
+    return B.lib()
+
+
+def _declared_symbols():
+    with open(os.path.join(ROOT, "include", "conv_mcmk.h")) as f:
+        text = f.read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(conv_mcmk_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_symbols()
+    assert set(names) == set(B.EXPORTS)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_strerror_covers_all_codes(lib):
+    texts = [B.strerror(c) for c in range(7)]
+    assert texts[0] == "ok" and len(set(texts)) == 7
+    assert "unknown" in B.strerror(99)
+
+
+def test_check_accepts_benchmark_layers(lib):
+    from paper_1704_04428_amd import workloads as wl
+    for L in wl.LAYERS.values():
+        d = B.desc(L.n, L.c, L.h, L.w, L.m, L.k, L.pad)
+        for v in (B.KN2ROW, B.KN2ROW_2PASS, B.IM2COL, B.DIRECT):
+            assert B.conv_mcmk_check(d, v) == B.OK, (L.name, v)
+
+
+def test_check_rejects_bad_descriptors(lib):
+    ok = dict(n=1, c=4, h=8, w=8, m=4, k=3, pad=1)
+    for field in ("n", "c", "h", "w", "m", "k"):
+        bad = dict(ok, **{field: 0})
+        assert B.conv_mcmk_check(B.desc(**bad), B.KN2ROW_2PASS) == B.ERR_SHAPE, field
+    assert B.conv_mcmk_check(B.desc(**dict(ok, pad=-1)), B.KN2ROW) == B.ERR_SHAPE
+    assert B.conv_mcmk_check(B.desc(**dict(ok, h=2, w=2, k=5, pad=0)), B.IM2COL) == B.ERR_SHAPE   # empty output
+    assert B.conv_mcmk_check(B.desc(**ok, stride=2), B.KN2ROW) == B.ERR_UNSUPPORTED              # section II-A
+    assert B.conv_mcmk_check(B.desc(**ok, dtype=7), B.KN2ROW) == B.ERR_UNSUPPORTED
+    assert B.conv_mcmk_check(B.desc(**ok), 9) == B.ERR_UNSUPPORTED
+    assert B.conv_mcmk_check(B.desc(**dict(ok, k=4)), B.KN2ROW) == B.ERR_UNSUPPORTED             # fused: k in 1,3,5,7
+    assert B.conv_mcmk_check(B.desc(**dict(ok, k=4)), B.KN2ROW_2PASS) == B.OK
+    assert B.conv_mcmk_check(B.desc(**dict(ok, h=70000, w=70000)), B.DIRECT) == B.ERR_SHAPE      # >= 2^31 per image
+    assert lib.conv_mcmk_check(None, B.KN2ROW) == B.ERR_NULL
+
+
+def test_sizes(lib):
+    d = B.desc(2, 20, 9, 11, 35, 3, 1)
+    q, p = 9, 11
+    assert B.conv_mcmk_workspace_bytes(d, B.KN2ROW) == 0
+    assert B.conv_mcmk_workspace_bytes(d, B.DIRECT) == 0
+    assert B.conv_mcmk_workspace_bytes(d, B.KN2ROW_2PASS) == 2 * 9 * 35 * 9 * 11 * 4     # k^2 x the output
+    assert B.conv_mcmk_workspace_bytes(d, B.IM2COL) == 2 * 20 * 9 * q * p * 4             # k^2 x the input
+    mb, cg = 3, 2      # ceil(35/16), ceil(20/16)
+    assert B.conv_mcmk_packed_kernel_bytes(d, B.KN2ROW) == 9 * mb * cg * 256 * 4
+    assert B.conv_mcmk_packed_kernel_bytes(d, B.KN2ROW_2PASS) == 9 * mb * cg * 256 * 4
+    assert B.conv_mcmk_packed_kernel_bytes(d, B.IM2COL) == mb * 12 * 256 * 4              # ceil(180/16) = 12
+    assert B.conv_mcmk_packed_kernel_bytes(d, B.DIRECT) == 0
+    assert B.conv_mcmk_workspace_bytes(B.desc(0, 1, 1, 1, 1, 1, 0), B.IM2COL) == 0
+
+
+def test_compute_calls_validate_before_launch(lib):
+    """NULL pointers and bad descriptors are refused on the host: no device is touched."""
+    import ctypes
+    d = B.desc(1, 4, 8, 8, 4, 3, 1)
+    null = ctypes.c_void_p(0)
+    for name in ("conv_mcmk_kn2row", "conv_mcmk_kn2row_2pass", "conv_mcmk_im2col", "conv_mcmk_direct"):
+        fn = getattr(lib, name)
+        assert fn(ctypes.byref(d), null, null, null, null, 0, null) == B.ERR_NULL
+        bad = B.desc(1, 4, 8, 8, 4, 3, 1, stride=2)
+        assert fn(ctypes.byref(bad), null, null, null, null, 0, null) == B.ERR_UNSUPPORTED
+    fake = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1004)
+    assert lib.conv_mcmk_kn2row(ctypes.byref(d), odd, fake, fake, null, 0, null) == B.ERR_ALIGN
+    assert lib.conv_mcmk_im2col(ctypes.byref(d), fake, fake, fake, null, 0, null) == B.ERR_WORKSPACE
+    assert lib.conv_mcmk_kn2row_2pass(ctypes.byref(d), fake, fake, fake, fake, 16, null) == B.ERR_WORKSPACE
+    assert lib.conv_mcmk_prepack(ctypes.byref(d), B.KN2ROW, null, null, null) == B.ERR_NULL
+    assert lib.conv_mcmk_prepack(ctypes.byref(d), B.DIRECT, fake, fake, null) == B.ERR_UNSUPPORTED
+    assert lib.conv_mcmk_cvt_f32_bf16(null, null, 4, null) == B.ERR_NULL

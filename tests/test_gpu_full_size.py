@@ -1,0 +1,47 @@
+"""The benchmark configurations at full size, in the launch configuration bench.py times:
+sampled outputs against the oracle (it computes single outputs one by one), plus whole-output
+comparison for the shapes the oracle finishes in seconds."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1704_04428_amd import binding as B
+from paper_1704_04428_amd import workloads as wl
+
+from gpu_util import TOL_F32, announce, assert_within_bound, run_variant
+
+pytestmark = pytest.mark.gpu
+
+VARIANTS = [("kn2row", B.KN2ROW), ("kn2row_2pass", B.KN2ROW_2PASS), ("im2col", B.IM2COL), ("direct", B.DIRECT)]
+
+
+@pytest.mark.parametrize("name,variant", VARIANTS)
+@pytest.mark.parametrize("layer", ["cfg1_tiny", "cfg2_googlenet5x5", "cfg3_alexnet_conv2"])
+def test_whole_output(layer, name, variant):
+    L = wl.LAYERS[layer]
+    announce("full", layer, name)
+    I, K = wl.make_input(L), wl.make_kernel(L)
+    ref, absref = oracle.mcmk(I, K, L.pad)
+    got = run_variant(variant, I, K, L.pad)
+    assert_within_bound(got, ref, absref, TOL_F32, f"{name} {layer}")
+
+
+@pytest.mark.parametrize("name,variant", VARIANTS)
+@pytest.mark.parametrize("layer", ["cfg4_vgg_early", "cfg5a_vgg_deep56", "cfg5b_vgg_deep28", "cfg5c_vgg_deep14"])
+def test_sampled_outputs(layer, name, variant):
+    L = wl.LAYERS[layer]
+    if variant == B.DIRECT and L.flops > 1e10:
+        pytest.skip("the plain-ALU direct kernel is a comparison point for the small layers only")
+    announce("sampled", layer, name)
+    I, K = wl.make_input(L), wl.make_kernel(L)
+    pts = wl.sample_points(L, 3000)
+    ref, absref = oracle.mcmk_at(I, K, L.pad, pts)
+    got = run_variant(variant, I, K, L.pad)
+    assert np.all(np.isfinite(got))
+    sampled = got[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]]
+    assert_within_bound(sampled, ref, absref, TOL_F32, f"{name} {layer}")
+    # every variant must agree with the fused kernel everywhere (any-size property)
+    if variant != B.KN2ROW:
+        fused = run_variant(B.KN2ROW, I, K, L.pad)
+        scale = np.abs(fused).max()
+        assert np.abs(got - fused).max() <= 2e-4 * max(scale, 1.0) * 4

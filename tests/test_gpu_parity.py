@@ -1,0 +1,215 @@
+"""GPU parity: every variant of the library, called through the C ABI, against the CPU oracle.
+
+Bounds: fp32 operands |gpu - oracle| <= 1e-4 * sum|K||I| per output element (the oracle's second
+output is that sum); data made of small integers must match bit for bit in any summation order.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import steps
+from paper_1704_04428_amd import binding as B
+from paper_1704_04428_amd import workloads as wl
+
+from gpu_util import TOL_F32, announce, assert_within_bound, run_variant
+
+pytestmark = pytest.mark.gpu
+
+ALL = [("kn2row", B.KN2ROW), ("kn2row_2pass", B.KN2ROW_2PASS), ("im2col", B.IM2COL), ("direct", B.DIRECT)]
+
+# (n, c, h, w, m, k, pad): several tiles, ragged tails in every dimension, degenerate sizes
+SMALL = [
+    (1, 16, 32, 32, 16, 3, 1),     # the tiny benchmark shape
+    (2, 20, 17, 19, 35, 3, 1),     # nothing a multiple of a tile
+    (1, 5, 30, 9, 7, 5, 2),
+    (1, 33, 15, 15, 18, 1, 0),     # 1x1: the plain GEMM of section III
+    (1, 7, 20, 21, 9, 7, 3),
+    (1, 3, 14, 14, 64, 3, 1),      # exactly one spatial tile, few channels (first-layer-like)
+    (3, 17, 29, 43, 70, 3, 1),     # several row tiles
+    (1, 4, 9, 9, 5, 3, 0),         # no padding: output smaller than input
+    (1, 4, 6, 7, 5, 3, 2),         # padding k-1: output larger than input
+    (1, 1, 1, 1, 1, 1, 0),         # a single product
+    (1, 2, 3, 3, 2, 3, 1),
+    (2, 40, 28, 28, 48, 5, 2),
+]
+EVEN_K = [(1, 6, 12, 13, 10, 2, 1), (2, 5, 11, 10, 20, 4, 1), (1, 3, 10, 10, 4, 6, 0)]
+
+
+def _inputs(case, seed):
+    n, c, h, w, m, k, pad = case
+    I = wl.uniform(seed, n * c * h * w, -1, 1).reshape(n, c, h, w)
+    K = wl.normal(seed + 1, m * c * k * k, 0.5).reshape(m, c, k, k)
+    return I, K
+
+
+@pytest.mark.parametrize("name,variant", ALL)
+@pytest.mark.parametrize("case", SMALL)
+def test_small_shapes_match_oracle(name, variant, case):
+    announce("small", name, case)
+    I, K = _inputs(case, 1000 + sum(case))
+    ref, absref = oracle.mcmk(I, K, case[-1])
+    got = run_variant(variant, I, K, case[-1])
+    assert got.shape == ref.shape
+    assert_within_bound(got, ref, absref, TOL_F32, f"{name} {case}")
+
+
+@pytest.mark.parametrize("name,variant", [a for a in ALL if a[1] != B.KN2ROW])
+@pytest.mark.parametrize("case", EVEN_K)
+def test_even_kernel_sizes(name, variant, case):
+    announce("even-k", name, case)
+    I, K = _inputs(case, 2000 + sum(case))
+    ref, absref = oracle.mcmk(I, K, case[-1])
+    got = run_variant(variant, I, K, case[-1])
+    assert_within_bound(got, ref, absref, TOL_F32, f"{name} {case}")
+
+
+@pytest.mark.parametrize("name,variant", ALL)
+@pytest.mark.parametrize("case", [(2, 20, 17, 19, 35, 3, 1), (1, 24, 31, 16, 40, 5, 2), (1, 9, 15, 16, 33, 1, 0)])
+def test_integer_data_is_bit_exact(name, variant, case):
+    """Integer-valued inputs keep every partial sum below 2^24, so any summation order is exact."""
+    announce("exact-int", name, case)
+    n, c, h, w, m, k, pad = case
+    I = wl.small_integers(31, n * c * h * w, 0, 8).reshape(n, c, h, w)
+    K = wl.small_integers(32, m * c * k * k, -4, 4).reshape(m, c, k, k)
+    ref, _ = oracle.mcmk(I, K, pad)
+    got = run_variant(variant, I, K, pad)
+    np.testing.assert_array_equal(got.astype(np.float64), ref)
+
+
+@pytest.mark.parametrize("name,variant", ALL)
+def test_delta_kernels_shift_without_row_wrap(name, variant):
+    """A single tap copies the input displaced by the tap's offset; values leaving a row are dropped
+    (section III-A), including at tile borders."""
+    c, h, w, k, pad = 2, 30, 17, 3, 1
+    I = wl.uniform(77, c * h * w, -1, 1).reshape(1, c, h, w)
+    K = np.zeros((k * k, c, k, k), dtype=np.float32)
+    for i in range(k):
+        for j in range(k):
+            K[i * k + j, 1, i, j] = 1.0          # kernel t is the delta at tap t on channel 1
+    announce("delta", name)
+    got = run_variant(variant, I, K, pad)
+    for i in range(k):
+        for j in range(k):
+            want = np.zeros((h, w), dtype=np.float32)
+            di, dj = i - pad, j - pad
+            q0, q1 = max(0, -di), min(h, h - di)
+            p0, p1 = max(0, -dj), min(w, w - dj)
+            want[q0:q1, p0:p1] = I[0, 1, q0 + di:q1 + di, p0 + dj:p1 + dj]
+            np.testing.assert_array_equal(got[0, i * k + j], want)
+
+
+def test_zero_terms_give_exact_zero():
+    """Where sum|K||I| is 0 the result must be exactly 0."""
+    announce("zeros")
+    I = np.zeros((1, 4, 16, 16), dtype=np.float32)
+    K = wl.normal(5, 8 * 4 * 9, 1.0).reshape(8, 4, 3, 3)
+    for _, variant in ALL:
+        assert not run_variant(variant, I, K, 1).any()
+
+
+# ------------------------------------------------------------------ stage outputs
+
+def _expected_packing(K, im2col):
+    """The packed-kernel layout documented in conv_mcmk.h, written out with plain loops."""
+    m, c, k, _ = K.shape
+    mb = (m + 15) // 16
+    if im2col:
+        A = K.reshape(1, m, c * k * k)
+    else:
+        A = np.stack([K[:, :, i, j] for i in range(k) for j in range(k)])      # [t][m][c]
+    taps, _, kc = A.shape
+    cg = (kc + 15) // 16
+    out = np.zeros((taps, mb, cg, 64, 4), dtype=np.float32)
+    for t in range(taps):
+        for row in range(m):
+            for col in range(kc):
+                lane = (col % 4) * 16 + row % 16
+                out[t, row // 16, col // 16, lane, (col % 16) // 4] = A[t, row, col]
+    return out
+
+
+@pytest.mark.parametrize("variant", [B.KN2ROW, B.KN2ROW_2PASS, B.IM2COL])
+def test_prepack_layout(variant):
+    import torch
+    m, c, k = 35, 21, 3
+    announce("prepack", variant)
+    K = wl.normal(9, m * c * k * k, 1.0).reshape(m, c, k, k)
+    d = B.desc(1, c, 8, 8, m, k, 1)
+    nbytes = B.conv_mcmk_packed_kernel_bytes(d, variant)
+    Kp = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device="cuda")
+    B.conv_mcmk_prepack(d, variant, torch.from_numpy(K).cuda(), Kp)
+    torch.cuda.synchronize()
+    got = Kp.view(torch.float32).cpu().numpy()
+    want = _expected_packing(K, variant == B.IM2COL).reshape(-1)
+    assert got.size == want.size
+    np.testing.assert_array_equal(got, want)
+
+
+def test_two_pass_workspace_holds_the_gemm_result():
+    """After the two-pass call the workspace is the [k*k*M] x [H*W] product of section III-A."""
+    case = (2, 12, 13, 11, 21, 3, 1)
+    announce("2pass-workspace", case)
+    n, c, h, w, m, k, pad = case
+    I, K = _inputs(case, 4242)
+    O, ws = run_variant(B.KN2ROW_2PASS, I, K, pad, return_ws=True)
+    T = ws.view(np.float32).reshape(n, k * k * m, h * w)
+    for i in range(n):
+        ref = steps.kn2row_gemm(I[i], K)
+        absref = steps.kn2row_gemm(np.abs(I[i]), np.abs(K))
+        assert_within_bound(T[i], ref, absref, TOL_F32, "kn2row GEMM result")
+        # and the post pass applied to the library's own product gives the library's output
+        again = steps.shift_add(T[i], m, h, w, k, pad)
+        assert np.all(np.abs(again - O[i]) <= 1e-6 * steps.shift_add(np.abs(T[i]), m, h, w, k, pad) + 1e-30)
+
+
+def test_im2col_workspace_holds_the_patch_matrix():
+    case = (2, 6, 9, 13, 10, 3, 1)
+    announce("im2col-workspace", case)
+    n, c, h, w, m, k, pad = case
+    I, K = _inputs(case, 4343)
+    _, ws = run_variant(B.IM2COL, I, K, pad, return_ws=True)
+    cols = ws.view(np.float32).reshape(n, c * k * k, h * w)
+    for i in range(n):
+        np.testing.assert_array_equal(cols[i], steps.input_patch_matrix(I[i], k, pad).astype(np.float32))
+
+
+def test_cvt_f32_bf16_bit_exact():
+    import torch
+    announce("cvt")
+    x = np.concatenate([wl.normal(1, 100000, 1.0), wl.uniform(2, 1000, -1e-30, 1e-30),
+                        np.array([0.0, -0.0, np.inf, -np.inf, np.nan, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8,
+                                  3.3e38, 3.4e38, 1e-45], dtype=np.float32)]).astype(np.float32)
+    src = torch.from_numpy(x).cuda()
+    dst = torch.zeros(x.size, dtype=torch.int16, device="cuda")
+    B.conv_mcmk_cvt_f32_bf16(src, dst)
+    torch.cuda.synchronize()
+    got = dst.cpu().numpy().view(np.uint16)
+    np.testing.assert_array_equal(got, steps.round_to_bf16_bits(x))
+
+
+def test_repeat_calls_are_bitwise_identical():
+    """No atomics, no races: the same call twice gives the same bits."""
+    case = (2, 40, 28, 28, 48, 3, 1)
+    announce("repeat", case)
+    I, K = _inputs(case, 555)
+    a = run_variant(B.KN2ROW, I, K, 1)
+    b = run_variant(B.KN2ROW, I, K, 1)
+    np.testing.assert_array_equal(a, b)
+
+
+def test_runtime_errors_through_binding():
+    import torch
+    announce("errors")
+    d = B.desc(1, 4, 8, 8, 4, 3, 1)
+    I = torch.zeros(4 * 64, device="cuda")
+    K = torch.zeros(4 * 4 * 9, device="cuda")
+    O = torch.zeros(4 * 64, device="cuda")
+    with pytest.raises(B.ConvMcmkError) as e:
+        B.conv_mcmk_im2col(d, I, K, O, None)
+    assert e.value.code == B.ERR_WORKSPACE
+    with pytest.raises(B.ConvMcmkError) as e:
+        B.conv_mcmk_kn2row(B.desc(1, 4, 8, 8, 4, 3, 1, stride=2), I, K, O)
+    assert e.value.code == B.ERR_UNSUPPORTED
+    with pytest.raises(B.ConvMcmkError) as e:
+        B.conv_mcmk_kn2row(d, I[1:], K, O)
+    assert e.value.code == B.ERR_ALIGN
