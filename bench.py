@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the kn2row MCMK convolution on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-table] [--no-cpu]
+
+A step is one call of conv_mcmk_kn2row (the 1x1 GEMMs of all k*k taps with the shift-add fused,
+paper section III-A) on one batch of synthetic input that is already resident in HBM; the kernel
+re-ordering is done once before timing, as the paper prescribes.  Prints ONE JSON line: conv
+GFLOP/s (2 M C k^2 P Q N per call), the roofline of the kernel, the CPU oracle timed on the host's
+cores, and -- outside the timed steps -- the same layer through the im2col, two-pass kn2row and
+direct variants plus the other benchmark layers, so the kn2row : im2col time and memory ratios are
+reported per configuration.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_F32_MFMA_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
+PEAK_HBM_GBS = 8000.0
+DEFAULT_WORKLOAD = "cfg5a_vgg_deep56"
+
+# HBM bytes per launch of the fused kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE
+# scaled by a copy kernel of known size); filled in from the committed summaries, None = not measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def time_calls(fn, steps, warmup):
+    """Wall-clock around `steps` back-to-back calls (synchronised both sides) and the average
+    device time per call from HIP events recorded on the launch stream."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    start.record()
+    for _ in range(steps):
+        fn()
+    stop.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return wall_ms / steps, start.elapsed_time(stop) / steps
+
+
+def bench_layer(L, variants, steps, warmup, I_dev=None, K_dev=None):
+    import torch
+    from paper_1704_04428_amd import binding as B
+    from paper_1704_04428_amd import workloads as wl
+    dev = torch.device("cuda:0")
+    if I_dev is None:
+        I_dev = torch.from_numpy(wl.make_input(L)).to(dev)
+        K_dev = torch.from_numpy(wl.make_kernel(L)).to(dev)
+    d = B.desc(L.n, L.c, L.h, L.w, L.m, L.k, L.pad)
+    out = {}
+    for name in variants:
+        variant = B.VARIANTS[name]
+        plan = B.Plan(d, variant, K_dev)
+        torch.cuda.synchronize()
+        wall_ms, dev_ms = time_calls(lambda: plan.run(I_dev), steps, warmup)
+        out[name] = {
+            "ms": round(dev_ms, 5),
+            "gflops": round(L.flops / (dev_ms * 1e-3) / 1e9, 1),
+            "workspace_bytes": B.conv_mcmk_workspace_bytes(d, variant),
+        }
+        del plan
+    return out
+
+
+def cpu_baseline(L, I, K, budget_s=12.0, max_passes=40):
+    """The oracle as it stands, timed on the host cores: whole passes over the workload until about
+    `budget_s` seconds of CPU work have been spent."""
+    import oracle
+    passes, t0 = 0, time.perf_counter()
+    while True:
+        oracle.mcmk(I, K, L.pad)
+        passes += 1
+        dt = time.perf_counter() - t0
+        if dt >= budget_s or passes >= max_passes:
+            break
+    cores = int(os.environ.get("OMP_NUM_THREADS", "0")) or len(os.sched_getaffinity(0))
+    return {"value": round(passes * L.flops / dt / 1e9, 3), "unit": "GFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": f"{passes} pass(es) over the whole {L.name} batch ({L.flops / 1e9:.2f} GFLOP each, "
+                      f"fp64 direct loop nest, OpenMP), {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
+    ap.add_argument("--no-table", action="store_true", help="skip the other variants and layers")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--probe-copy", action="store_true",
+                    help="also run a 256 MiB device copy a few times (known HBM traffic, for scaling "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (one process, one MI355X); use --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_1704_04428_amd import binding as B
+    from paper_1704_04428_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    B.lib()
+    L = wl.LAYERS[args.workload]
+    dev = torch.device("cuda:0")
+    I, K = wl.make_input(L), wl.make_kernel(L)
+    I_dev, K_dev = torch.from_numpy(I).to(dev), torch.from_numpy(K).to(dev)
+    d = B.desc(L.n, L.c, L.h, L.w, L.m, L.k, L.pad)
+    plan = B.Plan(d, B.KN2ROW, K_dev)          # re-orders the kernel once, outside the timed region
+    torch.cuda.synchronize()
+
+    if args.probe_copy:
+        src = torch.ones(64 << 20, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    wall_ms, dev_ms = time_calls(lambda: plan.run(I_dev), args.steps, args.warmup)
+    gflops = L.flops / (wall_ms * 1e-3) / 1e9
+    achieved_tflops = L.flops / (dev_ms * 1e-3) / 1e12
+
+    # sanity: the timed output against the oracle on sampled points
+    pts = wl.sample_points(L, 512)
+    got = plan.out.cpu().numpy()[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]].astype(np.float64)
+    import oracle
+    ref, absref = oracle.mcmk_at(I, K, L.pad, pts)
+    worst = float(np.max(np.abs(got - ref) / np.maximum(absref, 1e-30)))
+    if not worst <= 1e-4:
+        sys.exit(f"bench.py: output fails parity (worst error {worst:.3e} of sum|K||I|)")
+
+    result = {
+        "metric": "conv GFLOP/s (2*M*C*k^2*P*Q*N / time), kn2row",
+        "value": round(gflops, 1),
+        "unit": "GFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(wall_ms, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": L.name, "n": L.n, "c": L.c, "h": L.h, "w": L.w, "m": L.m, "k": L.k,
+                   "pad": L.pad, "variant": "kn2row (fused shift-add)", "flops_per_step": L.flops},
+        "roofline": {"bound": "mfma", "achieved": round(achieved_tflops, 3), "peak": PEAK_F32_MFMA_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_F32_MFMA_TFLOPS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(L.name), "kernel_ms": round(dev_ms, 5)},
+        "parity_worst_err_over_bound_norm": worst,
+    }
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(L, I, K)
+    if not args.no_table:
+        table = {}
+        for name, layer in wl.LAYERS.items():
+            variants = ["kn2row", "im2col", "kn2row_2pass"] + (["direct"] if layer.flops < 5e9 else [])
+            steps = 50 if layer.flops > 1e9 else 200
+            same = name == L.name
+            table[name] = bench_layer(layer, variants, steps, 5, I_dev if same else None, K_dev if same else None)
+            r = table[name]
+            r["kn2row_over_im2col_time"] = round(r["kn2row"]["ms"] / r["im2col"]["ms"], 4)
+            r["frac_f32_mfma_peak"] = round(r["kn2row"]["gflops"] / 1e3 / PEAK_F32_MFMA_TFLOPS, 4)
+            log(name, json.dumps(r))
+        result["table"] = table
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()
