@@ -102,7 +102,7 @@ def main():
     ap.add_argument("--no-table", action="store_true", help="skip the other variants and layers")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--probe-copy", action="store_true",
-                    help="also run a 256 MiB device copy a few times (known HBM traffic, for scaling "
+                    help="also run a 256 MiB elementwise copy kernel (dst = src + 1) a few times (known HBM traffic, for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -128,7 +128,7 @@ def main():
         src = torch.ones(64 << 20, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
         for _ in range(5):
-            dst.copy_(src)
+            torch.add(src, 1.0, out=dst)     # reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
         del src, dst
 

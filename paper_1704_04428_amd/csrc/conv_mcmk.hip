@@ -26,6 +26,8 @@ int validate(const conv_mcmk_desc *d, int variant, Dims *out)
     const long long q = (long long)d->h + 2LL * d->pad - d->k + 1;
     const long long p = (long long)d->w + 2LL * d->pad - d->k + 1;
     if (q < 1 || p < 1) return CONV_MCMK_ERR_SHAPE;
+    // the tile kernel addresses one image through a 32-bit byte offset with 2 GiB kept free
+    if (((long long)d->c + 32) * d->h * d->w >= (1LL << 29)) return CONV_MCMK_ERR_SHAPE;
     const long long lim = 1LL << 31;
     const long long kk = (long long)d->k * d->k;
     if ((long long)d->c * d->h * d->w >= lim || (long long)d->m * q * p >= lim ||

@@ -27,6 +27,8 @@ namespace mcmk {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+constexpr int kXcds = 8;   // accelerator complex dies on MI355X
+
 struct TileArgs {
     const float *in;      // [n][c][h][w]
     const float *apk;     // packed A: [taps][mb_per_tap][cg][64][4]
@@ -79,8 +81,15 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a
     const int wm = wave % WM;
     const int wp = wave / WM;
 
-    // ---- which tile
+    // ---- which tile.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2), so
+    // the launch index is re-mapped to give every XCD a contiguous run of tiles: the row tiles that
+    // share one input tile, and spatially adjacent tiles that share halo columns and output cache
+    // lines, then meet in the same L2.
     int bid = blockIdx.x;
+    {
+        const int per_xcd = gridDim.x / kXcds;
+        if (bid < per_xcd * kXcds) bid = (bid % kXcds) * per_xcd + bid / kXcds;
+    }
     const int rt = bid % a.row_tiles;  bid /= a.row_tiles;
     const int tx = bid % a.tiles_x;    bid /= a.tiles_x;
     const int ty = bid % a.tiles_y;    bid /= a.tiles_y;
@@ -94,12 +103,18 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a
     const int grp = rb / a.mb_per_group;         // row group (tap index when rows are (tap, m))
     const int mbi = rb % a.mb_per_group;
 
-    // ---- staging plan: element e = tid + s*NT of the [CC][POS] halo tile
+    // ---- staging plan: element e = tid + s*NT of the [CC][POS] halo tile.
+    // The image is read through a raw buffer descriptor whose range check returns 0 for any offset
+    // at or beyond its size: positions outside the image get an offset of 2 GiB (never valid, and
+    // adding a chunk's channel offset cannot wrap it), channels beyond C fall off the end by
+    // themselves.  No branch and no select sits between a load and its use.
     const size_t plane = (size_t)a.h * a.w;
     const float *in_img = a.in + (size_t)img * a.c * plane;
-    int g_off[SLOTS];      // offset inside one channel plane, or -1 when outside the image
+    const __amdgpu_buffer_rsrc_t in_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(in_img), 0, (int)((size_t)a.c * plane * sizeof(float)), 0x00020000);
+    const uint32_t chunk_bytes = (uint32_t)(CC * plane * sizeof(float));
+    uint32_t g_off[SLOTS]; // byte offset of the element in chunk 0, or 2 GiB when outside the image
     int l_off[SLOTS];      // word offset inside an LDS buffer, or -1 when the slot is unused
-    int s_ch[SLOTS];       // channel inside the chunk
 #pragma unroll
     for (int s = 0; s < SLOTS; ++s) {
         const int e = tid + s * NT;
@@ -108,20 +123,16 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a
         const int gy = y0 - a.pad + r, gx = x0 - a.pad + col;
         const bool used = e < CC * POS;
         const bool inside = used && gy >= 0 && gy < a.h && gx >= 0 && gx < a.w;
-        g_off[s] = inside ? gy * a.w + gx : -1;
+        g_off[s] = inside ? (uint32_t)((cl * plane + (size_t)gy * a.w + gx) * sizeof(float)) : 0x80000000u;
         l_off[s] = used ? cl * CHS + r * WT + col : -1;
-        s_ch[s] = cl;
     }
 
     float stage[SLOTS];
     auto load_chunk = [&](int chunk) {
 #pragma unroll
-        for (int s = 0; s < SLOTS; ++s) {
-            const int ch = chunk * CC + s_ch[s];
-            float v = 0.0f;
-            if (g_off[s] >= 0 && ch < a.c) v = in_img[(size_t)ch * plane + g_off[s]];
-            stage[s] = v;
-        }
+        for (int s = 0; s < SLOTS; ++s)
+            stage[s] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                in_rsrc, (int)(g_off[s] + (uint32_t)chunk * chunk_bytes), 0, 0));
     };
     auto store_chunk = [&](float *buf) {
 #pragma unroll
@@ -163,7 +174,7 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a
 
     // One chunk of matrix-core work for NB position blocks (NB is PBW, or PBW-1 for the wave that
     // owns the ragged last share); straight-line code, every LDS offset an immediate.
-    auto compute_chunk = [&](auto nb_tag, int chunk, bool more) {
+    auto compute_chunk = [&](auto nb_tag, int chunk, int next_chunk) {
         constexpr int NB = decltype(nb_tag)::value;
         constexpr int STEPS = KS * 4;              // per tap row: (column tap j, channel quad v)
         const float *bsrc = lds + (chunk & 1) * BUF;
@@ -176,7 +187,7 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a
 #pragma unroll
             for (int j = 0; j < KS; ++j) a_cur[j] = a_next[j];
             if (i + 1 < KS) load_a_row(chunk, i + 1, a_next);
-            else if (more) load_a_row(chunk + 1, 0, a_next);
+            else load_a_row(next_chunk, 0, a_next);
 #pragma unroll
             for (int s = 0; s < STEPS; ++s) {
                 const int j = s / 4, v = s % 4;
@@ -205,13 +216,16 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a
         }
     };
 
+    // The loop body has no data-dependent branch around its loads: the prefetches for "the next
+    // chunk" are issued in the last iteration too (A from the last chunk again, input from beyond
+    // the last channel, which the buffer range check turns into zeros) and simply go unused.
     const int nchunks = a.cg;
     for (int chunk = 0; chunk < nchunks; ++chunk) {
-        const bool more = chunk + 1 < nchunks;
-        if (more) load_chunk(chunk + 1);
-        if (kRagged && nb_wave != PBW) compute_chunk(std::integral_constant<int, kRagged ? PBW - 1 : PBW>{}, chunk, more);
-        else compute_chunk(std::integral_constant<int, PBW>{}, chunk, more);
-        if (more) store_chunk(lds + ((chunk + 1) & 1) * BUF);
+        const int next_chunk = min(chunk + 1, nchunks - 1);
+        load_chunk(chunk + 1);
+        if (kRagged && nb_wave != PBW) compute_chunk(std::integral_constant<int, kRagged ? PBW - 1 : PBW>{}, chunk, next_chunk);
+        else compute_chunk(std::integral_constant<int, PBW>{}, chunk, next_chunk);
+        store_chunk(lds + ((chunk + 1) & 1) * BUF);
         __syncthreads();
     }
 
