@@ -121,6 +121,17 @@ __global__ void direct_f32_kernel(const float *__restrict__ I, const float *__re
 }
 
 // ---------------------------------------------------------------------------------------------
+// Zero `count` floats (count a multiple of 4 is not required; dst 16-byte aligned).
+__global__ void fill_zero_kernel(float *__restrict__ dst, size_t count)
+{
+    const size_t vec = count / 4;
+    float4 *d4 = reinterpret_cast<float4 *>(dst);
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < vec; e += (size_t)gridDim.x * blockDim.x)
+        d4[e] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (blockIdx.x == 0 && threadIdx.x < count - vec * 4) dst[vec * 4 + threadIdx.x] = 0.f;
+}
+
+// ---------------------------------------------------------------------------------------------
 // float -> bfloat16, round to nearest even; NaN stays a quiet NaN.
 __device__ inline uint16_t f32_to_bf16_rne(float f)
 {

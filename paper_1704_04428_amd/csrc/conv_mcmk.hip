@@ -3,6 +3,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
+
 #include "aux_kernels.h"
 #include "kn2row_tile.h"
 
@@ -76,15 +78,14 @@ int grid_for(size_t total, int block)
 
 // ------------------------------------------------------------------------------------------
 // Tile-shape menu for the fused kernel and the cost estimate that picks from it.
-// cost = matrix-core block-steps on the busiest SIMD: workgroups per CU (ceil) x waves per SIMD x
-// blocks per wave.  Ties go to the larger row tile (fewer re-reads of the input tile).
 struct Candidate {
-    int th, tw, wm, wp;
+    int th, tw, wm, wp, csplit;
 };
 
 template <int KS, int TH, int TW, int WM, int WP>
 int launch_tile(const conv_mcmk_desc *d, const Dims &dm, const float *in, const float *apk, float *out,
-                int in_c, int in_h, int in_w, int out_q, int out_p, int pad, int row_groups, hipStream_t st)
+                int in_c, int in_h, int in_w, int out_q, int out_p, int pad, int row_groups, int csplit,
+                hipStream_t st)
 {
     using S = TileShape<KS, TH, TW, WM, WP>;
     TileArgs a;
@@ -96,39 +97,85 @@ int launch_tile(const conv_mcmk_desc *d, const Dims &dm, const float *in, const 
     a.tiles_x = ceil_div(out_p, TW);
     a.tiles_y = ceil_div(out_q, TH);
     a.row_tiles = ceil_div((long long)row_groups * dm.mb, WM);
-    const long long blocks = (long long)a.n * a.tiles_x * a.tiles_y * a.row_tiles;
+    a.csplit = csplit;
+    const long long blocks = (long long)a.n * a.tiles_x * a.tiles_y * a.row_tiles * csplit;
     if (blocks < 1 || blocks >= (1LL << 31)) return CONV_MCMK_ERR_SHAPE;
+    if (csplit > 1) {
+        // partial sums are added into the output, so it starts from zero (a fill kernel, not a
+        // memset node, so the call can be captured into a graph)
+        const size_t total = (size_t)a.n * row_groups * d->m * out_q * out_p;
+        hipLaunchKernelGGL(fill_zero_kernel, dim3(grid_for(total / 4 + 1, 256)), dim3(256), 0, st, out, total);
+        if (int rc = launch_status()) return rc;
+    }
     hipLaunchKernelGGL((kn2row_tile_f32<KS, TH, TW, WM, WP>), dim3((unsigned)blocks), dim3(S::kThreads),
                        S::kLdsBytes, st, a);
     return launch_status();
 }
 
-long long tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c)
+// Estimated run time of a candidate in microseconds; the constants were fitted to measurements of
+// every candidate on the benchmark layers.
+//   - a block-step is one 16x16x4 MFMA, 32 cycles of a SIMD's matrix pipe (13.9 ns at 2.3 GHz);
+//   - a workgroup's waves are dealt round-robin to the 4 SIMDs, its time is that of the SIMD with
+//     the most position blocks; the busiest CU runs ceil(workgroups / 256) of them;
+//   - a SIMD with a single resident wave cannot hide LDS and global latency (70 % pipe use
+//     against 90 % with two or more);
+//   - each launch pays a fixed prologue / epilogue; the channel split pays a zero fill plus two
+//     device-scope atomic adds per output element.
+double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, int ks)
 {
-    const long long wgs = (long long)d->n * ceil_div(dm.p, c.tw) * ceil_div(dm.q, c.th) * ceil_div(dm.mb, c.wm);
+    const long long tiles = (long long)d->n * ceil_div(dm.p, c.tw) * ceil_div(dm.q, c.th) * ceil_div(dm.mb, c.wm);
+    const long long wgs = tiles * c.csplit;
     const int npb = ceil_div(c.th * c.tw, 16);
-    const int pbw = ceil_div(npb, c.wp);
-    const int waves_per_simd = ceil_div(c.wm * c.wp, 4);
-    return ((wgs + kNumCU - 1) / kNumCU) * waves_per_simd * pbw;
+    const int waves = c.wm * c.wp;
+    int simd_blocks[4] = {0, 0, 0, 0};
+    for (int w = 0; w < waves; ++w) {
+        const int wp = w / c.wm;
+        const int rem = npb % c.wp, pbw = ceil_div(npb, c.wp);
+        simd_blocks[w % 4] += (rem == 0 || wp < rem) ? pbw : pbw - 1;
+    }
+    int simd_load = 0;
+    for (int i = 0; i < 4; ++i) simd_load = simd_blocks[i] > simd_load ? simd_blocks[i] : simd_load;
+    const int chunks = ceil_div(ceil_div(d->c, 16), c.csplit);
+    const double steps = (double)chunks * ks * ks * 4;
+    const long long per_cu = (wgs + kNumCU - 1) / kNumCU;
+    const int can_hold = 16 / waves;                                   // workgroups a CU can hold
+    const long long held = per_cu < can_hold ? per_cu : can_hold;
+    const double waves_per_simd = (double)held * waves / 4.0;
+    const double pipe_use = waves_per_simd >= 2.0 ? 0.9 : 0.7;
+    double us = (double)per_cu * simd_load * steps * 0.0139 / pipe_use + 6.0;
+    if (c.csplit > 1) us += 3.0 + 2.0 * (double)d->n * d->m * dm.q * dm.p * 6.25e-6;
+    return us;
 }
 
 template <int KS>
 int launch_fused(const conv_mcmk_desc *d, const Dims &dm, const float *in, const float *apk, float *out,
                  hipStream_t st)
 {
-    static const Candidate menu[] = {{14, 14, 4, 2}, {16, 16, 4, 2}, {14, 14, 1, 4}, {16, 16, 1, 4}};
+    static const Candidate menu[] = {
+        {14, 14, 4, 2, 1}, {14, 14, 2, 4, 1}, {14, 14, 1, 4, 1}, {16, 16, 4, 2, 1}, {16, 16, 2, 4, 1}, {16, 16, 1, 4, 1},
+        {14, 14, 4, 2, 2}, {14, 14, 2, 4, 2}, {14, 14, 1, 4, 2}, {16, 16, 4, 2, 2}, {16, 16, 2, 4, 2}, {16, 16, 1, 4, 2},
+    };
+    constexpr int kMenu = sizeof(menu) / sizeof(menu[0]);
     int best = 0;
-    long long best_cost = -1;
-    for (int i = 0; i < 4; ++i) {
-        const long long c = tile_cost(d, dm, menu[i]);
+    double best_cost = -1.0;
+    for (int i = 0; i < kMenu; ++i) {
+        const double c = tile_cost(d, dm, menu[i], KS);
         if (best_cost < 0 || c < best_cost) { best_cost = c; best = i; }
     }
+    // tuning aid: CONV_MCMK_TILE=<menu index> overrides the choice
+    if (const char *force = getenv("CONV_MCMK_TILE")) {
+        const int i = atoi(force);
+        if (i >= 0 && i < kMenu) best = i;
+    }
+    const int cs = menu[best].csplit;
 #define MCMK_GO(TH, TW, WM, WP) \
-    return launch_tile<KS, TH, TW, WM, WP>(d, dm, in, apk, out, d->c, d->h, d->w, dm.q, dm.p, d->pad, 1, st)
-    switch (best) {
+    return launch_tile<KS, TH, TW, WM, WP>(d, dm, in, apk, out, d->c, d->h, d->w, dm.q, dm.p, d->pad, 1, cs, st)
+    switch (best % 6) {
     case 0: MCMK_GO(14, 14, 4, 2);
-    case 1: MCMK_GO(16, 16, 4, 2);
+    case 1: MCMK_GO(14, 14, 2, 4);
     case 2: MCMK_GO(14, 14, 1, 4);
+    case 3: MCMK_GO(16, 16, 4, 2);
+    case 4: MCMK_GO(16, 16, 2, 4);
     default: MCMK_GO(16, 16, 1, 4);
     }
 #undef MCMK_GO
@@ -140,7 +187,7 @@ int launch_gemm(const conv_mcmk_desc *d, const Dims &dm, const float *bmat, cons
                 int kc, long long cols, int row_groups, hipStream_t st)
 {
     if (cols >= (1LL << 31)) return CONV_MCMK_ERR_SHAPE;
-    return launch_tile<1, 1, 256, 4, 2>(d, dm, bmat, apk, cmat, kc, 1, (int)cols, 1, (int)cols, 0, row_groups, st);
+    return launch_tile<1, 1, 256, 4, 2>(d, dm, bmat, apk, cmat, kc, 1, (int)cols, 1, (int)cols, 0, row_groups, 1, st);
 }
 
 int common_ptr_checks(const void *I, const void *K, const void *O)

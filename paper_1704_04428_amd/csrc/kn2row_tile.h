@@ -42,6 +42,8 @@ struct TileArgs {
     int cg;               // 16-channel groups (= ceil(c/16)) == number of chunks
     int tiles_x, tiles_y; // spatial tiles per image
     int row_tiles;        // ceil(row_groups*mb_per_group / WM)
+    int csplit;           // 1, or 2: two workgroups share a tile, each takes half the chunks and
+                          // adds its partial sums into a zeroed output (a + b is order-independent)
 };
 
 template <int KS, int TH, int TW, int WM, int WP>
@@ -90,6 +92,7 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a
         const int per_xcd = gridDim.x / kXcds;
         if (bid < per_xcd * kXcds) bid = (bid % kXcds) * per_xcd + bid / kXcds;
     }
+    const int part = bid % a.csplit;   bid /= a.csplit;
     const int rt = bid % a.row_tiles;  bid /= a.row_tiles;
     const int tx = bid % a.tiles_x;    bid /= a.tiles_x;
     const int ty = bid % a.tiles_y;    bid /= a.tiles_y;
@@ -113,10 +116,15 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a
     const __amdgpu_buffer_rsrc_t in_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(in_img), 0, (int)((size_t)a.c * plane * sizeof(float)), 0x00020000);
     const uint32_t chunk_bytes = (uint32_t)(CC * plane * sizeof(float));
-    uint32_t g_off[SLOTS]; // byte offset of the element in chunk 0, or 2 GiB when outside the image
-    int l_off[SLOTS];      // word offset inside an LDS buffer, or -1 when the slot is unused
+    // When the thread count is a multiple of the positions per channel every thread keeps one
+    // position and walks the channels in steps of NT/POS: one offset pair serves all its slots.
+    constexpr bool kRegular = (NT % POS) == 0;
+    constexpr int NOFF = kRegular ? 1 : SLOTS;
+    constexpr int CSTEP = kRegular ? NT / POS : 0;
+    uint32_t g_off[NOFF];  // byte offset of the element in chunk 0, or 2 GiB when outside the image
+    int l_off[NOFF];       // word offset inside an LDS buffer, or -1 when the slot is unused
 #pragma unroll
-    for (int s = 0; s < SLOTS; ++s) {
+    for (int s = 0; s < NOFF; ++s) {
         const int e = tid + s * NT;
         const int cl = e / POS, pos = e % POS;
         const int r = pos / WT, col = pos % WT;
@@ -126,18 +134,24 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a
         g_off[s] = inside ? (uint32_t)((cl * plane + (size_t)gy * a.w + gx) * sizeof(float)) : 0x80000000u;
         l_off[s] = used ? cl * CHS + r * WT + col : -1;
     }
+    static_assert(!kRegular || SLOTS * CSTEP == CC, "regular staging must cover the chunk exactly");
 
     float stage[SLOTS];
     auto load_chunk = [&](int chunk) {
 #pragma unroll
-        for (int s = 0; s < SLOTS; ++s)
+        for (int s = 0; s < SLOTS; ++s) {
+            const uint32_t off = kRegular ? g_off[0] + (uint32_t)(s * CSTEP) * (uint32_t)(plane * sizeof(float))
+                                          : g_off[kRegular ? 0 : s];
             stage[s] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                in_rsrc, (int)(g_off[s] + (uint32_t)chunk * chunk_bytes), 0, 0));
+                in_rsrc, (int)(off + (uint32_t)chunk * chunk_bytes), 0, 0));
+        }
     };
     auto store_chunk = [&](float *buf) {
 #pragma unroll
-        for (int s = 0; s < SLOTS; ++s)
-            if (l_off[s] >= 0) buf[l_off[s]] = stage[s];
+        for (int s = 0; s < SLOTS; ++s) {
+            if (kRegular) buf[l_off[0] + s * CSTEP * CHS] = stage[s];
+            else if (l_off[kRegular ? 0 : s] >= 0) buf[l_off[kRegular ? 0 : s]] = stage[s];
+        }
     };
 
     // ---- per-lane LDS offsets of this wave's output positions (B operand: k = lane/16, col = lane%16)
@@ -151,60 +165,62 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a
         b_off[b] = (lane >> 4) * CHS + (pp / TW) * WT + (pp % TW);
     }
 
-    // ---- A fragments: one f32x4 per lane per tap covers a 16-channel chunk
+    // ---- A fragments: one f32x4 per lane per tap covers a 16-channel chunk.  They are fetched
+    // straight from global memory kDepth taps ahead of use and handed down a short register queue.
+    constexpr int T = KS * KS;                   // taps per chunk
+    constexpr int kDepth = 2;
+    const int nchunks = a.cg;
+    const int chunk_lo = (int)((long long)nchunks * part / a.csplit);
+    const int chunk_hi = (int)((long long)nchunks * (part + 1) / a.csplit);
     const f32x4 *apk = reinterpret_cast<const f32x4 *>(a.apk);
-    auto load_a_row = [&](int chunk, int i, f32x4 (&dst)[KS]) {
-#pragma unroll
-        for (int j = 0; j < KS; ++j) {
-            // conv: tap planes are [tap][mb][cg]; row-group GEMM: KS == 1 and grp picks the plane
-            const size_t tap = (size_t)(i * KS + j) + grp;
-            dst[j] = apk[((tap * a.mb_per_group + mbi) * a.cg + chunk) * 64 + lane];
-        }
+    auto load_a = [&](int chunk, int t) {
+        // conv: tap planes are [tap][mb][cg]; row-group GEMM: KS == 1 and grp picks the plane
+        const size_t tap = (size_t)t + grp;
+        return apk[((tap * a.mb_per_group + mbi) * a.cg + min(chunk, nchunks - 1)) * 64 + lane];
     };
 
     f32x4 acc[PBW];
 #pragma unroll
     for (int b = 0; b < PBW; ++b) acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    f32x4 a_next[KS];
-    load_chunk(0);
-    load_a_row(0, 0, a_next);
-    store_chunk(lds);
+    f32x4 a_queue[kDepth];
+    load_chunk(chunk_lo);
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) a_queue[d] = load_a(chunk_lo + d / T, d % T);
+    store_chunk(lds + (chunk_lo & 1) * BUF);
     __syncthreads();
 
     // One chunk of matrix-core work for NB position blocks (NB is PBW, or PBW-1 for the wave that
     // owns the ragged last share); straight-line code, every LDS offset an immediate.
-    auto compute_chunk = [&](auto nb_tag, int chunk, int next_chunk) {
+    auto compute_chunk = [&](auto nb_tag, int chunk) {
         constexpr int NB = decltype(nb_tag)::value;
-        constexpr int STEPS = KS * 4;              // per tap row: (column tap j, channel quad v)
+        constexpr int G = T * 4;                   // steps per chunk: (tap, channel quad)
         const float *bsrc = lds + (chunk & 1) * BUF;
         float bq[2][NB];                           // B fragments: this step's and the next one's
 #pragma unroll
         for (int b = 0; b < NB; ++b) bq[0][b] = bsrc[b_off[b]];
 #pragma unroll
-        for (int i = 0; i < KS; ++i) {
-            f32x4 a_cur[KS];
+        for (int t = 0; t < T; ++t) {
+            const f32x4 a_cur = a_queue[0];
 #pragma unroll
-            for (int j = 0; j < KS; ++j) a_cur[j] = a_next[j];
-            if (i + 1 < KS) load_a_row(chunk, i + 1, a_next);
-            else load_a_row(next_chunk, 0, a_next);
+            for (int d = 0; d + 1 < kDepth; ++d) a_queue[d] = a_queue[d + 1];
+            a_queue[kDepth - 1] = load_a(chunk + (t + kDepth) / T, (t + kDepth) % T);
 #pragma unroll
-            for (int s = 0; s < STEPS; ++s) {
-                const int j = s / 4, v = s % 4;
-                const int g = i * STEPS + s;       // step number inside the chunk
+            for (int v = 0; v < 4; ++v) {
+                const int g = t * 4 + v;           // step number inside the chunk
                 // fetch the next step's fragments while this step's products run
-                const int s1 = (s + 1) % STEPS, i1 = (s + 1 < STEPS) ? i : i + 1;
-                if (i1 < KS) {
+                const int t1 = (g + 1) / 4, v1 = (g + 1) % 4;
+                if (g + 1 < G) {
 #pragma unroll
                     for (int b = 0; b < NB; ++b)
-                        bq[(g + 1) & 1][b] = bsrc[b_off[b] + (4 * (s1 % 4)) * CHS + i1 * WT + s1 / 4];
+                        bq[(g + 1) & 1][b] = bsrc[b_off[b] + (4 * v1) * CHS + (t1 / KS) * WT + (t1 % KS)];
                 }
 #pragma unroll
                 for (int b = 0; b < NB; ++b)
-                    acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[j][v], bq[g & 1][b], acc[b], 0, 0, 0);
-                // keep the steps in program order: reads for step g+1 stay ahead of the products of
-                // step g and never drift further
-                if (i1 < KS) {
+                    acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[v], bq[g & 1][b], acc[b], 0, 0, 0);
+                // pin the order: one LDS read of step g+1 between consecutive products of step g,
+                // and nothing drifts across steps
+                if (g + 1 < G) {
 #pragma unroll
                     for (int b = 0; b < NB; ++b) {
                         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read ...
@@ -219,12 +235,10 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a
     // The loop body has no data-dependent branch around its loads: the prefetches for "the next
     // chunk" are issued in the last iteration too (A from the last chunk again, input from beyond
     // the last channel, which the buffer range check turns into zeros) and simply go unused.
-    const int nchunks = a.cg;
-    for (int chunk = 0; chunk < nchunks; ++chunk) {
-        const int next_chunk = min(chunk + 1, nchunks - 1);
+    for (int chunk = chunk_lo; chunk < chunk_hi; ++chunk) {
         load_chunk(chunk + 1);
-        if (kRagged && nb_wave != PBW) compute_chunk(std::integral_constant<int, kRagged ? PBW - 1 : PBW>{}, chunk, next_chunk);
-        else compute_chunk(std::integral_constant<int, PBW>{}, chunk, next_chunk);
+        if (kRagged && nb_wave != PBW) compute_chunk(std::integral_constant<int, kRagged ? PBW - 1 : PBW>{}, chunk);
+        else compute_chunk(std::integral_constant<int, PBW>{}, chunk);
         store_chunk(lds + ((chunk + 1) & 1) * BUF);
         __syncthreads();
     }
@@ -243,7 +257,10 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int mrow = mbi * 16 + 4 * (lane >> 4) + v;
-            if (mrow < a.m) out_img[(size_t)(grp * a.m + mrow) * oplane + (size_t)y * a.p + x] = acc[b][v];
+            if (mrow >= a.m) continue;
+            float *dst = out_img + (size_t)(grp * a.m + mrow) * oplane + (size_t)y * a.p + x;
+            if (a.csplit == 1) *dst = acc[b][v];
+            else unsafeAtomicAdd(dst, acc[b][v]);      // hardware fp32 add at the L2
         }
     }
 }
