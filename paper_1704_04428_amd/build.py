@@ -1,35 +1,47 @@
-"""Compile the HIP library for gfx950 into paper_1704_04428_amd/libconv_mcmk.so (in-tree)."""
+"""Compile the HIP library for gfx950 into paper_1704_04428_amd/libconv_mcmk.so (in-tree).
+
+Every .hip file under csrc/ is a translation unit; they are compiled in parallel and linked.
+"""
+import concurrent.futures
 import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "csrc", "conv_mcmk.hip")
+CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libconv_mcmk.so")
 
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument",
 ]
+JOBS = 8
+TIMEOUT_S = 900      # per translation unit; a compile that takes longer is a bug, not patience
 
 
-def sources():
-    csrc = os.path.join(HERE, "csrc")
-    inc = os.path.join(os.path.dirname(HERE), "include")
-    out = [os.path.join(csrc, f) for f in sorted(os.listdir(csrc))]
-    out += [os.path.join(inc, f) for f in sorted(os.listdir(inc))]
-    return out
+def units():
+    return sorted(f for f in os.listdir(CSRC) if f.endswith(".hip"))
 
 
-def is_current() -> bool:
-    return os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(s) for s in sources())
+def _compile(name: str) -> str:
+    obj = os.path.join(OBJ, name[:-4] + ".o")
+    cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, name), "-o", obj]
+    subprocess.run(cmd, check=True, timeout=TIMEOUT_S, stdout=subprocess.DEVNULL, stderr=subprocess.PIPE)
+    return obj
 
 
-def build(force: bool = True, extra=()) -> str:
+def build(force: bool = True) -> str:
     if not force and os.path.exists(LIB):
         return LIB
-    cmd = ["hipcc", *FLAGS, *extra, "-o", LIB, SRC]
-    subprocess.run(cmd, check=True)
+    os.makedirs(OBJ, exist_ok=True)
+    try:
+        with concurrent.futures.ThreadPoolExecutor(max_workers=JOBS) as pool:
+            objs = list(pool.map(_compile, units()))
+    except subprocess.CalledProcessError as e:
+        raise RuntimeError("hipcc failed:\n" + e.stderr.decode(errors="replace")[-4000:]) from None
+    subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs],
+                   check=True, timeout=TIMEOUT_S)
     return LIB
 
 

@@ -6,7 +6,7 @@
 #include <cstdlib>
 
 #include "aux_kernels.h"
-#include "kn2row_tile.h"
+#include "tile_dispatch.h"
 
 namespace {
 
@@ -52,7 +52,6 @@ int validate(const conv_mcmk_desc *d, int variant, Dims *out)
     default:
         return CONV_MCMK_ERR_UNSUPPORTED;
     }
-    if (d->dtype == CONV_MCMK_BF16) return CONV_MCMK_ERR_UNSUPPORTED;   // bf16 operands: not built yet
     if (out) {
         out->q = (int)q;
         out->p = (int)p;
@@ -79,27 +78,51 @@ int grid_for(size_t total, int block)
 // ------------------------------------------------------------------------------------------
 // Tile-shape menu for the fused kernel and the cost estimate that picks from it.
 struct Candidate {
-    int th, tw, wm, wp, csplit;
+    int shape;     // index into kTileShapes
+    int csplit;    // 1 or 2
+    int th, tw, wm, wp;
 };
 
-template <int KS, int TH, int TW, int WM, int WP>
-int launch_tile(const conv_mcmk_desc *d, const Dims &dm, const float *in, const float *apk, float *out,
-                int in_c, int in_h, int in_w, int out_q, int out_p, int pad, int row_groups, int csplit,
-                hipStream_t st)
+int run_tile(int dtype, int ks, const TileRequest &rq)
 {
-    using S = TileShape<KS, TH, TW, WM, WP>;
-    TileArgs a;
-    a.in = in;  a.apk = apk;  a.out = out;
+    int rc = 2;
+    if (dtype == CONV_MCMK_F32) {
+        switch (ks) {
+        case 1: rc = run_tile_f32_k1(rq); break;
+        case 3: rc = run_tile_f32_k3(rq); break;
+        case 5: rc = run_tile_f32_k5(rq); break;
+        case 7: rc = run_tile_f32_k7(rq); break;
+        }
+    } else {
+        switch (ks) {
+        case 1: rc = run_tile_bf16_k1(rq); break;
+        case 3: rc = run_tile_bf16_k3(rq); break;
+        case 5: rc = run_tile_bf16_k5(rq); break;
+        case 7: rc = run_tile_bf16_k7(rq); break;
+        }
+    }
+    return rc == 0 ? CONV_MCMK_OK : rc == 1 ? CONV_MCMK_ERR_DEVICE : rc == 3 ? CONV_MCMK_ERR_SHAPE : CONV_MCMK_ERR_UNSUPPORTED;
+}
+
+// One launch of the tile kernel: a convolution (ks x ks taps, row_groups = 1) or a plain GEMM
+// (ks = 1 over a 1 x cols image, row_groups row planes of m rows each).
+int launch_tile(const conv_mcmk_desc *d, const Dims &dm, int ks, int shape, int csplit, const void *in,
+                const void *apk, float *out, int in_c, int in_h, int in_w, int out_q, int out_p, int pad,
+                int row_groups, hipStream_t st)
+{
+    TileRequest rq;
+    TileArgs &a = rq.args;
+    a.in = static_cast<const float *>(in);
+    a.apk = static_cast<const float *>(apk);
+    a.out = out;
     a.n = d->n;  a.c = in_c;  a.h = in_h;  a.w = in_w;
     a.q = out_q;  a.p = out_p;  a.pad = pad;
     a.m = d->m;  a.mb_per_group = dm.mb;  a.row_groups = row_groups;
-    a.cg = ceil_div(in_c, 16);
-    a.tiles_x = ceil_div(out_p, TW);
-    a.tiles_y = ceil_div(out_q, TH);
-    a.row_tiles = ceil_div((long long)row_groups * dm.mb, WM);
+    a.cg = ceil_div(in_c, d->dtype == CONV_MCMK_BF16 ? 32 : 16);
+    a.tiles_x = a.tiles_y = a.row_tiles = 0;
     a.csplit = csplit;
-    const long long blocks = (long long)a.n * a.tiles_x * a.tiles_y * a.row_tiles * csplit;
-    if (blocks < 1 || blocks >= (1LL << 31)) return CONV_MCMK_ERR_SHAPE;
+    rq.shape = shape;
+    rq.stream = st;
     if (csplit > 1) {
         // partial sums are added into the output, so it starts from zero (a fill kernel, not a
         // memset node, so the call can be captured into a graph)
@@ -107,9 +130,7 @@ int launch_tile(const conv_mcmk_desc *d, const Dims &dm, const float *in, const 
         hipLaunchKernelGGL(fill_zero_kernel, dim3(grid_for(total / 4 + 1, 256)), dim3(256), 0, st, out, total);
         if (int rc = launch_status()) return rc;
     }
-    hipLaunchKernelGGL((kn2row_tile_f32<KS, TH, TW, WM, WP>), dim3((unsigned)blocks), dim3(S::kThreads),
-                       S::kLdsBytes, st, a);
-    return launch_status();
+    return run_tile(d->dtype, ks, rq);
 }
 
 // Estimated run time of a candidate in microseconds; the constants were fitted to measurements of
@@ -135,8 +156,10 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
     }
     int simd_load = 0;
     for (int i = 0; i < 4; ++i) simd_load = simd_blocks[i] > simd_load ? simd_blocks[i] : simd_load;
-    const int chunks = ceil_div(ceil_div(d->c, 16), c.csplit);
-    const double steps = (double)chunks * ks * ks * 4;
+    const bool bf16 = d->dtype == CONV_MCMK_BF16;
+    const int chunks = ceil_div(ceil_div(d->c, bf16 ? 32 : 16), c.csplit);
+    // fp32: 4 MFMAs of 32 cycles per tap and 16-channel chunk; bf16: 1 MFMA of 16 cycles per tap and 32-channel chunk
+    const double steps = (double)chunks * ks * ks * (bf16 ? 0.5 : 4.0);
     const long long per_cu = (wgs + kNumCU - 1) / kNumCU;
     const int can_hold = 16 / waves;                                   // workgroups a CU can hold
     const long long held = per_cu < can_hold ? per_cu : can_hold;
@@ -147,47 +170,30 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
     return us;
 }
 
-template <int KS>
-int launch_fused(const conv_mcmk_desc *d, const Dims &dm, const float *in, const float *apk, float *out,
+int launch_fused(const conv_mcmk_desc *d, const Dims &dm, const void *in, const void *apk, float *out,
                  hipStream_t st)
 {
-    static const Candidate menu[] = {
-        {14, 14, 4, 2, 1}, {14, 14, 2, 4, 1}, {14, 14, 1, 4, 1}, {16, 16, 4, 2, 1}, {16, 16, 2, 4, 1}, {16, 16, 1, 4, 1},
-        {14, 14, 4, 2, 2}, {14, 14, 2, 4, 2}, {14, 14, 1, 4, 2}, {16, 16, 4, 2, 2}, {16, 16, 2, 4, 2}, {16, 16, 1, 4, 2},
-    };
-    constexpr int kMenu = sizeof(menu) / sizeof(menu[0]);
-    int best = 0;
+    Candidate best{};
     double best_cost = -1.0;
-    for (int i = 0; i < kMenu; ++i) {
-        const double c = tile_cost(d, dm, menu[i], KS);
-        if (best_cost < 0 || c < best_cost) { best_cost = c; best = i; }
-    }
-    // tuning aid: CONV_MCMK_TILE=<menu index> overrides the choice
-    if (const char *force = getenv("CONV_MCMK_TILE")) {
-        const int i = atoi(force);
-        if (i >= 0 && i < kMenu) best = i;
-    }
-    const int cs = menu[best].csplit;
-#define MCMK_GO(TH, TW, WM, WP) \
-    return launch_tile<KS, TH, TW, WM, WP>(d, dm, in, apk, out, d->c, d->h, d->w, dm.q, dm.p, d->pad, 1, cs, st)
-    switch (best % 6) {
-    case 0: MCMK_GO(14, 14, 4, 2);
-    case 1: MCMK_GO(14, 14, 2, 4);
-    case 2: MCMK_GO(14, 14, 1, 4);
-    case 3: MCMK_GO(16, 16, 4, 2);
-    case 4: MCMK_GO(16, 16, 2, 4);
-    default: MCMK_GO(16, 16, 1, 4);
-    }
-#undef MCMK_GO
+    int index = 0, best_index = 0;
+    const char *force = getenv("CONV_MCMK_TILE");      // tuning aid: menu index = shape + 6 * (csplit - 1)
+    for (int cs = 1; cs <= 2; ++cs)
+        for (int sh = 0; sh < kConvShapes; ++sh, ++index) {
+            const Candidate c{sh, cs, kTileShapes[sh].th, kTileShapes[sh].tw, kTileShapes[sh].wm, kTileShapes[sh].wp};
+            const double cost = (force && atoi(force) == index) ? 0.0 : tile_cost(d, dm, c, d->k);
+            if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = c; best_index = index; }
+        }
+    (void)best_index;
+    return launch_tile(d, dm, d->k, best.shape, best.csplit, in, apk, out, d->c, d->h, d->w, dm.q, dm.p, d->pad, 1, st);
 }
 
 // Plain GEMM [rows x kc] . [kc x cols] per image on the same tile kernel: a 1x1 "convolution" over a
 // 1 x cols image.
-int launch_gemm(const conv_mcmk_desc *d, const Dims &dm, const float *bmat, const float *apk, float *cmat,
+int launch_gemm(const conv_mcmk_desc *d, const Dims &dm, const void *bmat, const void *apk, float *cmat,
                 int kc, long long cols, int row_groups, hipStream_t st)
 {
     if (cols >= (1LL << 31)) return CONV_MCMK_ERR_SHAPE;
-    return launch_tile<1, 1, 256, 4, 2>(d, dm, bmat, apk, cmat, kc, 1, (int)cols, 1, (int)cols, 0, row_groups, 1, st);
+    return launch_tile(d, dm, 1, kGemmShape, 1, bmat, apk, cmat, kc, 1, (int)cols, 1, (int)cols, 0, row_groups, st);
 }
 
 int common_ptr_checks(const void *I, const void *K, const void *O)
@@ -264,12 +270,19 @@ int conv_mcmk_prepack(const conv_mcmk_desc *d, int variant, const void *K_dev, v
     if (misaligned(K_dev) || misaligned(Kp_dev)) return CONV_MCMK_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool im2col = variant == CONV_MCMK_IM2COL;
+    const bool bf16 = d->dtype == CONV_MCMK_BF16;
+    const int group = bf16 ? 32 : 16;
     const int taps = im2col ? 1 : dm.taps;
-    const int cg = im2col ? ceil_div((long long)d->c * dm.taps, 16) : ceil_div(d->c, 16);
-    const size_t total = (size_t)taps * dm.mb * cg * 256;
-    hipLaunchKernelGGL(prepack_f32_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st,
-                       static_cast<const float *>(K_dev), static_cast<float *>(Kp_dev),
-                       d->m, d->c, d->k, dm.mb, cg, taps, im2col);
+    const int cg = im2col ? ceil_div((long long)d->c * dm.taps, group) : ceil_div(d->c, group);
+    const size_t total = (size_t)taps * dm.mb * cg * 16 * group;
+    if (bf16)
+        hipLaunchKernelGGL(prepack_bf16_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st,
+                           static_cast<const float *>(K_dev), static_cast<uint16_t *>(Kp_dev),
+                           d->m, d->c, d->k, dm.mb, cg, taps, im2col);
+    else
+        hipLaunchKernelGGL(prepack_f32_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st,
+                           static_cast<const float *>(K_dev), static_cast<float *>(Kp_dev),
+                           d->m, d->c, d->k, dm.mb, cg, taps, im2col);
     return launch_status();
 }
 
@@ -281,17 +294,7 @@ int conv_mcmk_kn2row(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_
     int rc = validate(d, CONV_MCMK_KN2ROW, &dm);
     if (rc) return rc;
     if ((rc = common_ptr_checks(I_dev, Kp_dev, O_dev))) return rc;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const float *in = static_cast<const float *>(I_dev);
-    const float *apk = static_cast<const float *>(Kp_dev);
-    float *out = static_cast<float *>(O_dev);
-    switch (d->k) {
-    case 1: return launch_fused<1>(d, dm, in, apk, out, st);
-    case 3: return launch_fused<3>(d, dm, in, apk, out, st);
-    case 5: return launch_fused<5>(d, dm, in, apk, out, st);
-    case 7: return launch_fused<7>(d, dm, in, apk, out, st);
-    default: return CONV_MCMK_ERR_UNSUPPORTED;
-    }
+    return launch_fused(d, dm, I_dev, Kp_dev, static_cast<float *>(O_dev), static_cast<hipStream_t>(stream));
 }
 
 int conv_mcmk_kn2row_2pass(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_dev, void *O_dev,
@@ -305,8 +308,7 @@ int conv_mcmk_kn2row_2pass(const conv_mcmk_desc *d, const void *I_dev, const voi
     hipStream_t st = static_cast<hipStream_t>(stream);
     float *T = static_cast<float *>(ws);
     // pass 1: T[n][t*M+m][HW] = Kp[k*k*M x C] . I[n][C x HW]
-    rc = launch_gemm(d, dm, static_cast<const float *>(I_dev), static_cast<const float *>(Kp_dev), T,
-                     d->c, (long long)d->h * d->w, dm.taps, st);
+    rc = launch_gemm(d, dm, I_dev, Kp_dev, T, d->c, (long long)d->h * d->w, dm.taps, st);
     if (rc) return rc;
     // pass 2: shift-add of the k*k planes
     const size_t total = (size_t)d->n * d->m * dm.q * dm.p;
@@ -324,13 +326,17 @@ int conv_mcmk_im2col(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_
     if ((rc = common_ptr_checks(I_dev, Kp_dev, O_dev))) return rc;
     if ((rc = workspace_check(d, CONV_MCMK_IM2COL, ws, ws_bytes))) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    float *cols = static_cast<float *>(ws);
     const size_t total = (size_t)d->n * d->c * dm.taps * dm.q * dm.p;
-    hipLaunchKernelGGL(im2col_build_f32_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st,
-                       static_cast<const float *>(I_dev), cols, d->n, d->c, d->h, d->w, d->k, d->pad, dm.q, dm.p);
+    if (d->dtype == CONV_MCMK_BF16)
+        hipLaunchKernelGGL(im2col_build_kernel<uint16_t>, dim3(grid_for(total, 256)), dim3(256), 0, st,
+                           static_cast<const uint16_t *>(I_dev), static_cast<uint16_t *>(ws),
+                           d->n, d->c, d->h, d->w, d->k, d->pad, dm.q, dm.p);
+    else
+        hipLaunchKernelGGL(im2col_build_kernel<float>, dim3(grid_for(total, 256)), dim3(256), 0, st,
+                           static_cast<const float *>(I_dev), static_cast<float *>(ws),
+                           d->n, d->c, d->h, d->w, d->k, d->pad, dm.q, dm.p);
     if ((rc = launch_status())) return rc;
-    return launch_gemm(d, dm, cols, static_cast<const float *>(Kp_dev), static_cast<float *>(O_dev),
-                       d->c * dm.taps, (long long)dm.q * dm.p, 1, st);
+    return launch_gemm(d, dm, ws, Kp_dev, static_cast<float *>(O_dev), d->c * dm.taps, (long long)dm.q * dm.p, 1, st);
 }
 
 int conv_mcmk_direct(const conv_mcmk_desc *d, const void *I_dev, const void *K_dev, void *O_dev,

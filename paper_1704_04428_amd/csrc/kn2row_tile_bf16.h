@@ -1,0 +1,223 @@
+// Workgroup-tile kernel for bfloat16 operands with fp32 accumulation: the same decomposition as
+// kn2row_tile_f32 (one workgroup = 16*WM rows x a TH x TW output tile; all k*k taps of the kn2row
+// sum, paper section III-A, accumulate into the same registers; a tap is an address offset into the
+// input tile in LDS), re-shaped for v_mfma_f32_16x16x32_bf16:
+//
+//   - a chunk is 32 channels, one MFMA per (tap, position block, chunk);
+//   - the B operand wants 8 consecutive channels of ONE position per lane, so the halo tile lives in
+//     LDS channel-innermost, [position][32 channels] bf16 with an 80-byte position stride (16 lanes
+//     of a 16-byte read then cover all 64 banks once); global memory stays [C][H][W], the staging
+//     pass transposes: a thread gathers 8 channels of one position with eight 2-byte loads and
+//     writes them with one 16-byte LDS store;
+//   - the A operand is again pre-ordered in global memory: one 16-byte load per lane gives the
+//     fragment of a (tap, 16-row block, 32-channel chunk).
+//
+// MFMA 16x16x32 bf16 layouts (lane l of 64):  A[row l%16][k 8*(l/16) + e],  B[k 8*(l/16) + e][col l%16],
+//   e = 0..7;  D[row 4*(l/16) + v][col l%16], v = 0..3.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <type_traits>
+
+#include "kn2row_tile.h"
+
+namespace mcmk {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <int KS, int TH, int TW, int WM, int WP>
+struct TileShapeBf16 {
+    static constexpr int kCC = 32;                       // channels per chunk
+    static constexpr int kThreads = 64 * WM * WP;
+    static constexpr int kHT = TH + KS - 1;
+    static constexpr int kWT = TW + KS - 1;
+    static constexpr int kPos = kHT * kWT;
+    static constexpr int kPosStride = 80;                // bytes per position: 64 of data + 16 of padding
+    static constexpr int kBufBytes = kPos * kPosStride;
+    static constexpr int kNPB = (TH * TW + 15) / 16;
+    static constexpr int kPBW = (kNPB + WP - 1) / WP;
+    static constexpr int kItems = 4 * kPos;              // (position, channel octet) pairs per chunk
+    static constexpr int kSlots = (kItems + kThreads - 1) / kThreads;
+    static constexpr size_t kLdsBytes = 2 * (size_t)kBufBytes;
+};
+
+// TileArgs is shared with the fp32 kernel; `in` and `apk` point at bf16 data, cg counts 32-channel groups.
+template <int KS, int TH, int TW, int WM, int WP>
+__global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs a)
+{
+    using S = TileShapeBf16<KS, TH, TW, WM, WP>;
+    constexpr int CC = S::kCC, NT = S::kThreads, WT = S::kWT, POS = S::kPos, PST = S::kPosStride;
+    constexpr int PBW = S::kPBW, NPB = S::kNPB, SLOTS = S::kSlots, BUF = S::kBufBytes;
+    constexpr int REM = NPB % WP;
+    constexpr bool kRagged = REM != 0;
+    static_assert(NPB >= WP, "every wave needs at least one position block");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WM;
+    const int wp = wave / WM;
+
+    // ---- which tile (XCD-aware order, see kn2row_tile_f32)
+    int bid = blockIdx.x;
+    {
+        const int per_xcd = gridDim.x / kXcds;
+        if (bid < per_xcd * kXcds) bid = (bid % kXcds) * per_xcd + bid / kXcds;
+    }
+    const int part = bid % a.csplit;   bid /= a.csplit;
+    const int rt = bid % a.row_tiles;  bid /= a.row_tiles;
+    const int tx = bid % a.tiles_x;    bid /= a.tiles_x;
+    const int ty = bid % a.tiles_y;    bid /= a.tiles_y;
+    const int img = bid;
+    const int x0 = tx * TW, y0 = ty * TH;
+
+    const int total_rb = a.row_groups * a.mb_per_group;
+    int rb = rt * WM + wm;
+    const bool rb_valid = rb < total_rb;
+    if (!rb_valid) rb = total_rb - 1;
+    const int grp = rb / a.mb_per_group;
+    const int mbi = rb % a.mb_per_group;
+
+    // ---- staging plan: item e = tid + s*NT is (channel octet e / POS, position e % POS).
+    // 2-byte loads through a range-checked buffer descriptor: outside the image (offset 2 GiB) and
+    // beyond channel C the hardware returns 0.
+    const size_t plane = (size_t)a.h * a.w;
+    const uint16_t *in_img = reinterpret_cast<const uint16_t *>(a.in) + (size_t)img * a.c * plane;
+    const __amdgpu_buffer_rsrc_t in_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>(in_img), 0, (int)((size_t)a.c * plane * sizeof(uint16_t)), 0x00020000);
+    const uint32_t plane_bytes = (uint32_t)(plane * sizeof(uint16_t));
+    const uint32_t chunk_bytes = (uint32_t)CC * plane_bytes;
+    uint32_t g_off[SLOTS];   // byte offset of (first channel of the octet, position) in chunk 0, or 2 GiB
+    int l_off[SLOTS];        // byte offset inside an LDS buffer, or -1 when the slot is unused
+#pragma unroll
+    for (int s = 0; s < SLOTS; ++s) {
+        const int e = tid + s * NT;
+        const int oct = e / POS, pos = e % POS;
+        const int r = pos / WT, col = pos % WT;
+        const int gy = y0 - a.pad + r, gx = x0 - a.pad + col;
+        const bool used = e < S::kItems;
+        const bool inside = used && gy >= 0 && gy < a.h && gx >= 0 && gx < a.w;
+        g_off[s] = inside ? (uint32_t)(oct * 8) * plane_bytes + (uint32_t)((size_t)gy * a.w + gx) * 2u : 0x80000000u;
+        l_off[s] = used ? pos * PST + oct * 16 : -1;
+    }
+
+    uint16_t stage[SLOTS][8];
+    auto load_chunk = [&](int chunk) {
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s)
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                stage[s][e] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(
+                    in_rsrc, (int)(g_off[s] + (uint32_t)e * plane_bytes + (uint32_t)chunk * chunk_bytes), 0, 0);
+    };
+    auto store_chunk = [&](unsigned char *buf) {
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) {
+            u32x4 v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = (uint32_t)stage[s][2 * e] | ((uint32_t)stage[s][2 * e + 1] << 16);
+            if (l_off[s] >= 0) *reinterpret_cast<u32x4 *>(buf + l_off[s]) = v;
+        }
+    };
+
+    // ---- per-lane LDS byte offsets of this wave's output positions (B operand: k octet = lane/16)
+    const int nb_wave = (!kRagged || wp < REM) ? PBW : PBW - 1;
+    const int first_pb = kRagged ? wp * (PBW - 1) + min(wp, REM) : wp * PBW;
+    int b_off[PBW];
+#pragma unroll
+    for (int b = 0; b < PBW; ++b) {
+        int pp = (first_pb + b) * 16 + (lane & 15);
+        if (pp >= TH * TW) pp = 0;
+        b_off[b] = ((pp / TW) * WT + (pp % TW)) * PST + (lane >> 4) * 16;
+    }
+
+    // ---- A fragments, fetched kDepth taps ahead through a register queue
+    constexpr int T = KS * KS;
+    constexpr int kDepth = 2;
+    const int nchunks = a.cg;
+    const int chunk_lo = (int)((long long)nchunks * part / a.csplit);
+    const int chunk_hi = (int)((long long)nchunks * (part + 1) / a.csplit);
+    const u32x4 *apk = reinterpret_cast<const u32x4 *>(a.apk);
+    auto load_a = [&](int chunk, int t) {
+        const size_t tap = (size_t)t + grp;
+        return apk[((tap * a.mb_per_group + mbi) * a.cg + min(chunk, nchunks - 1)) * 64 + lane];
+    };
+
+    f32x4 acc[PBW];
+#pragma unroll
+    for (int b = 0; b < PBW; ++b) acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    u32x4 a_queue[kDepth];
+    load_chunk(chunk_lo);
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) a_queue[d] = load_a(chunk_lo + d / T, d % T);
+    store_chunk(lds_raw + (chunk_lo & 1) * BUF);
+    __syncthreads();
+
+    auto compute_chunk = [&](auto nb_tag, int chunk) {
+        constexpr int NB = decltype(nb_tag)::value;
+        const unsigned char *bsrc = lds_raw + (chunk & 1) * BUF;
+        u32x4 bq[2][NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) bq[0][b] = *reinterpret_cast<const u32x4 *>(bsrc + b_off[b]);
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const u32x4 a_cur = a_queue[0];
+#pragma unroll
+            for (int d = 0; d + 1 < kDepth; ++d) a_queue[d] = a_queue[d + 1];
+            a_queue[kDepth - 1] = load_a(chunk + (t + kDepth) / T, (t + kDepth) % T);
+            if (t + 1 < T) {
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+                    bq[(t + 1) & 1][b] = *reinterpret_cast<const u32x4 *>(
+                        bsrc + b_off[b] + (((t + 1) / KS) * WT + ((t + 1) % KS)) * PST);
+            }
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+                acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a_cur),
+                                                                 __builtin_bit_cast(bf16x8, bq[t & 1][b]),
+                                                                 acc[b], 0, 0, 0);
+            if (t + 1 < T) {
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read ...
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // ... then one MFMA
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    for (int chunk = chunk_lo; chunk < chunk_hi; ++chunk) {
+        load_chunk(chunk + 1);
+        if (kRagged && nb_wave != PBW) compute_chunk(std::integral_constant<int, kRagged ? PBW - 1 : PBW>{}, chunk);
+        else compute_chunk(std::integral_constant<int, PBW>{}, chunk);
+        store_chunk(lds_raw + ((chunk + 1) & 1) * BUF);
+        __syncthreads();
+    }
+
+    if (!rb_valid) return;
+    const size_t oplane = (size_t)a.q * a.p;
+    const int out_rows = a.row_groups * a.m;
+    float *out_img = a.out + (size_t)img * out_rows * oplane;
+#pragma unroll
+    for (int b = 0; b < PBW; ++b) {
+        if (b >= nb_wave) continue;
+        const int pp = (first_pb + b) * 16 + (lane & 15);
+        const int y = y0 + pp / TW, x = x0 + pp % TW;
+        if (pp >= TH * TW || y >= a.q || x >= a.p) continue;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int mrow = mbi * 16 + 4 * (lane >> 4) + v;
+            if (mrow >= a.m) continue;
+            float *dst = out_img + (size_t)(grp * a.m + mrow) * oplane + (size_t)y * a.p + x;
+            if (a.csplit == 1) *dst = acc[b][v];
+            else unsafeAtomicAdd(dst, acc[b][v]);
+        }
+    }
+}
+
+}  // namespace mcmk

@@ -1,0 +1,38 @@
+// Host-side interface between the C ABI and the tile-kernel instantiations.  Every (operand type,
+// kernel side) pair is compiled in a translation unit of its own (tile_f32_k3.hip, ...), so the
+// library builds in parallel; this header is what they share.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "kn2row_tile.h"
+
+namespace mcmk {
+
+// Tile shapes every instantiation file provides.  Index kGemmShape is the plain-GEMM shape
+// (1 x 256 positions) and exists for kernel side 1 only.
+struct TileShapeDesc {
+    int th, tw, wm, wp;
+};
+constexpr TileShapeDesc kTileShapes[] = {
+    {14, 14, 4, 2}, {14, 14, 2, 4}, {14, 14, 1, 4}, {16, 16, 4, 2}, {16, 16, 2, 4}, {16, 16, 1, 4}, {1, 256, 4, 2},
+};
+constexpr int kConvShapes = 6;
+constexpr int kGemmShape = 6;
+
+struct TileRequest {
+    TileArgs args;       // tiles_x, tiles_y and row_tiles are filled in by the launcher
+    int shape;           // index into kTileShapes
+    hipStream_t stream;
+};
+
+// Return hipSuccess-or-not as 0 / 1; 2 when the shape index is not instantiated, 3 when the grid is too large.
+int run_tile_f32_k1(const TileRequest &);
+int run_tile_f32_k3(const TileRequest &);
+int run_tile_f32_k5(const TileRequest &);
+int run_tile_f32_k7(const TileRequest &);
+int run_tile_bf16_k1(const TileRequest &);
+int run_tile_bf16_k3(const TileRequest &);
+int run_tile_bf16_k5(const TileRequest &);
+int run_tile_bf16_k7(const TileRequest &);
+
+}  // namespace mcmk

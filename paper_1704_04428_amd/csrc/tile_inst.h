@@ -1,0 +1,60 @@
+// Body of one tile-kernel translation unit.  The including file defines
+//   MCMK_KS    kernel side (1, 3, 5 or 7)
+//   MCMK_BF16  0: fp32 operands, 1: bf16 operands
+// and gets run_tile_<type>_k<KS>() with every tile shape of kTileShapes instantiated.
+#include "tile_dispatch.h"
+#if MCMK_BF16
+#include "kn2row_tile_bf16.h"
+#endif
+
+namespace mcmk {
+namespace {
+
+template <int TH, int TW, int WM, int WP>
+int launch_shape(const TileRequest &rq)
+{
+    TileArgs a = rq.args;
+    a.tiles_x = (a.p + TW - 1) / TW;
+    a.tiles_y = (a.q + TH - 1) / TH;
+    a.row_tiles = (a.row_groups * a.mb_per_group + WM - 1) / WM;
+    const long long blocks = (long long)a.n * a.tiles_x * a.tiles_y * a.row_tiles * a.csplit;
+    if (blocks < 1 || blocks >= (1LL << 31)) return 3;
+#if MCMK_BF16
+    using S = TileShapeBf16<MCMK_KS, TH, TW, WM, WP>;
+    hipLaunchKernelGGL((kn2row_tile_bf16<MCMK_KS, TH, TW, WM, WP>), dim3((unsigned)blocks), dim3(S::kThreads),
+                       S::kLdsBytes, rq.stream, a);
+#else
+    using S = TileShape<MCMK_KS, TH, TW, WM, WP>;
+    hipLaunchKernelGGL((kn2row_tile_f32<MCMK_KS, TH, TW, WM, WP>), dim3((unsigned)blocks), dim3(S::kThreads),
+                       S::kLdsBytes, rq.stream, a);
+#endif
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+}  // namespace
+
+#define MCMK_CAT2(a, b, c) a##b##c
+#define MCMK_CAT(a, b, c) MCMK_CAT2(a, b, c)
+#if MCMK_BF16
+#define MCMK_FN MCMK_CAT(run_tile_bf16, _k, MCMK_KS)
+#else
+#define MCMK_FN MCMK_CAT(run_tile_f32, _k, MCMK_KS)
+#endif
+
+int MCMK_FN(const TileRequest &rq)
+{
+    switch (rq.shape) {
+    case 0: return launch_shape<14, 14, 4, 2>(rq);
+    case 1: return launch_shape<14, 14, 2, 4>(rq);
+    case 2: return launch_shape<14, 14, 1, 4>(rq);
+    case 3: return launch_shape<16, 16, 4, 2>(rq);
+    case 4: return launch_shape<16, 16, 2, 4>(rq);
+    case 5: return launch_shape<16, 16, 1, 4>(rq);
+#if MCMK_KS == 1
+    case 6: return launch_shape<1, 256, 4, 2>(rq);
+#endif
+    default: return 2;
+    }
+}
+
+}  // namespace mcmk

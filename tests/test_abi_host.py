@@ -75,6 +75,13 @@ def test_sizes(lib):
     assert B.conv_mcmk_packed_kernel_bytes(d, B.IM2COL) == mb * 12 * 256 * 4              # ceil(180/16) = 12
     assert B.conv_mcmk_packed_kernel_bytes(d, B.DIRECT) == 0
     assert B.conv_mcmk_workspace_bytes(B.desc(0, 1, 1, 1, 1, 1, 0), B.IM2COL) == 0
+    # bf16 operands: 32-channel groups, 2-byte elements; the two-pass product stays fp32
+    db = B.desc(2, 20, 9, 11, 35, 3, 1, 1, B.BF16)
+    assert B.conv_mcmk_packed_kernel_bytes(db, B.KN2ROW) == 9 * mb * 1 * 512 * 2
+    assert B.conv_mcmk_packed_kernel_bytes(db, B.IM2COL) == mb * 6 * 512 * 2                  # ceil(180/32) = 6
+    assert B.conv_mcmk_workspace_bytes(db, B.IM2COL) == 2 * 20 * 9 * q * p * 2
+    assert B.conv_mcmk_workspace_bytes(db, B.KN2ROW_2PASS) == 2 * 9 * 35 * 9 * 11 * 4
+    assert B.conv_mcmk_check(db, B.DIRECT) == B.ERR_UNSUPPORTED
 
 
 def test_compute_calls_validate_before_launch(lib):
