@@ -22,6 +22,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_F32_MFMA_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
+PEAK_BF16_MFMA_TFLOPS = 2500.0    # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0
 DEFAULT_WORKLOAD = "cfg5a_vgg_deep56"
 
@@ -52,7 +53,7 @@ def time_calls(fn, steps, warmup):
     return wall_ms / steps, start.elapsed_time(stop) / steps
 
 
-def bench_layer(L, variants, steps, warmup, I_dev=None, K_dev=None):
+def bench_layer(L, variants, steps, warmup, I_dev=None, K_dev=None, dtype=0):
     import torch
     from paper_1704_04428_amd import binding as B
     from paper_1704_04428_amd import workloads as wl
@@ -60,7 +61,11 @@ def bench_layer(L, variants, steps, warmup, I_dev=None, K_dev=None):
     if I_dev is None:
         I_dev = torch.from_numpy(wl.make_input(L)).to(dev)
         K_dev = torch.from_numpy(wl.make_kernel(L)).to(dev)
-    d = B.desc(L.n, L.c, L.h, L.w, L.m, L.k, L.pad)
+    if dtype == B.BF16:
+        I_bf = torch.empty(I_dev.shape, dtype=torch.bfloat16, device=dev)
+        B.conv_mcmk_cvt_f32_bf16(I_dev, I_bf)
+        I_dev = I_bf
+    d = B.desc(L.n, L.c, L.h, L.w, L.m, L.k, L.pad, 1, dtype)
     out = {}
     for name in variants:
         variant = B.VARIANTS[name]
@@ -177,6 +182,11 @@ def main():
             r = table[name]
             r["kn2row_over_im2col_time"] = round(r["kn2row"]["ms"] / r["im2col"]["ms"], 4)
             r["frac_f32_mfma_peak"] = round(r["kn2row"]["gflops"] / 1e3 / PEAK_F32_MFMA_TFLOPS, 4)
+            if name.startswith("cfg5"):          # the deep-layer sweep is also quoted with bf16 operands
+                b = bench_layer(layer, ["kn2row", "im2col", "kn2row_2pass"], steps, 5,
+                                I_dev if same else None, K_dev if same else None, dtype=B.BF16)
+                b["frac_bf16_mfma_peak"] = round(b["kn2row"]["gflops"] / 1e3 / PEAK_BF16_MFMA_TFLOPS, 4)
+                r["bf16"] = b
             log(name, json.dumps(r))
         result["table"] = table
     print(json.dumps(result), flush=True)
