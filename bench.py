@@ -104,6 +104,9 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
+    ap.add_argument("--variant", default="kn2row", choices=["kn2row", "kn2row_2pass", "im2col", "direct"],
+                    help="which entry point the timed steps call (the headline is kn2row)")
+    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"], help="operand type of the timed steps")
     ap.add_argument("--no-table", action="store_true", help="skip the other variants and layers")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--probe-copy", action="store_true",
@@ -125,8 +128,13 @@ def main():
     dev = torch.device("cuda:0")
     I, K = wl.make_input(L), wl.make_kernel(L)
     I_dev, K_dev = torch.from_numpy(I).to(dev), torch.from_numpy(K).to(dev)
-    d = B.desc(L.n, L.c, L.h, L.w, L.m, L.k, L.pad)
-    plan = B.Plan(d, B.KN2ROW, K_dev)          # re-orders the kernel once, outside the timed region
+    dtype = B.BF16 if args.dtype == "bf16" else B.F32
+    d = B.desc(L.n, L.c, L.h, L.w, L.m, L.k, L.pad, 1, dtype)
+    plan = B.Plan(d, B.VARIANTS[args.variant], K_dev)   # re-orders the kernel once, outside the timed region
+    I_run = I_dev
+    if dtype == B.BF16:
+        I_run = torch.empty(I_dev.shape, dtype=torch.bfloat16, device=dev)
+        B.conv_mcmk_cvt_f32_bf16(I_dev, I_run)
     torch.cuda.synchronize()
 
     if args.probe_copy:
@@ -137,7 +145,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    wall_ms, dev_ms = time_calls(lambda: plan.run(I_dev), args.steps, args.warmup)
+    wall_ms, dev_ms = time_calls(lambda: plan.run(I_run), args.steps, args.warmup)
     gflops = L.flops / (wall_ms * 1e-3) / 1e9
     achieved_tflops = L.flops / (dev_ms * 1e-3) / 1e12
 
@@ -147,11 +155,13 @@ def main():
     import oracle
     ref, absref = oracle.mcmk_at(I, K, L.pad, pts)
     worst = float(np.max(np.abs(got - ref) / np.maximum(absref, 1e-30)))
-    if not worst <= 1e-4:
+    if not worst <= (1e-2 if dtype == B.BF16 else 1e-4):
         sys.exit(f"bench.py: output fails parity (worst error {worst:.3e} of sum|K||I|)")
 
+    peak = PEAK_BF16_MFMA_TFLOPS if dtype == B.BF16 else PEAK_F32_MFMA_TFLOPS
+    headline = args.variant == "kn2row" and dtype == B.F32
     result = {
-        "metric": "conv GFLOP/s (2*M*C*k^2*P*Q*N / time), kn2row",
+        "metric": f"conv GFLOP/s (2*M*C*k^2*P*Q*N / time), {args.variant}",
         "value": round(gflops, 1),
         "unit": "GFLOP/s",
         "n_gpus": 1,
@@ -161,13 +171,15 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": args.dtype,
         "data": "synthetic",
         "config": {"workload": L.name, "n": L.n, "c": L.c, "h": L.h, "w": L.w, "m": L.m, "k": L.k,
-                   "pad": L.pad, "variant": "kn2row (fused shift-add)", "flops_per_step": L.flops},
-        "roofline": {"bound": "mfma", "achieved": round(achieved_tflops, 3), "peak": PEAK_F32_MFMA_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_F32_MFMA_TFLOPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(L.name), "kernel_ms": round(dev_ms, 5)},
+                   "pad": L.pad, "variant": args.variant + (" (fused shift-add)" if args.variant == "kn2row" else ""),
+                   "flops_per_step": L.flops},
+        "roofline": {"bound": "mfma", "achieved": round(achieved_tflops, 3), "peak": peak,
+                     "unit": "TFLOP/s", "frac": round(achieved_tflops / peak, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(L.name) if headline else None,
+                     "kernel_ms": round(dev_ms, 5)},
         "parity_worst_err_over_bound_norm": worst,
     }
     if not args.no_cpu:

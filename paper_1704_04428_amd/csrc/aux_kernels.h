@@ -78,53 +78,81 @@ __global__ void prepack_bf16_kernel(const float *__restrict__ K, uint16_t *__res
 // ---------------------------------------------------------------------------------------------
 // Input-patch-matrix of section II-B for one batch: Ihat[n][(c*k+i)*k+j][q*P+p]; T is float, or
 // uint16_t for bfloat16 bit patterns (zero is all-bits-zero in both).
-template <typename T>
+// One thread owns VEC consecutive output columns of one (image, channel, output row) and writes
+// them for all k*k taps, so the input patch is read once (through L1/L2) and every store is a
+// full VEC-wide, coalesced row segment of one of the k*k matrix rows -- the k*k-fold replication
+// is pure write traffic.  VEC > 1 needs P % VEC == 0 (16-byte aligned stores); the host picks.
+template <typename T, int VEC>
 __global__ void im2col_build_kernel(const T *__restrict__ I, T *__restrict__ cols,
                                     int n, int c, int h, int w, int k, int pad, int q, int p)
 {
+    struct alignas(sizeof(T) * VEC) Pack { T v[VEC]; };
+    const int pv = p / VEC;                                   // column groups per row
     const size_t qp = (size_t)q * p;
-    const size_t total = (size_t)n * c * k * k * qp;
+    const size_t total = (size_t)n * c * q * pv;
     for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total;
          e += (size_t)gridDim.x * blockDim.x) {
-        const int op = (int)(e % qp);
-        size_t row = e / qp;                           // n*(c*k*k) + (c*k+i)*k+j
-        const int j = row % k;  row /= k;
-        const int i = row % k;  row /= k;              // row = n*c + channel
-        const int y = op / p - pad + i;
-        const int x = op % p - pad + j;
-        T v = T(0);
-        if (y >= 0 && y < h && x >= 0 && x < w) v = I[(row * h + y) * w + x];
-        cols[e] = v;
+        const int xg = (int)(e % pv);
+        size_t rest = e / pv;
+        const int oq = (int)(rest % q);
+        const size_t nc = rest / q;                           // image * C + channel
+        const T *src = I + nc * (size_t)h * w;
+        T *dst = cols + nc * (size_t)k * k * qp + (size_t)oq * p + (size_t)xg * VEC;
+        const int x0 = xg * VEC - pad;
+        for (int i = 0; i < k; ++i) {
+            const int y = oq - pad + i;
+            const bool row_ok = y >= 0 && y < h;
+            for (int j = 0; j < k; ++j) {
+                Pack out;
+#pragma unroll
+                for (int u = 0; u < VEC; ++u) {
+                    const int x = x0 + j + u;
+                    out.v[u] = (row_ok && x >= 0 && x < w) ? src[(size_t)y * w + x] : T(0);
+                }
+                *reinterpret_cast<Pack *>(dst + (size_t)(i * k + j) * qp) = out;
+            }
+        }
     }
 }
 
 // ---------------------------------------------------------------------------------------------
 // Shift-add post pass of section III-A: O[n][m][q][p] = sum over taps of T[n][t*M+m][q+di][p+dj],
 // offsets taken in the 2-D plane; positions outside the H x W plane are discarded.
+// One thread owns VEC consecutive columns of one output row (VEC > 1 needs P % VEC == 0).
+template <int VEC>
 __global__ void shift_add_f32_kernel(const float *__restrict__ T, float *__restrict__ O,
                                      int n, int m, int h, int w, int k, int pad, int q, int p)
 {
-    const size_t qp = (size_t)q * p, hw = (size_t)h * w;
-    const size_t total = (size_t)n * m * qp;
+    struct alignas(sizeof(float) * VEC) Pack { float v[VEC]; };
+    const int pv = p / VEC;
+    const size_t hw = (size_t)h * w;
+    const size_t total = (size_t)n * m * q * pv;
     for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total;
          e += (size_t)gridDim.x * blockDim.x) {
-        const int op = (int)(e % qp);
-        const size_t nm = e / qp;
+        const int xg = (int)(e % pv);
+        size_t rest = e / pv;
+        const int oq = (int)(rest % q);
+        const size_t nm = rest / q;
         const int im = (int)(nm % m);
         const size_t in = nm / m;
-        const int oq = op / p, ox = op % p;
         const float *Tn = T + in * (size_t)k * k * m * hw;
-        float acc = 0.0f;
+        Pack acc;
+#pragma unroll
+        for (int u = 0; u < VEC; ++u) acc.v[u] = 0.0f;
         for (int i = 0; i < k; ++i) {
             const int y = oq - pad + i;
             if (y < 0 || y >= h) continue;
             for (int j = 0; j < k; ++j) {
-                const int x = ox - pad + j;
-                if (x < 0 || x >= w) continue;
-                acc += Tn[((size_t)(i * k + j) * m + im) * hw + (size_t)y * w + x];
+                const float *row = Tn + ((size_t)(i * k + j) * m + im) * hw + (size_t)y * w;
+                const int x0 = xg * VEC - pad + j;
+#pragma unroll
+                for (int u = 0; u < VEC; ++u) {
+                    const int x = x0 + u;
+                    if (x >= 0 && x < w) acc.v[u] += row[x];
+                }
             }
         }
-        O[e] = acc;
+        *reinterpret_cast<Pack *>(O + (nm * q + oq) * (size_t)p + (size_t)xg * VEC) = acc;
     }
 }
 

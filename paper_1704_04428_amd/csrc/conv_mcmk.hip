@@ -311,9 +311,14 @@ int conv_mcmk_kn2row_2pass(const conv_mcmk_desc *d, const void *I_dev, const voi
     rc = launch_gemm(d, dm, I_dev, Kp_dev, T, d->c, (long long)d->h * d->w, dm.taps, st);
     if (rc) return rc;
     // pass 2: shift-add of the k*k planes
-    const size_t total = (size_t)d->n * d->m * dm.q * dm.p;
-    hipLaunchKernelGGL(shift_add_f32_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, T,
-                       static_cast<float *>(O_dev), d->n, d->m, d->h, d->w, d->k, d->pad, dm.q, dm.p);
+    const int vec = dm.p % 4 == 0 ? 4 : 1;
+    const size_t total = (size_t)d->n * d->m * dm.q * (dm.p / vec);
+    if (vec == 4)
+        hipLaunchKernelGGL(shift_add_f32_kernel<4>, dim3(grid_for(total, 256)), dim3(256), 0, st, T,
+                           static_cast<float *>(O_dev), d->n, d->m, d->h, d->w, d->k, d->pad, dm.q, dm.p);
+    else
+        hipLaunchKernelGGL(shift_add_f32_kernel<1>, dim3(grid_for(total, 256)), dim3(256), 0, st, T,
+                           static_cast<float *>(O_dev), d->n, d->m, d->h, d->w, d->k, d->pad, dm.q, dm.p);
     return launch_status();
 }
 
@@ -326,15 +331,17 @@ int conv_mcmk_im2col(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_
     if ((rc = common_ptr_checks(I_dev, Kp_dev, O_dev))) return rc;
     if ((rc = workspace_check(d, CONV_MCMK_IM2COL, ws, ws_bytes))) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const size_t total = (size_t)d->n * d->c * dm.taps * dm.q * dm.p;
-    if (d->dtype == CONV_MCMK_BF16)
-        hipLaunchKernelGGL(im2col_build_kernel<uint16_t>, dim3(grid_for(total, 256)), dim3(256), 0, st,
-                           static_cast<const uint16_t *>(I_dev), static_cast<uint16_t *>(ws),
-                           d->n, d->c, d->h, d->w, d->k, d->pad, dm.q, dm.p);
-    else
-        hipLaunchKernelGGL(im2col_build_kernel<float>, dim3(grid_for(total, 256)), dim3(256), 0, st,
-                           static_cast<const float *>(I_dev), static_cast<float *>(ws),
-                           d->n, d->c, d->h, d->w, d->k, d->pad, dm.q, dm.p);
+    // widest store the row length allows: 16 bytes when P is a multiple of 4 (fp32) / 8 (bf16)
+    const bool bf16 = d->dtype == CONV_MCMK_BF16;
+    const int vec = bf16 ? (dm.p % 8 == 0 ? 8 : 1) : (dm.p % 4 == 0 ? 4 : 1);
+    const size_t total = (size_t)d->n * d->c * dm.q * (dm.p / vec);
+    const dim3 grid(grid_for(total, 256)), block(256);
+#define MCMK_IM2COL(T, V)                                                                             \
+    hipLaunchKernelGGL((im2col_build_kernel<T, V>), grid, block, 0, st, static_cast<const T *>(I_dev), \
+                       static_cast<T *>(ws), d->n, d->c, d->h, d->w, d->k, d->pad, dm.q, dm.p)
+    if (bf16) { if (vec == 8) MCMK_IM2COL(uint16_t, 8); else MCMK_IM2COL(uint16_t, 1); }
+    else      { if (vec == 4) MCMK_IM2COL(float, 4);    else MCMK_IM2COL(float, 1); }
+#undef MCMK_IM2COL
     if ((rc = launch_status())) return rc;
     return launch_gemm(d, dm, ws, Kp_dev, static_cast<float *>(O_dev), d->c * dm.taps, (long long)dm.q * dm.p, 1, st);
 }
