@@ -177,6 +177,7 @@ int launch_fused(const conv_mcmk_desc *d, const Dims &dm, const void *in, const 
     double best_cost = -1.0;
     int index = 0, best_index = 0;
     const char *force = getenv("CONV_MCMK_TILE");      // tuning aid: menu index = shape + 6 * (csplit - 1)
+    if (force && (force[0] < '0' || force[0] > '9')) force = nullptr;
     for (int cs = 1; cs <= 2; ++cs)
         for (int sh = 0; sh < kConvShapes; ++sh, ++index) {
             const Candidate c{sh, cs, kTileShapes[sh].th, kTileShapes[sh].tw, kTileShapes[sh].wm, kTileShapes[sh].wp};

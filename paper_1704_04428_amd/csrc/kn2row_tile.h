@@ -46,9 +46,9 @@ struct TileArgs {
                           // adds its partial sums into a zeroed output (a + b is order-independent)
 };
 
-template <int KS, int TH, int TW, int WM, int WP>
+template <int KS, int TH, int TW, int WM, int WP, int CCH = 16>
 struct TileShape {
-    static constexpr int kCC = 16;                       // channels per chunk
+    static constexpr int kCC = CCH;                      // channels per chunk, a multiple of 16
     static constexpr int kThreads = 64 * WM * WP;
     static constexpr int kHT = TH + KS - 1;
     static constexpr int kWT = TW + KS - 1;
@@ -63,10 +63,12 @@ struct TileShape {
     static constexpr size_t kLdsBytes = 2 * (size_t)kBuf * sizeof(float);
 };
 
-template <int KS, int TH, int TW, int WM, int WP>
+template <int KS, int TH, int TW, int WM, int WP, int CCH = 16>
 __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a)
 {
-    using S = TileShape<KS, TH, TW, WM, WP>;
+    using S = TileShape<KS, TH, TW, WM, WP, CCH>;
+    static_assert(CCH % 16 == 0, "a chunk is a whole number of packed 16-channel groups");
+    constexpr int NQ = CCH / 16;                   // packed A vectors per tap and chunk
     constexpr int CC = S::kCC, NT = S::kThreads, WT = S::kWT, POS = S::kPos, CHS = S::kCHS;
     constexpr int PBW = S::kPBW, NPB = S::kNPB, SLOTS = S::kSlots, BUF = S::kBuf;
     // position blocks are dealt evenly to the WP waves: the first REM waves own PBW blocks, the
@@ -169,21 +171,31 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a
     // straight from global memory kDepth taps ahead of use and handed down a short register queue.
     constexpr int T = KS * KS;                   // taps per chunk
     constexpr int kDepth = 2;
-    const int nchunks = a.cg;
+    const int nchunks = (a.cg + NQ - 1) / NQ;
     const int chunk_lo = (int)((long long)nchunks * part / a.csplit);
     const int chunk_hi = (int)((long long)nchunks * (part + 1) / a.csplit);
     const f32x4 *apk = reinterpret_cast<const f32x4 *>(a.apk);
+    struct AFrag { f32x4 q[NQ]; };
     auto load_a = [&](int chunk, int t) {
         // conv: tap planes are [tap][mb][cg]; row-group GEMM: KS == 1 and grp picks the plane
         const size_t tap = (size_t)t + grp;
-        return apk[((tap * a.mb_per_group + mbi) * a.cg + min(chunk, nchunks - 1)) * 64 + lane];
+        const int c0 = min(chunk, nchunks - 1) * NQ;
+        AFrag f;
+#pragma unroll
+        for (int qq = 0; qq < NQ; ++qq) {
+            // a chunk may reach past the last packed group: read the last one and zero it
+            const int g16 = min(c0 + qq, a.cg - 1);
+            const f32x4 v = apk[((tap * a.mb_per_group + mbi) * a.cg + g16) * 64 + lane];
+            f.q[qq] = (NQ == 1 || c0 + qq < a.cg) ? v : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        return f;
     };
 
     f32x4 acc[PBW];
 #pragma unroll
     for (int b = 0; b < PBW; ++b) acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    f32x4 a_queue[kDepth];
+    AFrag a_queue[kDepth];
     load_chunk(chunk_lo);
 #pragma unroll
     for (int d = 0; d < kDepth; ++d) a_queue[d] = load_a(chunk_lo + d / T, d % T);
@@ -194,22 +206,23 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a
     // owns the ragged last share); straight-line code, every LDS offset an immediate.
     auto compute_chunk = [&](auto nb_tag, int chunk) {
         constexpr int NB = decltype(nb_tag)::value;
-        constexpr int G = T * 4;                   // steps per chunk: (tap, channel quad)
+        constexpr int VQ = CCH / 4;                // channel quads per chunk
+        constexpr int G = T * VQ;                  // steps per chunk: (tap, channel quad)
         const float *bsrc = lds + (chunk & 1) * BUF;
         float bq[2][NB];                           // B fragments: this step's and the next one's
 #pragma unroll
         for (int b = 0; b < NB; ++b) bq[0][b] = bsrc[b_off[b]];
 #pragma unroll
         for (int t = 0; t < T; ++t) {
-            const f32x4 a_cur = a_queue[0];
+            const AFrag a_cur = a_queue[0];
 #pragma unroll
             for (int d = 0; d + 1 < kDepth; ++d) a_queue[d] = a_queue[d + 1];
             a_queue[kDepth - 1] = load_a(chunk + (t + kDepth) / T, (t + kDepth) % T);
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int g = t * 4 + v;           // step number inside the chunk
+            for (int v = 0; v < VQ; ++v) {
+                const int g = t * VQ + v;          // step number inside the chunk
                 // fetch the next step's fragments while this step's products run
-                const int t1 = (g + 1) / 4, v1 = (g + 1) % 4;
+                const int t1 = (g + 1) / VQ, v1 = (g + 1) % VQ;
                 if (g + 1 < G) {
 #pragma unroll
                     for (int b = 0; b < NB; ++b)
@@ -217,7 +230,7 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a
                 }
 #pragma unroll
                 for (int b = 0; b < NB; ++b)
-                    acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[v], bq[g & 1][b], acc[b], 0, 0, 0);
+                    acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur.q[v / 4][v % 4], bq[g & 1][b], acc[b], 0, 0, 0);
                 // pin the order: one LDS read of step g+1 between consecutive products of step g,
                 // and nothing drifts across steps
                 if (g + 1 < G) {

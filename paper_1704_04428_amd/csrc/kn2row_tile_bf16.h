@@ -5,10 +5,13 @@
 //
 //   - a chunk is 32 channels, one MFMA per (tap, position block, chunk);
 //   - the B operand wants 8 consecutive channels of ONE position per lane, so the halo tile lives in
-//     LDS channel-innermost, [position][32 channels] bf16 with an 80-byte position stride (16 lanes
-//     of a 16-byte read then cover all 64 banks once); global memory stays [C][H][W], the staging
-//     pass transposes: a thread gathers 8 channels of one position with eight 2-byte loads and
-//     writes them with one 16-byte LDS store;
+//     LDS as [channel octet][row][column][8 channels]: the 16 lanes that share an octet read 16
+//     bytes each from consecutive columns, i.e. one contiguous 256-byte run -- the only pattern a
+//     probe of ds_read_b128 on gfx950 showed to run at full rate.  A 16-position block of a tile
+//     that is TW wide continues on the next tile row; the row stride is chosen congruent to
+//     16*TW modulo 256 bytes, so the continued part falls on exactly the banks the first part
+//     left free.  Global memory stays [C][H][W]; the staging pass transposes: a thread gathers 8
+//     channels of one position with eight 2-byte loads and writes them with one 16-byte LDS store;
 //   - the A operand is again pre-ordered in global memory: one 16-byte load per lane gives the
 //     fragment of a (tap, 16-row block, 32-channel chunk).
 //
@@ -33,8 +36,10 @@ struct TileShapeBf16 {
     static constexpr int kHT = TH + KS - 1;
     static constexpr int kWT = TW + KS - 1;
     static constexpr int kPos = kHT * kWT;
-    static constexpr int kPosStride = 80;                // bytes per position: 64 of data + 16 of padding
-    static constexpr int kBufBytes = kPos * kPosStride;
+    // bytes between tile rows: >= 16 per column, == 16*TW (mod 256)
+    static constexpr int kRowBytes = ((kWT * 16 - (TW * 16) % 256 + 255) / 256) * 256 + (TW * 16) % 256;
+    static constexpr int kPlaneBytes = ((kHT * kRowBytes + 255) / 256) * 256;   // one channel octet
+    static constexpr int kBufBytes = 4 * kPlaneBytes;
     static constexpr int kNPB = (TH * TW + 15) / 16;
     static constexpr int kPBW = (kNPB + WP - 1) / WP;
     static constexpr int kItems = 4 * kPos;              // (position, channel octet) pairs per chunk
@@ -47,7 +52,8 @@ template <int KS, int TH, int TW, int WM, int WP>
 __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs a)
 {
     using S = TileShapeBf16<KS, TH, TW, WM, WP>;
-    constexpr int CC = S::kCC, NT = S::kThreads, WT = S::kWT, POS = S::kPos, PST = S::kPosStride;
+    constexpr int CC = S::kCC, NT = S::kThreads, WT = S::kWT, POS = S::kPos, RSB = S::kRowBytes, PLB = S::kPlaneBytes;
+    static_assert(RSB >= WT * 16 && (RSB - TW * 16) % 256 == 0, "row stride rule");
     constexpr int PBW = S::kPBW, NPB = S::kNPB, SLOTS = S::kSlots, BUF = S::kBufBytes;
     constexpr int REM = NPB % WP;
     constexpr bool kRagged = REM != 0;
@@ -101,7 +107,7 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs 
         const bool used = e < S::kItems;
         const bool inside = used && gy >= 0 && gy < a.h && gx >= 0 && gx < a.w;
         g_off[s] = inside ? (uint32_t)(oct * 8) * plane_bytes + (uint32_t)((size_t)gy * a.w + gx) * 2u : 0x80000000u;
-        l_off[s] = used ? pos * PST + oct * 16 : -1;
+        l_off[s] = used ? oct * PLB + r * RSB + col * 16 : -1;
     }
 
     uint16_t stage[SLOTS][8];
@@ -131,12 +137,16 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs 
     for (int b = 0; b < PBW; ++b) {
         int pp = (first_pb + b) * 16 + (lane & 15);
         if (pp >= TH * TW) pp = 0;
-        b_off[b] = ((pp / TW) * WT + (pp % TW)) * PST + (lane >> 4) * 16;
+        b_off[b] = (lane >> 4) * PLB + (pp / TW) * RSB + (pp % TW) * 16;
     }
 
-    // ---- A fragments, fetched kDepth taps ahead through a register queue
+    // ---- A fragments.  A tap lasts only ~100 ns here, far less than an L2 round trip, so the
+    // fragments are fetched a whole chunk ahead (kernel sides 1 and 3) or a tap row ahead (5, 7):
+    // a ring of D registers whose slot for tap t is t % D -- static, because D divides the taps per
+    // chunk -- is refilled right after use with the fragment D taps further on.
     constexpr int T = KS * KS;
-    constexpr int kDepth = 2;
+    constexpr int D = T <= 9 ? T : KS;
+    static_assert(T % D == 0, "ring slots must be static");
     const int nchunks = a.cg;
     const int chunk_lo = (int)((long long)nchunks * part / a.csplit);
     const int chunk_hi = (int)((long long)nchunks * (part + 1) / a.csplit);
@@ -150,10 +160,10 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs 
 #pragma unroll
     for (int b = 0; b < PBW; ++b) acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    u32x4 a_queue[kDepth];
+    u32x4 a_ring[D];
     load_chunk(chunk_lo);
 #pragma unroll
-    for (int d = 0; d < kDepth; ++d) a_queue[d] = load_a(chunk_lo + d / T, d % T);
+    for (int d = 0; d < D; ++d) a_ring[d] = load_a(chunk_lo + d / T, d % T);
     store_chunk(lds_raw + (chunk_lo & 1) * BUF);
     __syncthreads();
 
@@ -165,15 +175,13 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs 
         for (int b = 0; b < NB; ++b) bq[0][b] = *reinterpret_cast<const u32x4 *>(bsrc + b_off[b]);
 #pragma unroll
         for (int t = 0; t < T; ++t) {
-            const u32x4 a_cur = a_queue[0];
-#pragma unroll
-            for (int d = 0; d + 1 < kDepth; ++d) a_queue[d] = a_queue[d + 1];
-            a_queue[kDepth - 1] = load_a(chunk + (t + kDepth) / T, (t + kDepth) % T);
+            const u32x4 a_cur = a_ring[t % D];
+            a_ring[t % D] = load_a(chunk + (t + D) / T, (t + D) % T);
             if (t + 1 < T) {
 #pragma unroll
                 for (int b = 0; b < NB; ++b)
                     bq[(t + 1) & 1][b] = *reinterpret_cast<const u32x4 *>(
-                        bsrc + b_off[b] + (((t + 1) / KS) * WT + ((t + 1) % KS)) * PST);
+                        bsrc + b_off[b] + ((t + 1) / KS) * RSB + ((t + 1) % KS) * 16);
             }
 #pragma unroll
             for (int b = 0; b < NB; ++b)

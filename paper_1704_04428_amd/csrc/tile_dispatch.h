@@ -9,12 +9,12 @@
 namespace mcmk {
 
 // Tile shapes every instantiation file provides.  Index kGemmShape is the plain-GEMM shape
-// (1 x 256 positions) and exists for kernel side 1 only.
+// (1 x 224 positions, 32-channel chunks) and exists for kernel side 1 only.
 struct TileShapeDesc {
     int th, tw, wm, wp;
 };
 constexpr TileShapeDesc kTileShapes[] = {
-    {14, 14, 4, 2}, {14, 14, 2, 4}, {14, 14, 1, 4}, {16, 16, 4, 2}, {16, 16, 2, 4}, {16, 16, 1, 4}, {1, 256, 4, 2},
+    {14, 14, 4, 2}, {14, 14, 2, 4}, {14, 14, 1, 4}, {16, 16, 4, 2}, {16, 16, 2, 4}, {16, 16, 1, 4}, {1, 224, 4, 2},
 };
 constexpr int kConvShapes = 6;
 constexpr int kGemmShape = 6;

@@ -10,7 +10,7 @@
 namespace mcmk {
 namespace {
 
-template <int TH, int TW, int WM, int WP>
+template <int TH, int TW, int WM, int WP, int CCH = 16>
 int launch_shape(const TileRequest &rq)
 {
     TileArgs a = rq.args;
@@ -21,11 +21,23 @@ int launch_shape(const TileRequest &rq)
     if (blocks < 1 || blocks >= (1LL << 31)) return 3;
 #if MCMK_BF16
     using S = TileShapeBf16<MCMK_KS, TH, TW, WM, WP>;
+    if (S::kLdsBytes > 65536) {
+        // more than 64 KiB of dynamic LDS has to be allowed per kernel, once per device
+        static bool allowed[64] = {};
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 1;
+        if (!allowed[dev]) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&kn2row_tile_bf16<MCMK_KS, TH, TW, WM, WP>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::kLdsBytes) != hipSuccess)
+                return 1;
+            allowed[dev] = true;
+        }
+    }
     hipLaunchKernelGGL((kn2row_tile_bf16<MCMK_KS, TH, TW, WM, WP>), dim3((unsigned)blocks), dim3(S::kThreads),
                        S::kLdsBytes, rq.stream, a);
 #else
-    using S = TileShape<MCMK_KS, TH, TW, WM, WP>;
-    hipLaunchKernelGGL((kn2row_tile_f32<MCMK_KS, TH, TW, WM, WP>), dim3((unsigned)blocks), dim3(S::kThreads),
+    using S = TileShape<MCMK_KS, TH, TW, WM, WP, CCH>;
+    hipLaunchKernelGGL((kn2row_tile_f32<MCMK_KS, TH, TW, WM, WP, CCH>), dim3((unsigned)blocks), dim3(S::kThreads),
                        S::kLdsBytes, rq.stream, a);
 #endif
     return hipGetLastError() == hipSuccess ? 0 : 1;
@@ -51,7 +63,7 @@ int MCMK_FN(const TileRequest &rq)
     case 4: return launch_shape<16, 16, 2, 4>(rq);
     case 5: return launch_shape<16, 16, 1, 4>(rq);
 #if MCMK_KS == 1
-    case 6: return launch_shape<1, 256, 4, 2>(rq);
+    case 6: return launch_shape<1, 224, 4, 2, 32>(rq);     // plain GEMM: deeper chunks, fewer barriers
 #endif
     default: return 2;
     }
