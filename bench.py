@@ -175,7 +175,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": L.name, "n": L.n, "c": L.c, "h": L.h, "w": L.w, "m": L.m, "k": L.k,
                    "pad": L.pad, "variant": args.variant + (" (fused shift-add)" if args.variant == "kn2row" else ""),
-                   "flops_per_step": L.flops},
+                   "flops_per_step": L.flops, "plan": B.conv_mcmk_describe_plan(d, B.VARIANTS[args.variant])},
         "roofline": {"bound": "mfma", "achieved": round(achieved_tflops, 3), "peak": peak,
                      "unit": "TFLOP/s", "frac": round(achieved_tflops / peak, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get(L.name) if headline else None,

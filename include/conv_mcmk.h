@@ -76,6 +76,14 @@ const char *conv_mcmk_strerror(int code);
 int conv_mcmk_check(const conv_mcmk_desc *desc, int variant);
 
 /*
+ * Host-only introspection: writes one line of text saying how `variant` would run `desc` (for the
+ * fused kernel: the tile shape, wave layout and channel split the cost estimate picks -- the
+ * per-layer selection the paper's conclusion asks for -- and the number of workgroups) into buf,
+ * NUL-terminated, at most n bytes.  Returns CONV_MCMK_OK or the error conv_mcmk_check would give.
+ */
+int conv_mcmk_describe_plan(const conv_mcmk_desc *desc, int variant, char *buf, size_t n);
+
+/*
  * Bytes of caller-provided scratch a variant needs (0 for KN2ROW and DIRECT; 0 also for an invalid
  * desc -- use conv_mcmk_check for the reason).
  *   KN2ROW_2PASS: N * k*k*M * H*W floats -- the GEMM result of section III-A, per image
@@ -117,6 +125,8 @@ int conv_mcmk_prepack(const conv_mcmk_desc *desc, int variant, const void *K_dev
  *   ws, ws_bytes  scratch of at least conv_mcmk_workspace_bytes(); may be NULL / 0 when that is 0
  * conv_mcmk_kn2row implements k = 1, 3, 5, 7 (other k: CONV_MCMK_ERR_UNSUPPORTED; the other
  * variants take any k >= 1).  conv_mcmk_direct implements CONV_MCMK_F32 only.
+ * Results are bit-reproducible from call to call: where conv_mcmk_kn2row splits the channels over two
+ * workgroups it adds exactly two partial sums into a zeroed output, which is order-independent.
  */
 int conv_mcmk_kn2row(const conv_mcmk_desc *desc, const void *I_dev, const void *Kp_dev, void *O_dev,
                      void *ws, size_t ws_bytes, void *stream);

@@ -20,7 +20,7 @@ VARIANTS = {"kn2row": KN2ROW, "kn2row_2pass": KN2ROW_2PASS, "im2col": IM2COL, "d
 OK, ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_DEVICE, ERR_ALIGN = range(7)
 
 EXPORTS = (
-    "conv_mcmk_strerror", "conv_mcmk_check", "conv_mcmk_workspace_bytes", "conv_mcmk_packed_kernel_bytes",
+    "conv_mcmk_strerror", "conv_mcmk_check", "conv_mcmk_describe_plan", "conv_mcmk_workspace_bytes", "conv_mcmk_packed_kernel_bytes",
     "conv_mcmk_prepack", "conv_mcmk_kn2row", "conv_mcmk_kn2row_2pass", "conv_mcmk_im2col",
     "conv_mcmk_direct", "conv_mcmk_cvt_f32_bf16",
 )
@@ -54,6 +54,8 @@ def lib():
         L.conv_mcmk_strerror.restype = ctypes.c_char_p
         L.conv_mcmk_check.argtypes = [dp, i]
         L.conv_mcmk_check.restype = i
+        L.conv_mcmk_describe_plan.argtypes = [dp, i, ctypes.c_char_p, sz]
+        L.conv_mcmk_describe_plan.restype = i
         L.conv_mcmk_workspace_bytes.argtypes = [dp, i]
         L.conv_mcmk_workspace_bytes.restype = sz
         L.conv_mcmk_packed_kernel_bytes.argtypes = [dp, i]
@@ -95,6 +97,12 @@ def _stream(stream):
 
 def conv_mcmk_check(d: Desc, variant: int) -> int:
     return lib().conv_mcmk_check(ctypes.byref(d), variant)
+
+
+def conv_mcmk_describe_plan(d: Desc, variant: int) -> str:
+    buf = ctypes.create_string_buffer(256)
+    _raise(lib().conv_mcmk_describe_plan(ctypes.byref(d), variant, buf, len(buf)))
+    return buf.value.decode()
 
 
 def conv_mcmk_workspace_bytes(d: Desc, variant: int) -> int:

@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
 #include <cstdlib>
 
 #include "aux_kernels.h"
@@ -170,21 +171,28 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
     return us;
 }
 
-int launch_fused(const conv_mcmk_desc *d, const Dims &dm, const void *in, const void *apk, float *out,
-                 hipStream_t st)
+// The candidate the cost estimate prefers for the fused kernel (or the one CONV_MCMK_TILE forces:
+// tuning aid, menu index = shape + 6 * (csplit - 1)).
+Candidate choose_fused(const conv_mcmk_desc *d, const Dims &dm)
 {
     Candidate best{};
     double best_cost = -1.0;
-    int index = 0, best_index = 0;
-    const char *force = getenv("CONV_MCMK_TILE");      // tuning aid: menu index = shape + 6 * (csplit - 1)
+    int index = 0;
+    const char *force = getenv("CONV_MCMK_TILE");
     if (force && (force[0] < '0' || force[0] > '9')) force = nullptr;
     for (int cs = 1; cs <= 2; ++cs)
         for (int sh = 0; sh < kConvShapes; ++sh, ++index) {
             const Candidate c{sh, cs, kTileShapes[sh].th, kTileShapes[sh].tw, kTileShapes[sh].wm, kTileShapes[sh].wp};
             const double cost = (force && atoi(force) == index) ? 0.0 : tile_cost(d, dm, c, d->k);
-            if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = c; best_index = index; }
+            if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = c; }
         }
-    (void)best_index;
+    return best;
+}
+
+int launch_fused(const conv_mcmk_desc *d, const Dims &dm, const void *in, const void *apk, float *out,
+                 hipStream_t st)
+{
+    const Candidate best = choose_fused(d, dm);
     return launch_tile(d, dm, d->k, best.shape, best.csplit, in, apk, out, d->c, d->h, d->w, dm.q, dm.p, d->pad, 1, st);
 }
 
@@ -232,6 +240,37 @@ const char *conv_mcmk_strerror(int code)
 }
 
 int conv_mcmk_check(const conv_mcmk_desc *desc, int variant) { return validate(desc, variant, nullptr); }
+
+int conv_mcmk_describe_plan(const conv_mcmk_desc *d, int variant, char *buf, size_t n)
+{
+    Dims dm;
+    int rc = validate(d, variant, &dm);
+    if (rc) return rc;
+    if (!buf || n == 0) return CONV_MCMK_ERR_NULL;
+    const char *type = d->dtype == CONV_MCMK_BF16 ? "bf16" : "f32";
+    const TileShapeDesc &g = kTileShapes[kGemmShape];
+    switch (variant) {
+    case CONV_MCMK_KN2ROW: {
+        const Candidate c = choose_fused(d, dm);
+        const long long wgs = (long long)d->n * ceil_div(dm.p, c.tw) * ceil_div(dm.q, c.th) * ceil_div(dm.mb, c.wm) * c.csplit;
+        snprintf(buf, n, "kn2row fused %s: tile %dx%d, waves %dx%d, channel split %d, %lld workgroups, est %.1f us",
+                 type, c.th, c.tw, c.wm, c.wp, c.csplit, wgs, tile_cost(d, dm, c, d->k));
+        break;
+    }
+    case CONV_MCMK_KN2ROW_2PASS:
+        snprintf(buf, n, "kn2row two-pass %s: GEMM [%d x %d].[%d x %d] per image (tile 1x%d, waves %dx%d), then shift-add",
+                 type, dm.taps * d->m, d->c, d->c, d->h * d->w, g.tw, g.wm, g.wp);
+        break;
+    case CONV_MCMK_IM2COL:
+        snprintf(buf, n, "im2col %s: patch matrix [%d x %d] per image, GEMM [%d x %d].[%d x %d] (tile 1x%d, waves %dx%d)",
+                 type, d->c * dm.taps, dm.q * dm.p, d->m, d->c * dm.taps, d->c * dm.taps, dm.q * dm.p, g.tw, g.wm, g.wp);
+        break;
+    default:
+        snprintf(buf, n, "direct f32: one thread per output element, %lld outputs", (long long)d->n * d->m * dm.q * dm.p);
+        break;
+    }
+    return CONV_MCMK_OK;
+}
 
 size_t conv_mcmk_workspace_bytes(const conv_mcmk_desc *d, int variant)
 {

@@ -102,3 +102,28 @@ def test_compute_calls_validate_before_launch(lib):
     assert lib.conv_mcmk_prepack(ctypes.byref(d), B.KN2ROW, null, null, null) == B.ERR_NULL
     assert lib.conv_mcmk_prepack(ctypes.byref(d), B.DIRECT, fake, fake, null) == B.ERR_UNSUPPORTED
     assert lib.conv_mcmk_cvt_f32_bf16(null, null, 4, null) == B.ERR_NULL
+
+
+def test_plan_selection_for_benchmark_layers(lib, monkeypatch):
+    """The per-layer choice of the fused kernel (host logic only): the shapes measured fastest on
+    the benchmark layers."""
+    from paper_1704_04428_amd import workloads as wl
+    monkeypatch.delenv("CONV_MCMK_TILE", raising=False)
+    want = {
+        "cfg4_vgg_early": "tile 14x14, waves 4x2, channel split 1, 256 workgroups",
+        "cfg5a_vgg_deep56": "tile 14x14, waves 4x2, channel split 1, 512 workgroups",
+        "cfg5b_vgg_deep28": "tile 14x14, waves 4x2, channel split 1, 256 workgroups",
+        "cfg5c_vgg_deep14": "tile 14x14, waves 2x4, channel split 2, 256 workgroups",
+    }
+    for name, text in want.items():
+        L = wl.LAYERS[name]
+        plan = B.conv_mcmk_describe_plan(B.desc(L.n, L.c, L.h, L.w, L.m, L.k, L.pad), B.KN2ROW)
+        assert text in plan, (name, plan)
+    d = B.desc(1, 8, 10, 10, 8, 3, 1)
+    assert "shift-add" in B.conv_mcmk_describe_plan(d, B.KN2ROW_2PASS)
+    assert "patch matrix [72 x 100]" in B.conv_mcmk_describe_plan(d, B.IM2COL)
+    assert "800 outputs" in B.conv_mcmk_describe_plan(d, B.DIRECT)
+    with pytest.raises(B.ConvMcmkError):
+        B.conv_mcmk_describe_plan(B.desc(1, 8, 10, 10, 8, 3, 1, stride=2), B.KN2ROW)
+    monkeypatch.setenv("CONV_MCMK_TILE", "5")
+    assert "tile 16x16, waves 1x4, channel split 1" in B.conv_mcmk_describe_plan(d, B.KN2ROW)
