@@ -213,3 +213,41 @@ def test_runtime_errors_through_binding():
     with pytest.raises(B.ConvMcmkError) as e:
         B.conv_mcmk_kn2row(d, I[1:], K, O)
     assert e.value.code == B.ERR_ALIGN
+
+
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+@pytest.mark.parametrize("k,pad", [(1, 0), (3, 1), (5, 2), (7, 3)])
+def test_every_tile_shape_of_the_menu(k, pad, dtype, monkeypatch):
+    """The selector only ever launches the shape it prefers; force each of the 12 menu entries
+    (6 tile/wave shapes x channel split 1 and 2) so every instantiation is checked."""
+    from gpu_util import TOL_BF16
+    case = (2, 72, 33, 30, 80, k, pad)        # 5 (fp32) / 3 (bf16) channel chunks: an uneven split
+    n, c, h, w, m, _, _ = case
+    I = wl.uniform(600 + k, n * c * h * w, -1, 1).reshape(n, c, h, w)
+    K = wl.normal(601 + k, m * c * k * k, 0.5).reshape(m, c, k, k)
+    ref, absref = oracle.mcmk(I, K, pad)
+    tol = TOL_BF16 if dtype == B.BF16 else TOL_F32
+    for index in range(12):
+        announce("menu", "k", k, "dtype", dtype, "tile", index)
+        monkeypatch.setenv("CONV_MCMK_TILE", str(index))
+        got = run_variant(B.KN2ROW, I, K, pad, dtype=dtype)
+        assert_within_bound(got, ref, absref, tol, f"tile {index} k={k} dtype={dtype}")
+    monkeypatch.delenv("CONV_MCMK_TILE")
+
+
+@pytest.mark.parametrize("case", [
+    (1, 3, 600, 500, 8, 7, 3),        # large image, first-layer-like channel count
+    (1, 8, 9, 2000, 16, 3, 1),        # very wide, few rows
+    (1, 8, 2000, 9, 16, 3, 1),        # very tall
+    (4, 130, 20, 20, 300, 3, 1),      # many kernels, channels just past a chunk boundary
+    (1, 1, 40, 40, 1, 5, 2),          # one channel, one kernel
+])
+def test_stretched_shapes(case):
+    announce("stretched", case)
+    n, c, h, w, m, k, pad = case
+    I = wl.uniform(700 + c, n * c * h * w, -1, 1).reshape(n, c, h, w)
+    K = wl.normal(701 + c, m * c * k * k, 0.5).reshape(m, c, k, k)
+    ref, absref = oracle.mcmk(I, K, pad)
+    for name, variant in ALL:
+        got = run_variant(variant, I, K, pad)
+        assert_within_bound(got, ref, absref, TOL_F32, f"{name} {case}")
