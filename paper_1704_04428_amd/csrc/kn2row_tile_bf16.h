@@ -140,12 +140,12 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs 
         b_off[b] = (lane >> 4) * PLB + (pp / TW) * RSB + (pp % TW) * 16;
     }
 
-    // ---- A fragments.  A tap lasts only ~100 ns here, far less than an L2 round trip, so the
-    // fragments are fetched a whole chunk ahead (kernel sides 1 and 3) or a tap row ahead (5, 7):
-    // a ring of D registers whose slot for tap t is t % D -- static, because D divides the taps per
-    // chunk -- is refilled right after use with the fragment D taps further on.
+    // ---- A fragments, fetched one tap row ahead: a ring of D = KS registers whose slot for tap t is
+    // t % D -- static, because D divides the taps per chunk -- refilled right after use with the
+    // fragment D taps further on.  (A ring a whole chunk deep measured slower: it costs 24 more
+    // VGPRs in a kernel that is already register-bound.)
     constexpr int T = KS * KS;
-    constexpr int D = T <= 9 ? T : KS;
+    constexpr int D = KS;
     static_assert(T % D == 0, "ring slots must be static");
     const int nchunks = a.cg;
     const int chunk_lo = (int)((long long)nchunks * part / a.csplit);
