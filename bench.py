@@ -53,6 +53,13 @@ def time_calls(fn, steps, warmup):
     return wall_ms / steps, start.elapsed_time(stop) / steps
 
 
+def auto_counts(fn, warm_ms=60.0, timed_ms=120.0):
+    """Warm-up and step counts that give about `warm_ms` of warm-up and `timed_ms` of timed work."""
+    _, ms = time_calls(fn, 5, 2)
+    ms = max(ms, 1e-3)
+    return max(20, int(timed_ms / ms)), max(10, int(warm_ms / ms))
+
+
 def bench_layer(L, variants, steps, warmup, I_dev=None, K_dev=None, dtype=0):
     import torch
     from paper_1704_04428_amd import binding as B
@@ -71,7 +78,11 @@ def bench_layer(L, variants, steps, warmup, I_dev=None, K_dev=None, dtype=0):
         variant = B.VARIANTS[name]
         plan = B.Plan(d, variant, K_dev)
         torch.cuda.synchronize()
-        wall_ms, dev_ms = time_calls(lambda: plan.run(I_dev), steps, warmup)
+        if steps is None:
+            n_steps, n_warm = auto_counts(lambda: plan.run(I_dev))
+        else:
+            n_steps, n_warm = steps, warmup
+        wall_ms, dev_ms = time_calls(lambda: plan.run(I_dev), n_steps, n_warm)
         out[name] = {
             "ms": round(dev_ms, 5),
             "gflops": round(L.flops / (dev_ms * 1e-3) / 1e9, 1),
@@ -101,8 +112,10 @@ def cpu_baseline(L, I, K, budget_s=12.0, max_passes=40):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    # the GPU needs some tens of milliseconds under load to reach its steady clock: 300 warm-up steps
+    # of the default workload are about 70 ms, 1000 timed steps about a quarter of a second
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--variant", default="kn2row", choices=["kn2row", "kn2row_2pass", "im2col", "direct"],
                     help="which entry point the timed steps call (the headline is kn2row)")
@@ -188,14 +201,14 @@ def main():
         table = {}
         for name, layer in wl.LAYERS.items():
             variants = ["kn2row", "im2col", "kn2row_2pass"] + (["direct"] if layer.flops < 5e9 else [])
-            steps = 50 if layer.flops > 1e9 else 200
+            steps = None          # enough launches for ~60 ms of warm-up and ~120 ms of timed work
             same = name == L.name
-            table[name] = bench_layer(layer, variants, steps, 5, I_dev if same else None, K_dev if same else None)
+            table[name] = bench_layer(layer, variants, steps, None, I_dev if same else None, K_dev if same else None)
             r = table[name]
             r["kn2row_over_im2col_time"] = round(r["kn2row"]["ms"] / r["im2col"]["ms"], 4)
             r["frac_f32_mfma_peak"] = round(r["kn2row"]["gflops"] / 1e3 / PEAK_F32_MFMA_TFLOPS, 4)
             if name.startswith("cfg5"):          # the deep-layer sweep is also quoted with bf16 operands
-                b = bench_layer(layer, ["kn2row", "im2col", "kn2row_2pass"], steps, 5,
+                b = bench_layer(layer, ["kn2row", "im2col", "kn2row_2pass"], steps, None,
                                 I_dev if same else None, K_dev if same else None, dtype=B.BF16)
                 b["frac_bf16_mfma_peak"] = round(b["kn2row"]["gflops"] / 1e3 / PEAK_BF16_MFMA_TFLOPS, 4)
                 r["bf16"] = b
