@@ -56,7 +56,9 @@ enum {
     CONV_MCMK_KN2ROW_2PASS = 1, /* section III-A as written: one GEMM [k*k*M x C].[C x HW] into the
                                    workspace, then the shift-add post pass */
     CONV_MCMK_IM2COL       = 2, /* section II-B: build the column matrix in the workspace, then one GEMM */
-    CONV_MCMK_DIRECT       = 3  /* the loop nest of Eq. 1-3, one output element per thread, no matrix cores */
+    CONV_MCMK_DIRECT       = 3, /* the loop nest of Eq. 1-3, one output element per thread, no matrix cores */
+    CONV_MCMK_KN2COL       = 4  /* section III-A, last paragraph: kn2row with the channel innermost in the input
+                                   and in the output (I[N][H][W][C], O[N][Q][P][M]); shift-add fused as in KN2ROW */
 };
 
 enum {
@@ -84,7 +86,7 @@ int conv_mcmk_check(const conv_mcmk_desc *desc, int variant);
 int conv_mcmk_describe_plan(const conv_mcmk_desc *desc, int variant, char *buf, size_t n);
 
 /*
- * Bytes of caller-provided scratch a variant needs (0 for KN2ROW and DIRECT; 0 also for an invalid
+ * Bytes of caller-provided scratch a variant needs (0 for KN2ROW, KN2COL and DIRECT; 0 also for an invalid
  * desc -- use conv_mcmk_check for the reason).
  *   KN2ROW_2PASS: N * k*k*M * H*W floats -- the GEMM result of section III-A, per image
  *                 T[t*M + m][y*W + x], t = i*k + j ("some increase in the size of the output").
@@ -112,7 +114,7 @@ size_t conv_mcmk_packed_kernel_bytes(const conv_mcmk_desc *desc, int variant);
 /*
  * Re-order K (device, float, [M][C][k][k]) into Kp (device, conv_mcmk_packed_kernel_bytes() bytes)
  * for `variant`; converts to bfloat16 when desc->dtype is CONV_MCMK_BF16.  Done once per layer and
- * not part of the timed convolution (section III-A).  The KN2ROW and KN2ROW_2PASS packings are identical.
+ * not part of the timed convolution (section III-A).  The KN2ROW, KN2ROW_2PASS and KN2COL packings are identical.
  */
 int conv_mcmk_prepack(const conv_mcmk_desc *desc, int variant, const void *K_dev, void *Kp_dev, void *stream);
 
@@ -135,6 +137,18 @@ int conv_mcmk_kn2row_2pass(const conv_mcmk_desc *desc, const void *I_dev, const 
 int conv_mcmk_im2col(const conv_mcmk_desc *desc, const void *I_dev, const void *Kp_dev, void *O_dev,
                      void *ws, size_t ws_bytes, void *stream);
 int conv_mcmk_direct(const conv_mcmk_desc *desc, const void *I_dev, const void *K_dev, void *O_dev,
+                     void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * kn2col (section III-A, last paragraph): the same sum of k*k 1x1 products with the layouts swapped so
+ * that the channel is the innermost dimension -- the GEMM becomes [H*W x C] . [C x k*k*M].
+ *   I_dev   input  I[N][H][W][C]  (float, or bfloat16 with C a multiple of 8)
+ *   Kp_dev  conv_mcmk_prepack(desc, CONV_MCMK_KN2COL): physically the KN2ROW packing (the matrix-core
+ *           operand order does not care which of the two GEMM operands the kernel matrix is called)
+ *   O_dev   output O[N][Q][P][M], float
+ * No workspace; k = 1, 3, 5, 7; otherwise as conv_mcmk_kn2row.
+ */
+int conv_mcmk_kn2col(const conv_mcmk_desc *desc, const void *I_dev, const void *Kp_dev, void *O_dev,
                      void *ws, size_t ws_bytes, void *stream);
 
 /* float -> bfloat16 (round to nearest even), `count` elements, device to device. */

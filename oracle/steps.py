@@ -104,6 +104,44 @@ def kn2row_mcmk(I, K, pad):
     return shift_add(kn2row_gemm(I, K), m, h, w, k, pad)
 
 
+# ---------------------------------------------------------------- kn2col (section III-A, last paragraph)
+
+def kn2col_kernel_matrix(K):
+    """The kernel matrix with the dimensions swapped: [C] x [k*k*M], column t*M + m."""
+    return np.ascontiguousarray(kn2row_kernel_matrix(K).T)
+
+
+def kn2col_gemm(I_hwc, K):
+    """[H*W] x [C] (channel innermost input, I[H][W][C]) times [C] x [k*k*M] gives [H*W] x [k*k*M]."""
+    I_hwc = _f64(I_hwc)
+    h, w, c = I_hwc.shape
+    return np.matmul(I_hwc.reshape(h * w, c), kn2col_kernel_matrix(K))
+
+
+def shift_add_channels_last(T, m, h, w, k, pad):
+    """The same post pass on the channel-innermost product T ([H*W] x [k*k*M]): O[Q][P][M]."""
+    T = _f64(T).reshape(h, w, k * k, m)
+    q_out, p_out = h + 2 * pad - k + 1, w + 2 * pad - k + 1
+    O = np.zeros((q_out, p_out, m), dtype=np.float64)
+    for i in range(k):
+        for j in range(k):
+            di, dj = i - pad, j - pad
+            q0, q1 = max(0, -di), min(q_out, h - di)
+            p0, p1 = max(0, -dj), min(p_out, w - dj)
+            if q0 >= q1 or p0 >= p1:
+                continue
+            O[q0:q1, p0:p1, :] += T[q0 + di:q1 + di, p0 + dj:p1 + dj, i * k + j, :]
+    return O
+
+
+def kn2col_mcmk(I_hwc, K, pad):
+    """kn2col: input I[H][W][C], kernels K[M][C][k][k], output O[Q][P][M]."""
+    K = _f64(K)
+    m, _, k, _ = K.shape
+    h, w, _ = np.shape(I_hwc)
+    return shift_add_channels_last(kn2col_gemm(I_hwc, K), m, h, w, k, pad)
+
+
 # ---------------------------------------------------------------- bf16 rounding
 
 def round_to_bf16_bits(x):

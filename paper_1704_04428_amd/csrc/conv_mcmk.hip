@@ -41,8 +41,11 @@ int validate(const conv_mcmk_desc *d, int variant, Dims *out)
     if (d->dtype != CONV_MCMK_F32 && d->dtype != CONV_MCMK_BF16) return CONV_MCMK_ERR_UNSUPPORTED;
     switch (variant) {
     case CONV_MCMK_KN2ROW:
+    case CONV_MCMK_KN2COL:
         if (d->k != 1 && d->k != 3 && d->k != 5 && d->k != 7) return CONV_MCMK_ERR_UNSUPPORTED;
         if (d->pad > 65535) return CONV_MCMK_ERR_SHAPE;
+        // channels-last bf16 input is read in aligned 16-byte channel octets
+        if (variant == CONV_MCMK_KN2COL && d->dtype == CONV_MCMK_BF16 && d->c % 8 != 0) return CONV_MCMK_ERR_UNSUPPORTED;
         break;
     case CONV_MCMK_KN2ROW_2PASS:
     case CONV_MCMK_IM2COL:
@@ -109,7 +112,7 @@ int run_tile(int dtype, int ks, const TileRequest &rq)
 // (ks = 1 over a 1 x cols image, row_groups row planes of m rows each).
 int launch_tile(const conv_mcmk_desc *d, const Dims &dm, int ks, int shape, int csplit, const void *in,
                 const void *apk, float *out, int in_c, int in_h, int in_w, int out_q, int out_p, int pad,
-                int row_groups, hipStream_t st)
+                int row_groups, hipStream_t st, bool channels_last = false)
 {
     TileRequest rq;
     TileArgs &a = rq.args;
@@ -123,6 +126,7 @@ int launch_tile(const conv_mcmk_desc *d, const Dims &dm, int ks, int shape, int 
     a.tiles_x = a.tiles_y = a.row_tiles = 0;
     a.csplit = csplit;
     rq.shape = shape;
+    rq.channels_last = channels_last;
     rq.stream = st;
     if (csplit > 1) {
         // partial sums are added into the output, so it starts from zero (a fill kernel, not a
@@ -190,10 +194,11 @@ Candidate choose_fused(const conv_mcmk_desc *d, const Dims &dm)
 }
 
 int launch_fused(const conv_mcmk_desc *d, const Dims &dm, const void *in, const void *apk, float *out,
-                 hipStream_t st)
+                 hipStream_t st, bool channels_last)
 {
     const Candidate best = choose_fused(d, dm);
-    return launch_tile(d, dm, d->k, best.shape, best.csplit, in, apk, out, d->c, d->h, d->w, dm.q, dm.p, d->pad, 1, st);
+    return launch_tile(d, dm, d->k, best.shape, best.csplit, in, apk, out, d->c, d->h, d->w, dm.q, dm.p, d->pad, 1, st,
+                       channels_last);
 }
 
 // Plain GEMM [rows x kc] . [kc x cols] per image on the same tile kernel: a 1x1 "convolution" over a
@@ -250,11 +255,13 @@ int conv_mcmk_describe_plan(const conv_mcmk_desc *d, int variant, char *buf, siz
     const char *type = d->dtype == CONV_MCMK_BF16 ? "bf16" : "f32";
     const TileShapeDesc &g = kTileShapes[kGemmShape];
     switch (variant) {
-    case CONV_MCMK_KN2ROW: {
+    case CONV_MCMK_KN2ROW:
+    case CONV_MCMK_KN2COL: {
         const Candidate c = choose_fused(d, dm);
         const long long wgs = (long long)d->n * ceil_div(dm.p, c.tw) * ceil_div(dm.q, c.th) * ceil_div(dm.mb, c.wm) * c.csplit;
-        snprintf(buf, n, "kn2row fused %s: tile %dx%d, waves %dx%d, channel split %d, %lld workgroups, est %.1f us",
-                 type, c.th, c.tw, c.wm, c.wp, c.csplit, wgs, tile_cost(d, dm, c, d->k));
+        snprintf(buf, n, "%s fused %s: tile %dx%d, waves %dx%d, channel split %d, %lld workgroups, est %.1f us",
+                 variant == CONV_MCMK_KN2COL ? "kn2col" : "kn2row", type, c.th, c.tw, c.wm, c.wp, c.csplit, wgs,
+                 tile_cost(d, dm, c, d->k));
         break;
     }
     case CONV_MCMK_KN2ROW_2PASS:
@@ -293,6 +300,7 @@ size_t conv_mcmk_packed_kernel_bytes(const conv_mcmk_desc *d, int variant)
     switch (variant) {
     case CONV_MCMK_KN2ROW:
     case CONV_MCMK_KN2ROW_2PASS:
+    case CONV_MCMK_KN2COL:
         return (size_t)dm.taps * dm.mb * ceil_div(d->c, group) * 16 * group * elt;
     case CONV_MCMK_IM2COL:
         return (size_t)dm.mb * ceil_div((long long)d->c * dm.taps, group) * 16 * group * elt;
@@ -334,7 +342,18 @@ int conv_mcmk_kn2row(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_
     int rc = validate(d, CONV_MCMK_KN2ROW, &dm);
     if (rc) return rc;
     if ((rc = common_ptr_checks(I_dev, Kp_dev, O_dev))) return rc;
-    return launch_fused(d, dm, I_dev, Kp_dev, static_cast<float *>(O_dev), static_cast<hipStream_t>(stream));
+    return launch_fused(d, dm, I_dev, Kp_dev, static_cast<float *>(O_dev), static_cast<hipStream_t>(stream), false);
+}
+
+int conv_mcmk_kn2col(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_dev, void *O_dev,
+                     void *ws, size_t ws_bytes, void *stream)
+{
+    (void)ws; (void)ws_bytes;
+    Dims dm;
+    int rc = validate(d, CONV_MCMK_KN2COL, &dm);
+    if (rc) return rc;
+    if ((rc = common_ptr_checks(I_dev, Kp_dev, O_dev))) return rc;
+    return launch_fused(d, dm, I_dev, Kp_dev, static_cast<float *>(O_dev), static_cast<hipStream_t>(stream), true);
 }
 
 int conv_mcmk_kn2row_2pass(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_dev, void *O_dev,

@@ -63,7 +63,11 @@ struct TileShape {
     static constexpr size_t kLdsBytes = 2 * (size_t)kBuf * sizeof(float);
 };
 
-template <int KS, int TH, int TW, int WM, int WP, int CCH = 16>
+// CL = false: input [n][c][h][w], output [n][rows][q][p] (kn2row).
+// CL = true : channels last, input [n][h][w][c], output [n][q][p][rows] -- the layout of the paper's
+//             kn2col variant (section III-A, last paragraph); the packed kernel and the whole
+//             accumulation are the same, only the staging gather and the final store differ.
+template <int KS, int TH, int TW, int WM, int WP, int CCH = 16, bool CL = false>
 __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a)
 {
     using S = TileShape<KS, TH, TW, WM, WP, CCH>;
@@ -140,19 +144,49 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a
 
     float stage[SLOTS];
     auto load_chunk = [&](int chunk) {
+        if constexpr (CL) {
+            // channels last: element e = tid + s*NT is (channel e % CC, position e / CC), so a wave
+            // reads whole 64-byte channel runs.  The offsets are recomputed per chunk (an opaque
+            // copy of tid keeps the compiler from hoisting them into SLOTS more live registers).
+            int t = tid;
+            asm volatile("" : "+v"(t));
 #pragma unroll
-        for (int s = 0; s < SLOTS; ++s) {
-            const uint32_t off = kRegular ? g_off[0] + (uint32_t)(s * CSTEP) * (uint32_t)(plane * sizeof(float))
-                                          : g_off[kRegular ? 0 : s];
-            stage[s] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                in_rsrc, (int)(off + (uint32_t)chunk * chunk_bytes), 0, 0));
+            for (int s = 0; s < SLOTS; ++s) {
+                const int e = t + s * NT;
+                const int cl = e % CC, pos = e / CC;
+                const int r = pos / WT, col = pos % WT;
+                const int gy = y0 - a.pad + r, gx = x0 - a.pad + col;
+                const int ch = chunk * CC + cl;
+                const bool ok = e < CC * POS && gy >= 0 && gy < a.h && gx >= 0 && gx < a.w && ch < a.c;
+                const uint32_t off = ok ? (uint32_t)((((size_t)gy * a.w + gx) * a.c + ch) * sizeof(float)) : 0x80000000u;
+                stage[s] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(in_rsrc, (int)off, 0, 0));
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < SLOTS; ++s) {
+                const uint32_t off = kRegular ? g_off[0] + (uint32_t)(s * CSTEP) * (uint32_t)(plane * sizeof(float))
+                                              : g_off[kRegular ? 0 : s];
+                stage[s] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                    in_rsrc, (int)(off + (uint32_t)chunk * chunk_bytes), 0, 0));
+            }
         }
     };
     auto store_chunk = [&](float *buf) {
+        if constexpr (CL) {
+            int t = tid;
+            asm volatile("" : "+v"(t));
 #pragma unroll
-        for (int s = 0; s < SLOTS; ++s) {
-            if (kRegular) buf[l_off[0] + s * CSTEP * CHS] = stage[s];
-            else if (l_off[kRegular ? 0 : s] >= 0) buf[l_off[kRegular ? 0 : s]] = stage[s];
+            for (int s = 0; s < SLOTS; ++s) {
+                const int e = t + s * NT;
+                const int cl = e % CC, pos = e / CC;
+                if (e < CC * POS) buf[cl * CHS + (pos / WT) * WT + (pos % WT)] = stage[s];
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < SLOTS; ++s) {
+                if (kRegular) buf[l_off[0] + s * CSTEP * CHS] = stage[s];
+                else if (l_off[kRegular ? 0 : s] >= 0) buf[l_off[kRegular ? 0 : s]] = stage[s];
+            }
         }
     };
 
@@ -267,13 +301,29 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a
         const int pp = (first_pb + b) * 16 + (lane & 15);
         const int y = y0 + pp / TW, x = x0 + pp % TW;
         if (pp >= TH * TW || y >= a.q || x >= a.p) continue;
+        const int mrow0 = mbi * 16 + 4 * (lane >> 4);
+        if constexpr (CL) {
+            // channels last: the lane's four rows are four consecutive floats of one output position
+            float *dst = out_img + ((size_t)y * a.p + x) * out_rows + (size_t)grp * a.m + mrow0;
+            if (a.csplit == 1 && (out_rows & 3) == 0 && mrow0 + 3 < a.m) {
+                *reinterpret_cast<f32x4 *>(dst) = acc[b];
+            } else {
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int mrow = mbi * 16 + 4 * (lane >> 4) + v;
-            if (mrow >= a.m) continue;
-            float *dst = out_img + (size_t)(grp * a.m + mrow) * oplane + (size_t)y * a.p + x;
-            if (a.csplit == 1) *dst = acc[b][v];
-            else unsafeAtomicAdd(dst, acc[b][v]);      // hardware fp32 add at the L2
+                for (int v = 0; v < 4; ++v) {
+                    if (mrow0 + v >= a.m) continue;
+                    if (a.csplit == 1) dst[v] = acc[b][v];
+                    else unsafeAtomicAdd(dst + v, acc[b][v]);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int mrow = mrow0 + v;
+                if (mrow >= a.m) continue;
+                float *dst = out_img + (size_t)(grp * a.m + mrow) * oplane + (size_t)y * a.p + x;
+                if (a.csplit == 1) *dst = acc[b][v];
+                else unsafeAtomicAdd(dst, acc[b][v]);      // hardware fp32 add at the L2
+            }
         }
     }
 }

@@ -48,7 +48,10 @@ struct TileShapeBf16 {
 };
 
 // TileArgs is shared with the fp32 kernel; `in` and `apk` point at bf16 data, cg counts 32-channel groups.
-template <int KS, int TH, int TW, int WM, int WP>
+// CL = true: channels last (input [n][h][w][c], output [n][q][p][rows], the kn2col layout); needs
+// c % 8 == 0 so that a channel octet of one position is one aligned 16-byte load -- the staging
+// transpose disappears.
+template <int KS, int TH, int TW, int WM, int WP, bool CL = false>
 __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs a)
 {
     using S = TileShapeBf16<KS, TH, TW, WM, WP>;
@@ -110,22 +113,52 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs 
         l_off[s] = used ? oct * PLB + r * RSB + col * 16 : -1;
     }
 
-    uint16_t stage[SLOTS][8];
+    uint16_t stage[SLOTS][8];      // channels first: eight 2-byte gathers per item
+    u32x4 stage_cl[SLOTS];         // channels last: one 16-byte load per item
     auto load_chunk = [&](int chunk) {
+        if constexpr (CL) {
+            // item e = tid + s*NT is (channel octet e % 4, position e / 4): 4 lanes read one 64-byte run
+            int t = tid;
+            asm volatile("" : "+v"(t));
 #pragma unroll
-        for (int s = 0; s < SLOTS; ++s)
+            for (int s = 0; s < SLOTS; ++s) {
+                const int e = t + s * NT;
+                const int oct = e % 4, pos = e / 4;
+                const int r = pos / WT, col = pos % WT;
+                const int gy = y0 - a.pad + r, gx = x0 - a.pad + col;
+                const int ch = chunk * CC + oct * 8;
+                const bool ok = e < S::kItems && gy >= 0 && gy < a.h && gx >= 0 && gx < a.w && ch < a.c;
+                const uint32_t off = ok ? (uint32_t)((((size_t)gy * a.w + gx) * a.c + ch) * sizeof(uint16_t)) : 0x80000000u;
+                stage_cl[s] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(in_rsrc, (int)off, 0, 0));
+            }
+        } else {
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                stage[s][e] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(
-                    in_rsrc, (int)(g_off[s] + (uint32_t)e * plane_bytes + (uint32_t)chunk * chunk_bytes), 0, 0);
+            for (int s = 0; s < SLOTS; ++s)
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    stage[s][e] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(
+                        in_rsrc, (int)(g_off[s] + (uint32_t)e * plane_bytes + (uint32_t)chunk * chunk_bytes), 0, 0);
+        }
     };
     auto store_chunk = [&](unsigned char *buf) {
+        if constexpr (CL) {
+            int t = tid;
+            asm volatile("" : "+v"(t));
 #pragma unroll
-        for (int s = 0; s < SLOTS; ++s) {
-            u32x4 v;
+            for (int s = 0; s < SLOTS; ++s) {
+                const int e = t + s * NT;
+                const int oct = e % 4, pos = e / 4;
+                if (e < S::kItems)
+                    *reinterpret_cast<u32x4 *>(buf + oct * PLB + (pos / WT) * RSB + (pos % WT) * 16) = stage_cl[s];
+            }
+        } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = (uint32_t)stage[s][2 * e] | ((uint32_t)stage[s][2 * e + 1] << 16);
-            if (l_off[s] >= 0) *reinterpret_cast<u32x4 *>(buf + l_off[s]) = v;
+            for (int s = 0; s < SLOTS; ++s) {
+                u32x4 v;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = (uint32_t)stage[s][2 * e] | ((uint32_t)stage[s][2 * e + 1] << 16);
+                if (l_off[s] >= 0) *reinterpret_cast<u32x4 *>(buf + l_off[s]) = v;
+            }
         }
     };
 
@@ -217,13 +250,28 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs 
         const int pp = (first_pb + b) * 16 + (lane & 15);
         const int y = y0 + pp / TW, x = x0 + pp % TW;
         if (pp >= TH * TW || y >= a.q || x >= a.p) continue;
+        const int mrow0 = mbi * 16 + 4 * (lane >> 4);
+        if constexpr (CL) {
+            float *dst = out_img + ((size_t)y * a.p + x) * out_rows + (size_t)grp * a.m + mrow0;
+            if (a.csplit == 1 && (out_rows & 3) == 0 && mrow0 + 3 < a.m) {
+                *reinterpret_cast<f32x4 *>(dst) = acc[b];
+            } else {
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int mrow = mbi * 16 + 4 * (lane >> 4) + v;
-            if (mrow >= a.m) continue;
-            float *dst = out_img + (size_t)(grp * a.m + mrow) * oplane + (size_t)y * a.p + x;
-            if (a.csplit == 1) *dst = acc[b][v];
-            else unsafeAtomicAdd(dst, acc[b][v]);
+                for (int v = 0; v < 4; ++v) {
+                    if (mrow0 + v >= a.m) continue;
+                    if (a.csplit == 1) dst[v] = acc[b][v];
+                    else unsafeAtomicAdd(dst + v, acc[b][v]);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int mrow = mrow0 + v;
+                if (mrow >= a.m) continue;
+                float *dst = out_img + (size_t)(grp * a.m + mrow) * oplane + (size_t)y * a.p + x;
+                if (a.csplit == 1) *dst = acc[b][v];
+                else unsafeAtomicAdd(dst, acc[b][v]);
+            }
         }
     }
 }

@@ -22,6 +22,7 @@ constexpr int kGemmShape = 6;
 struct TileRequest {
     TileArgs args;       // tiles_x, tiles_y and row_tiles are filled in by the launcher
     int shape;           // index into kTileShapes
+    bool channels_last;  // input [n][h][w][c], output [n][q][p][rows] (kn2col); convolution shapes only
     hipStream_t stream;
 };
 

@@ -10,7 +10,7 @@
 namespace mcmk {
 namespace {
 
-template <int TH, int TW, int WM, int WP, int CCH = 16>
+template <int TH, int TW, int WM, int WP, int CCH = 16, bool CL = false>
 int launch_shape(const TileRequest &rq)
 {
     TileArgs a = rq.args;
@@ -27,17 +27,17 @@ int launch_shape(const TileRequest &rq)
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 1;
         if (!allowed[dev]) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&kn2row_tile_bf16<MCMK_KS, TH, TW, WM, WP>),
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&kn2row_tile_bf16<MCMK_KS, TH, TW, WM, WP, CL>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::kLdsBytes) != hipSuccess)
                 return 1;
             allowed[dev] = true;
         }
     }
-    hipLaunchKernelGGL((kn2row_tile_bf16<MCMK_KS, TH, TW, WM, WP>), dim3((unsigned)blocks), dim3(S::kThreads),
+    hipLaunchKernelGGL((kn2row_tile_bf16<MCMK_KS, TH, TW, WM, WP, CL>), dim3((unsigned)blocks), dim3(S::kThreads),
                        S::kLdsBytes, rq.stream, a);
 #else
     using S = TileShape<MCMK_KS, TH, TW, WM, WP, CCH>;
-    hipLaunchKernelGGL((kn2row_tile_f32<MCMK_KS, TH, TW, WM, WP, CCH>), dim3((unsigned)blocks), dim3(S::kThreads),
+    hipLaunchKernelGGL((kn2row_tile_f32<MCMK_KS, TH, TW, WM, WP, CCH, CL>), dim3((unsigned)blocks), dim3(S::kThreads),
                        S::kLdsBytes, rq.stream, a);
 #endif
     return hipGetLastError() == hipSuccess ? 0 : 1;
@@ -55,6 +55,17 @@ int launch_shape(const TileRequest &rq)
 
 int MCMK_FN(const TileRequest &rq)
 {
+    if (rq.channels_last) {
+        switch (rq.shape) {
+        case 0: return launch_shape<14, 14, 4, 2, 16, true>(rq);
+        case 1: return launch_shape<14, 14, 2, 4, 16, true>(rq);
+        case 2: return launch_shape<14, 14, 1, 4, 16, true>(rq);
+        case 3: return launch_shape<16, 16, 4, 2, 16, true>(rq);
+        case 4: return launch_shape<16, 16, 2, 4, 16, true>(rq);
+        case 5: return launch_shape<16, 16, 1, 4, 16, true>(rq);
+        default: return 2;
+        }
+    }
     switch (rq.shape) {
     case 0: return launch_shape<14, 14, 4, 2>(rq);
     case 1: return launch_shape<14, 14, 2, 4>(rq);

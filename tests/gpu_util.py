@@ -43,6 +43,9 @@ def run_variant(variant, I, K, pad, dtype=B.F32, return_ws=False):
         raise B.ConvMcmkError(rc, B.strerror(rc))
     q, p = h + 2 * pad - k + 1, w + 2 * pad - k + 1
     dev = torch.device("cuda:0")
+    channels_last = variant == B.KN2COL
+    if channels_last:
+        I = I.transpose(0, 2, 3, 1)                      # the library sees I[N][H][W][C]
     I_dev = torch.from_numpy(np.ascontiguousarray(I)).to(dev)
     K_dev = torch.from_numpy(np.ascontiguousarray(K)).to(dev)
     if dtype == B.BF16:
@@ -65,7 +68,10 @@ def run_variant(variant, I, K, pad, dtype=B.F32, return_ws=False):
         assert ws.intact(), "workspace guard band overwritten"
     if variant != B.DIRECT:
         assert kp.intact(), "packed-kernel guard band overwritten"
-    O = out.payload.view(torch.float32).reshape(n, m, q, p).cpu().numpy()
+    if channels_last:                                    # O[N][Q][P][M] back to the oracle's [N][M][Q][P]
+        O = np.ascontiguousarray(out.payload.view(torch.float32).reshape(n, q, p, m).cpu().numpy().transpose(0, 3, 1, 2))
+    else:
+        O = out.payload.view(torch.float32).reshape(n, m, q, p).cpu().numpy()
     if return_ws:
         return O, (ws.payload.cpu().numpy() if ws is not None else None)
     return O

@@ -42,7 +42,7 @@ def test_check_accepts_benchmark_layers(lib):
     from paper_1704_04428_amd import workloads as wl
     for L in wl.LAYERS.values():
         d = B.desc(L.n, L.c, L.h, L.w, L.m, L.k, L.pad)
-        for v in (B.KN2ROW, B.KN2ROW_2PASS, B.IM2COL, B.DIRECT):
+        for v in (B.KN2ROW, B.KN2ROW_2PASS, B.IM2COL, B.DIRECT, B.KN2COL):
             assert B.conv_mcmk_check(d, v) == B.OK, (L.name, v)
 
 
@@ -58,6 +58,10 @@ def test_check_rejects_bad_descriptors(lib):
     assert B.conv_mcmk_check(B.desc(**ok), 9) == B.ERR_UNSUPPORTED
     assert B.conv_mcmk_check(B.desc(**dict(ok, k=4)), B.KN2ROW) == B.ERR_UNSUPPORTED             # fused: k in 1,3,5,7
     assert B.conv_mcmk_check(B.desc(**dict(ok, k=4)), B.KN2ROW_2PASS) == B.OK
+    assert B.conv_mcmk_check(B.desc(**dict(ok, k=4)), B.KN2COL) == B.ERR_UNSUPPORTED
+    assert B.conv_mcmk_check(B.desc(**dict(ok, c=12), dtype=B.BF16), B.KN2COL) == B.ERR_UNSUPPORTED   # octets
+    assert B.conv_mcmk_check(B.desc(**dict(ok, c=16), dtype=B.BF16), B.KN2COL) == B.OK
+    assert B.conv_mcmk_check(B.desc(**dict(ok, c=12)), B.KN2COL) == B.OK
     assert B.conv_mcmk_check(B.desc(**dict(ok, h=70000, w=70000)), B.DIRECT) == B.ERR_SHAPE      # >= 2^31 per image
     assert lib.conv_mcmk_check(None, B.KN2ROW) == B.ERR_NULL
 
@@ -72,6 +76,8 @@ def test_sizes(lib):
     mb, cg = 3, 2      # ceil(35/16), ceil(20/16)
     assert B.conv_mcmk_packed_kernel_bytes(d, B.KN2ROW) == 9 * mb * cg * 256 * 4
     assert B.conv_mcmk_packed_kernel_bytes(d, B.KN2ROW_2PASS) == 9 * mb * cg * 256 * 4
+    assert B.conv_mcmk_packed_kernel_bytes(d, B.KN2COL) == 9 * mb * cg * 256 * 4
+    assert B.conv_mcmk_workspace_bytes(d, B.KN2COL) == 0
     assert B.conv_mcmk_packed_kernel_bytes(d, B.IM2COL) == mb * 12 * 256 * 4              # ceil(180/16) = 12
     assert B.conv_mcmk_packed_kernel_bytes(d, B.DIRECT) == 0
     assert B.conv_mcmk_workspace_bytes(B.desc(0, 1, 1, 1, 1, 1, 0), B.IM2COL) == 0
@@ -89,7 +95,8 @@ def test_compute_calls_validate_before_launch(lib):
     import ctypes
     d = B.desc(1, 4, 8, 8, 4, 3, 1)
     null = ctypes.c_void_p(0)
-    for name in ("conv_mcmk_kn2row", "conv_mcmk_kn2row_2pass", "conv_mcmk_im2col", "conv_mcmk_direct"):
+    for name in ("conv_mcmk_kn2row", "conv_mcmk_kn2row_2pass", "conv_mcmk_im2col", "conv_mcmk_direct",
+                 "conv_mcmk_kn2col"):
         fn = getattr(lib, name)
         assert fn(ctypes.byref(d), null, null, null, null, 0, null) == B.ERR_NULL
         bad = B.desc(1, 4, 8, 8, 4, 3, 1, stride=2)

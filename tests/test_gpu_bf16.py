@@ -19,6 +19,10 @@ from gpu_util import TOL_BF16, TOL_F32, announce, assert_within_bound, run_varia
 pytestmark = pytest.mark.gpu
 
 MFMA = [("kn2row", B.KN2ROW), ("kn2row_2pass", B.KN2ROW_2PASS), ("im2col", B.IM2COL)]
+KN2COL_CASES = [           # channels-last bf16 needs C % 8 == 0
+    (1, 16, 32, 32, 16, 3, 1), (2, 24, 17, 19, 35, 3, 1), (1, 40, 30, 9, 7, 5, 2), (1, 8, 15, 15, 18, 1, 0),
+    (1, 72, 20, 21, 9, 7, 3), (2, 64, 28, 28, 48, 5, 2),
+]
 
 CASES = [
     (1, 16, 32, 32, 16, 3, 1),
@@ -55,7 +59,19 @@ def test_bf16_matches_oracle(name, variant, case):
     assert_within_bound(got, ref_r, abs_r, TOL_F32, f"bf16 {name} {case} vs rounded inputs")
 
 
-@pytest.mark.parametrize("name,variant", MFMA)
+@pytest.mark.parametrize("case", KN2COL_CASES)
+def test_bf16_kn2col_matches_oracle(case):
+    announce("bf16 kn2col", case)
+    I, K = _inputs(case, 3500 + sum(case))
+    pad = case[-1]
+    got = run_variant(B.KN2COL, I, K, pad, dtype=B.BF16)
+    ref, absref = oracle.mcmk(I, K, pad)
+    assert_within_bound(got, ref, absref, TOL_BF16, f"bf16 kn2col {case} vs fp32 inputs")
+    ref_r, abs_r = oracle.mcmk(steps.round_to_bf16(I), steps.round_to_bf16(K), pad)
+    assert_within_bound(got, ref_r, abs_r, TOL_F32, f"bf16 kn2col {case} vs rounded inputs")
+
+
+@pytest.mark.parametrize("name,variant", MFMA + [("kn2col", B.KN2COL)])
 def test_bf16_integer_data_is_bit_exact(name, variant):
     case = (2, 40, 17, 19, 35, 3, 1)
     announce("bf16 exact-int", name, case)
@@ -116,7 +132,7 @@ def test_bf16_im2col_workspace_holds_the_rounded_patch_matrix():
         np.testing.assert_array_equal(cols[i], want.reshape(cols[i].shape))
 
 
-@pytest.mark.parametrize("name,variant", MFMA)
+@pytest.mark.parametrize("name,variant", MFMA + [("kn2col", B.KN2COL)])
 @pytest.mark.parametrize("layer", ["cfg5a_vgg_deep56", "cfg5b_vgg_deep28", "cfg5c_vgg_deep14"])
 def test_bf16_full_size_sampled(layer, name, variant):
     L = wl.LAYERS[layer]

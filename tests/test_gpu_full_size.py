@@ -12,7 +12,8 @@ from gpu_util import TOL_F32, announce, assert_within_bound, run_variant
 
 pytestmark = pytest.mark.gpu
 
-VARIANTS = [("kn2row", B.KN2ROW), ("kn2row_2pass", B.KN2ROW_2PASS), ("im2col", B.IM2COL), ("direct", B.DIRECT)]
+VARIANTS = [("kn2row", B.KN2ROW), ("kn2row_2pass", B.KN2ROW_2PASS), ("im2col", B.IM2COL), ("direct", B.DIRECT),
+            ("kn2col", B.KN2COL)]
 
 
 @pytest.mark.parametrize("name,variant", VARIANTS)

@@ -15,7 +15,8 @@ from gpu_util import TOL_F32, announce, assert_within_bound, run_variant
 
 pytestmark = pytest.mark.gpu
 
-ALL = [("kn2row", B.KN2ROW), ("kn2row_2pass", B.KN2ROW_2PASS), ("im2col", B.IM2COL), ("direct", B.DIRECT)]
+ALL = [("kn2row", B.KN2ROW), ("kn2row_2pass", B.KN2ROW_2PASS), ("im2col", B.IM2COL), ("direct", B.DIRECT),
+       ("kn2col", B.KN2COL)]
 
 # (n, c, h, w, m, k, pad): several tiles, ragged tails in every dimension, degenerate sizes
 SMALL = [
@@ -53,7 +54,7 @@ def test_small_shapes_match_oracle(name, variant, case):
     assert_within_bound(got, ref, absref, TOL_F32, f"{name} {case}")
 
 
-@pytest.mark.parametrize("name,variant", [a for a in ALL if a[1] != B.KN2ROW])
+@pytest.mark.parametrize("name,variant", [a for a in ALL if a[1] not in (B.KN2ROW, B.KN2COL)])
 @pytest.mark.parametrize("case", EVEN_K)
 def test_even_kernel_sizes(name, variant, case):
     announce("even-k", name, case)
@@ -228,10 +229,11 @@ def test_every_tile_shape_of_the_menu(k, pad, dtype, monkeypatch):
     ref, absref = oracle.mcmk(I, K, pad)
     tol = TOL_BF16 if dtype == B.BF16 else TOL_F32
     for index in range(12):
-        announce("menu", "k", k, "dtype", dtype, "tile", index)
-        monkeypatch.setenv("CONV_MCMK_TILE", str(index))
-        got = run_variant(B.KN2ROW, I, K, pad, dtype=dtype)
-        assert_within_bound(got, ref, absref, tol, f"tile {index} k={k} dtype={dtype}")
+        for variant in (B.KN2ROW, B.KN2COL):
+            announce("menu", "k", k, "dtype", dtype, "tile", index, "variant", variant)
+            monkeypatch.setenv("CONV_MCMK_TILE", str(index))
+            got = run_variant(variant, I, K, pad, dtype=dtype)
+            assert_within_bound(got, ref, absref, tol, f"tile {index} k={k} dtype={dtype} variant={variant}")
     monkeypatch.delenv("CONV_MCMK_TILE")
 
 

@@ -181,6 +181,22 @@ def test_kn2row_reformulation_matches(case):
         assert np.all(np.abs(got - O[i]) <= 1e-13 * A[i] + 1e-300)
 
 
+@pytest.mark.parametrize("case", CASES)
+def test_kn2col_reformulation_matches(case):
+    """kn2col is kn2row with the channel innermost: same numbers, transposed layouts."""
+    n, c, h, w, m, k, pad = case
+    I = wl.uniform(65, n * c * h * w, -1, 1).reshape(n, c, h, w)
+    K = wl.normal(66, m * c * k * k, 0.5).reshape(m, c, k, k)
+    O, A = oracle.mcmk(I, K, pad)
+    for i in range(n):
+        got = steps.kn2col_mcmk(np.ascontiguousarray(I[i].transpose(1, 2, 0)), K, pad)      # [Q][P][M]
+        assert got.shape == (O.shape[2], O.shape[3], m)
+        assert np.all(np.abs(got.transpose(2, 0, 1) - O[i]) <= 1e-13 * A[i] + 1e-300)
+    T = steps.kn2col_gemm(np.ascontiguousarray(I[0].transpose(1, 2, 0)), K)
+    assert T.shape == (h * w, k * k * m)
+    np.testing.assert_allclose(T, steps.kn2row_gemm(I[0], K).T, rtol=0, atol=1e-13)
+
+
 def test_one_by_one_is_a_matrix_product():
     """Section III: for k = 1 the layer is [M x C] times [C x HW]."""
     c, h, w, m = 7, 5, 6, 4
