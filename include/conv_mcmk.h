@@ -142,7 +142,8 @@ int conv_mcmk_direct(const conv_mcmk_desc *desc, const void *I_dev, const void *
 /*
  * kn2col (section III-A, last paragraph): the same sum of k*k 1x1 products with the layouts swapped so
  * that the channel is the innermost dimension -- the GEMM becomes [H*W x C] . [C x k*k*M].
- *   I_dev   input  I[N][H][W][C]  (float, or bfloat16 with C a multiple of 8)
+ *   I_dev   input  I[N][H][W][C]  (float with C a multiple of 4, or bfloat16 with C a multiple of 8:
+ *           the channel vectors are read 16 bytes at a time; other C: CONV_MCMK_ERR_UNSUPPORTED)
  *   Kp_dev  conv_mcmk_prepack(desc, CONV_MCMK_KN2COL): physically the KN2ROW packing (the matrix-core
  *           operand order does not care which of the two GEMM operands the kernel matrix is called)
  *   O_dev   output O[N][Q][P][M], float

@@ -44,8 +44,8 @@ int validate(const conv_mcmk_desc *d, int variant, Dims *out)
     case CONV_MCMK_KN2COL:
         if (d->k != 1 && d->k != 3 && d->k != 5 && d->k != 7) return CONV_MCMK_ERR_UNSUPPORTED;
         if (d->pad > 65535) return CONV_MCMK_ERR_SHAPE;
-        // channels-last bf16 input is read in aligned 16-byte channel octets
-        if (variant == CONV_MCMK_KN2COL && d->dtype == CONV_MCMK_BF16 && d->c % 8 != 0) return CONV_MCMK_ERR_UNSUPPORTED;
+        // channels-last input is read in aligned 16-byte channel vectors: 4 floats or 8 bfloat16
+        if (variant == CONV_MCMK_KN2COL && d->c % (d->dtype == CONV_MCMK_BF16 ? 8 : 4) != 0) return CONV_MCMK_ERR_UNSUPPORTED;
         break;
     case CONV_MCMK_KN2ROW_2PASS:
     case CONV_MCMK_IM2COL:

@@ -64,7 +64,7 @@ struct TileShape {
 };
 
 // CL = false: input [n][c][h][w], output [n][rows][q][p] (kn2row).
-// CL = true : channels last, input [n][h][w][c], output [n][q][p][rows] -- the layout of the paper's
+// CL = true : channels last (c a multiple of 4), input [n][h][w][c], output [n][q][p][rows] -- the layout of the paper's
 //             kn2col variant (section III-A, last paragraph); the packed kernel and the whole
 //             accumulation are the same, only the staging gather and the final store differ.
 template <int KS, int TH, int TW, int WM, int WP, int CCH = 16, bool CL = false>
@@ -142,24 +142,31 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a
     }
     static_assert(!kRegular || SLOTS * CSTEP == CC, "regular staging must cover the chunk exactly");
 
-    float stage[SLOTS];
+    // channels last: item e = tid + s*NT is (channel quad e % (CC/4), position e / (CC/4)): one
+    // 16-byte load of four consecutive channels (the host requires C to be a multiple of 4, so
+    // every quad is aligned and whole).  Offsets are recomputed per chunk (an opaque copy of tid keeps the compiler from
+    // hoisting them into more live registers).
+    constexpr int QPC = CC / 4;                                   // channel quads per chunk
+    constexpr int VSLOTS = (QPC * POS + NT - 1) / NT;             // items per thread
+    constexpr int NSTAGE = CL ? 4 * VSLOTS : SLOTS;
+    float stage[NSTAGE];
     auto load_chunk = [&](int chunk) {
         if constexpr (CL) {
-            // channels last: element e = tid + s*NT is (channel e % CC, position e / CC), so a wave
-            // reads whole 64-byte channel runs.  The offsets are recomputed per chunk (an opaque
-            // copy of tid keeps the compiler from hoisting them into SLOTS more live registers).
             int t = tid;
             asm volatile("" : "+v"(t));
 #pragma unroll
-            for (int s = 0; s < SLOTS; ++s) {
+            for (int s = 0; s < VSLOTS; ++s) {
                 const int e = t + s * NT;
-                const int cl = e % CC, pos = e / CC;
+                const int quad = e % QPC, pos = e / QPC;
                 const int r = pos / WT, col = pos % WT;
                 const int gy = y0 - a.pad + r, gx = x0 - a.pad + col;
-                const int ch = chunk * CC + cl;
-                const bool ok = e < CC * POS && gy >= 0 && gy < a.h && gx >= 0 && gx < a.w && ch < a.c;
-                const uint32_t off = ok ? (uint32_t)((((size_t)gy * a.w + gx) * a.c + ch) * sizeof(float)) : 0x80000000u;
-                stage[s] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(in_rsrc, (int)off, 0, 0));
+                const int ch = chunk * CC + quad * 4;
+                const bool ok = e < QPC * POS && gy >= 0 && gy < a.h && gx >= 0 && gx < a.w;
+                const uint32_t base = (uint32_t)((((size_t)gy * a.w + gx) * a.c + ch) * sizeof(float));
+                const f32x4 v = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
+                    in_rsrc, (int)((ok && ch < a.c) ? base : 0x80000000u), 0, 0));
+#pragma unroll
+                for (int u = 0; u < 4; ++u) stage[4 * s + u] = v[u];
             }
         } else {
 #pragma unroll
@@ -176,10 +183,14 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a
             int t = tid;
             asm volatile("" : "+v"(t));
 #pragma unroll
-            for (int s = 0; s < SLOTS; ++s) {
+            for (int s = 0; s < VSLOTS; ++s) {
                 const int e = t + s * NT;
-                const int cl = e % CC, pos = e / CC;
-                if (e < CC * POS) buf[cl * CHS + (pos / WT) * WT + (pos % WT)] = stage[s];
+                const int quad = e % QPC, pos = e / QPC;
+                if (e < QPC * POS) {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        buf[(quad * 4 + u) * CHS + (pos / WT) * WT + (pos % WT)] = stage[4 * s + u];
+                }
             }
         } else {
 #pragma unroll

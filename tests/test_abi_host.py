@@ -62,6 +62,7 @@ def test_check_rejects_bad_descriptors(lib):
     assert B.conv_mcmk_check(B.desc(**dict(ok, c=12), dtype=B.BF16), B.KN2COL) == B.ERR_UNSUPPORTED   # octets
     assert B.conv_mcmk_check(B.desc(**dict(ok, c=16), dtype=B.BF16), B.KN2COL) == B.OK
     assert B.conv_mcmk_check(B.desc(**dict(ok, c=12)), B.KN2COL) == B.OK
+    assert B.conv_mcmk_check(B.desc(**dict(ok, c=6)), B.KN2COL) == B.ERR_UNSUPPORTED                   # quads
     assert B.conv_mcmk_check(B.desc(**dict(ok, h=70000, w=70000)), B.DIRECT) == B.ERR_SHAPE      # >= 2^31 per image
     assert lib.conv_mcmk_check(None, B.KN2ROW) == B.ERR_NULL
 

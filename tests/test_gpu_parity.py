@@ -36,6 +36,21 @@ SMALL = [
 EVEN_K = [(1, 6, 12, 13, 10, 2, 1), (2, 5, 11, 10, 20, 4, 1), (1, 3, 10, 10, 4, 6, 0)]
 
 
+def _skip_unless_supported(variant, case, dtype=B.F32):
+    """kn2col reads whole channel vectors (4 floats / 8 bf16); other channel counts are refused."""
+    n, c, h, w, m, k, pad = case
+    if B.conv_mcmk_check(B.desc(n, c, h, w, m, k, pad, 1, dtype), variant) == B.ERR_UNSUPPORTED:
+        assert variant == B.KN2COL and c % 4 != 0
+        pytest.skip("kn2col needs a channel count that is a multiple of 4")
+
+
+# channel counts kn2col accepts, otherwise as ragged as SMALL
+KN2COL_CASES = [
+    (2, 20, 17, 19, 35, 3, 1), (1, 4, 30, 9, 7, 5, 2), (1, 36, 15, 15, 18, 1, 0), (1, 8, 20, 21, 9, 7, 3),
+    (3, 12, 29, 43, 70, 3, 1), (1, 4, 9, 9, 5, 3, 0), (1, 4, 6, 7, 5, 3, 2), (1, 4, 1, 1, 1, 1, 0), (2, 40, 28, 28, 49, 5, 2),
+]
+
+
 def _inputs(case, seed):
     n, c, h, w, m, k, pad = case
     I = wl.uniform(seed, n * c * h * w, -1, 1).reshape(n, c, h, w)
@@ -46,12 +61,22 @@ def _inputs(case, seed):
 @pytest.mark.parametrize("name,variant", ALL)
 @pytest.mark.parametrize("case", SMALL)
 def test_small_shapes_match_oracle(name, variant, case):
+    _skip_unless_supported(variant, case)
     announce("small", name, case)
     I, K = _inputs(case, 1000 + sum(case))
     ref, absref = oracle.mcmk(I, K, case[-1])
     got = run_variant(variant, I, K, case[-1])
     assert got.shape == ref.shape
     assert_within_bound(got, ref, absref, TOL_F32, f"{name} {case}")
+
+
+@pytest.mark.parametrize("case", KN2COL_CASES)
+def test_kn2col_shapes_match_oracle(case):
+    announce("kn2col", case)
+    I, K = _inputs(case, 1500 + sum(case))
+    ref, absref = oracle.mcmk(I, K, case[-1])
+    got = run_variant(B.KN2COL, I, K, case[-1])
+    assert_within_bound(got, ref, absref, TOL_F32, f"kn2col {case}")
 
 
 @pytest.mark.parametrize("name,variant", [a for a in ALL if a[1] not in (B.KN2ROW, B.KN2COL)])
@@ -68,6 +93,7 @@ def test_even_kernel_sizes(name, variant, case):
 @pytest.mark.parametrize("case", [(2, 20, 17, 19, 35, 3, 1), (1, 24, 31, 16, 40, 5, 2), (1, 9, 15, 16, 33, 1, 0)])
 def test_integer_data_is_bit_exact(name, variant, case):
     """Integer-valued inputs keep every partial sum below 2^24, so any summation order is exact."""
+    _skip_unless_supported(variant, case)
     announce("exact-int", name, case)
     n, c, h, w, m, k, pad = case
     I = wl.small_integers(31, n * c * h * w, 0, 8).reshape(n, c, h, w)
@@ -81,7 +107,7 @@ def test_integer_data_is_bit_exact(name, variant, case):
 def test_delta_kernels_shift_without_row_wrap(name, variant):
     """A single tap copies the input displaced by the tap's offset; values leaving a row are dropped
     (section III-A), including at tile borders."""
-    c, h, w, k, pad = 2, 30, 17, 3, 1
+    c, h, w, k, pad = 4, 30, 17, 3, 1
     I = wl.uniform(77, c * h * w, -1, 1).reshape(1, c, h, w)
     K = np.zeros((k * k, c, k, k), dtype=np.float32)
     for i in range(k):
@@ -251,5 +277,7 @@ def test_stretched_shapes(case):
     K = wl.normal(701 + c, m * c * k * k, 0.5).reshape(m, c, k, k)
     ref, absref = oracle.mcmk(I, K, pad)
     for name, variant in ALL:
+        if variant == B.KN2COL and c % 4:
+            continue
         got = run_variant(variant, I, K, pad)
         assert_within_bound(got, ref, absref, TOL_F32, f"{name} {case}")
