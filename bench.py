@@ -77,11 +77,11 @@ def bench_layer(L, variants, steps, warmup, I_dev=None, K_dev=None, dtype=0):
     out = {}
     for name in variants:
         variant = B.VARIANTS[name]
-        if variant == B.KN2COL and dtype == B.BF16 and L.c % 8:
+        if variant in B.CHANNELS_LAST and L.c % (8 if dtype == B.BF16 else 4):
             continue
         plan = B.Plan(d, variant, K_dev)
         I_use = I_dev
-        if variant == B.KN2COL:              # kn2col takes I[N][H][W][C]
+        if variant in B.CHANNELS_LAST:       # kn2col and im2row take I[N][H][W][C]
             if I_cl is None:
                 I_cl = I_dev.permute(0, 2, 3, 1).contiguous()
             I_use = I_cl
@@ -125,7 +125,7 @@ def main():
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
-    ap.add_argument("--variant", default="kn2row", choices=["kn2row", "kn2row_2pass", "im2col", "direct", "kn2col"],
+    ap.add_argument("--variant", default="kn2row", choices=["kn2row", "kn2row_2pass", "im2col", "direct", "kn2col", "im2row"],
                     help="which entry point the timed steps call (the headline is kn2row)")
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"], help="operand type of the timed steps")
     ap.add_argument("--no-table", action="store_true", help="skip the other variants and layers")
@@ -156,7 +156,8 @@ def main():
     if dtype == B.BF16:
         I_run = torch.empty(I_dev.shape, dtype=torch.bfloat16, device=dev)
         B.conv_mcmk_cvt_f32_bf16(I_dev, I_run)
-    if args.variant == "kn2col":
+    channels_last = B.VARIANTS[args.variant] in B.CHANNELS_LAST
+    if channels_last:
         I_run = I_run.permute(0, 2, 3, 1).contiguous()
     torch.cuda.synchronize()
 
@@ -174,7 +175,7 @@ def main():
 
     # sanity: the timed output against the oracle on sampled points
     pts = wl.sample_points(L, 512)
-    out_nmqp = plan.out.permute(0, 3, 1, 2) if args.variant == "kn2col" else plan.out
+    out_nmqp = plan.out.permute(0, 3, 1, 2) if channels_last else plan.out
     got = out_nmqp.cpu().numpy()[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]].astype(np.float64)
     import oracle
     ref, absref = oracle.mcmk_at(I, K, L.pad, pts)
@@ -211,7 +212,7 @@ def main():
     if not args.no_table:
         table = {}
         for name, layer in wl.LAYERS.items():
-            variants = ["kn2row", "kn2col", "im2col", "kn2row_2pass"] + (["direct"] if layer.flops < 5e9 else [])
+            variants = ["kn2row", "kn2col", "im2col", "im2row", "kn2row_2pass"] + (["direct"] if layer.flops < 5e9 else [])
             steps = None          # enough launches for ~60 ms of warm-up and ~120 ms of timed work
             same = name == L.name
             table[name] = bench_layer(layer, variants, steps, None, I_dev if same else None, K_dev if same else None)
@@ -219,7 +220,7 @@ def main():
             r["kn2row_over_im2col_time"] = round(r["kn2row"]["ms"] / r["im2col"]["ms"], 4)
             r["frac_f32_mfma_peak"] = round(r["kn2row"]["gflops"] / 1e3 / PEAK_F32_MFMA_TFLOPS, 4)
             if name.startswith("cfg5"):          # the deep-layer sweep is also quoted with bf16 operands
-                b = bench_layer(layer, ["kn2row", "kn2col", "im2col", "kn2row_2pass"], steps, None,
+                b = bench_layer(layer, ["kn2row", "kn2col", "im2col", "im2row", "kn2row_2pass"], steps, None,
                                 I_dev if same else None, K_dev if same else None, dtype=B.BF16)
                 b["frac_bf16_mfma_peak"] = round(b["kn2row"]["gflops"] / 1e3 / PEAK_BF16_MFMA_TFLOPS, 4)
                 r["bf16"] = b

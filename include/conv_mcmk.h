@@ -57,8 +57,10 @@ enum {
                                    workspace, then the shift-add post pass */
     CONV_MCMK_IM2COL       = 2, /* section II-B: build the column matrix in the workspace, then one GEMM */
     CONV_MCMK_DIRECT       = 3, /* the loop nest of Eq. 1-3, one output element per thread, no matrix cores */
-    CONV_MCMK_KN2COL       = 4  /* section III-A, last paragraph: kn2row with the channel innermost in the input
+    CONV_MCMK_KN2COL       = 4, /* section III-A, last paragraph: kn2row with the channel innermost in the input
                                    and in the output (I[N][H][W][C], O[N][Q][P][M]); shift-add fused as in KN2ROW */
+    CONV_MCMK_IM2ROW       = 5  /* section II-B, last paragraph: patches unrolled into rows of the workspace
+                                   (channels last), then one GEMM patches x kernels; layouts as KN2COL */
 };
 
 enum {
@@ -92,6 +94,7 @@ int conv_mcmk_describe_plan(const conv_mcmk_desc *desc, int variant, char *buf, 
  *                 T[t*M + m][y*W + x], t = i*k + j ("some increase in the size of the output").
  *   IM2COL:       N * C*k*k * Q*P elements of the input's type -- the input-patch-matrix of
  *                 section II-B, per image Ihat[(c*k + i)*k + j][q*P + p] (k*k times the input).
+ *   IM2ROW:       the same number of elements, per image rows[q*P + p][(i*k + j)*C + c].
  * After a 2PASS / IM2COL call the workspace holds exactly those matrices.
  */
 size_t conv_mcmk_workspace_bytes(const conv_mcmk_desc *desc, int variant);
@@ -106,8 +109,9 @@ size_t conv_mcmk_workspace_bytes(const conv_mcmk_desc *desc, int variant);
  *   (G = 16 for F32, 32 for BF16; CG = ceil(Kc/G) groups; Kc = C for kn2row, C*k*k for im2col):
  *     F32 : float  Kp[t][mb][cg][lane 0..63][v 0..3]  = A_t[mb*16 + lane%16][cg*16 + 4*v + lane/16]
  *     BF16: bf16   Kp[t][mb][cg][lane 0..63][e 0..7]  = A_t[mb*16 + lane%16][cg*32 + 8*(lane/16) + e]
- *   where A_t[m][c] = K[m][c][i][j] for kn2row (t = i*k + j) and, for im2col, t = 0 and
- *   A_0[m][(c*k + i)*k + j] = K[m][c][i][j].  Entries beyond M or Kc are zero.
+ *   where A_t[m][c] = K[m][c][i][j] for kn2row / kn2col (t = i*k + j); for im2col t = 0 and
+ *   A_0[m][(c*k + i)*k + j] = K[m][c][i][j]; for im2row t = 0 and A_0[m][(i*k + j)*C + c] = K[m][c][i][j].
+ *   Entries beyond M or Kc are zero.
  */
 size_t conv_mcmk_packed_kernel_bytes(const conv_mcmk_desc *desc, int variant);
 
@@ -150,6 +154,18 @@ int conv_mcmk_direct(const conv_mcmk_desc *desc, const void *I_dev, const void *
  * No workspace; k = 1, 3, 5, 7; otherwise as conv_mcmk_kn2row.
  */
 int conv_mcmk_kn2col(const conv_mcmk_desc *desc, const void *I_dev, const void *Kp_dev, void *O_dev,
+                     void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * im2row (section II-B, last paragraph): the input-patch-matrix holds one ROW per output position,
+ * rows[n][q*P+p][(i*k+j)*C + c] (the workspace: N * Q*P * k*k*C elements of the input's type, k*k times the
+ * input), the kernel-patch-matrix one column per kernel, and O = rows x kernels.
+ *   I_dev   input  I[N][H][W][C]  (float with C a multiple of 4, or bfloat16 with C a multiple of 8)
+ *   Kp_dev  conv_mcmk_prepack(desc, CONV_MCMK_IM2ROW): A_0[m][(i*k+j)*C + c] = K[m][c][i][j] in the packed form
+ *   O_dev   output O[N][Q][P][M], float
+ * Any k >= 1.
+ */
+int conv_mcmk_im2row(const conv_mcmk_desc *desc, const void *I_dev, const void *Kp_dev, void *O_dev,
                      void *ws, size_t ws_bytes, void *stream);
 
 /* float -> bfloat16 (round to nearest even), `count` elements, device to device. */

@@ -59,6 +59,39 @@ def im2col_mcmk(I, K, pad):
     return out.reshape(m, q_out, p_out)
 
 
+def input_patch_matrix_rows(I_hwc, k, pad):
+    """im2row: the patches unrolled into ROWS, [Q*P] x [k*k*C], from a channel-innermost input
+    I[H][W][C]; columns ordered (i, j, c) so that consecutive patch elements are consecutive in memory."""
+    I_hwc = _f64(I_hwc)
+    h, w, c = I_hwc.shape
+    q_out, p_out = h + 2 * pad - k + 1, w + 2 * pad - k + 1
+    rows = np.zeros((q_out * p_out, k * k * c), dtype=np.float64)
+    for q in range(q_out):
+        for p in range(p_out):
+            for i in range(k):
+                for j in range(k):
+                    y, x = q - pad + i, p - pad + j
+                    if 0 <= y < h and 0 <= x < w:
+                        rows[q * p_out + p, (i * k + j) * c:(i * k + j + 1) * c] = I_hwc[y, x, :]
+    return rows
+
+
+def kernel_patch_matrix_cols(K):
+    """im2row: each kernel unrolled into one COLUMN, [k*k*C] x [M], rows ordered (i, j, c)."""
+    K = _f64(K)
+    m = K.shape[0]
+    return np.ascontiguousarray(K.transpose(2, 3, 1, 0)).reshape(-1, m)
+
+
+def im2row_mcmk(I_hwc, K, pad):
+    """O = I-hat x K-hat, read back as O[Q][P][M]."""
+    K = _f64(K)
+    m, _, k, _ = K.shape
+    h, w, _ = np.shape(I_hwc)
+    q_out, p_out = h + 2 * pad - k + 1, w + 2 * pad - k + 1
+    return np.matmul(input_patch_matrix_rows(I_hwc, k, pad), kernel_patch_matrix_cols(K)).reshape(q_out, p_out, m)
+
+
 # ---------------------------------------------------------------- kn2row (section III-A)
 
 def kn2row_kernel_matrix(K):

@@ -14,15 +14,17 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libconv_mcmk.so")
 
 F32, BF16 = 0, 1
-KN2ROW, KN2ROW_2PASS, IM2COL, DIRECT, KN2COL = 0, 1, 2, 3, 4
-VARIANTS = {"kn2row": KN2ROW, "kn2row_2pass": KN2ROW_2PASS, "im2col": IM2COL, "direct": DIRECT, "kn2col": KN2COL}
+KN2ROW, KN2ROW_2PASS, IM2COL, DIRECT, KN2COL, IM2ROW = 0, 1, 2, 3, 4, 5
+CHANNELS_LAST = (KN2COL, IM2ROW)       # variants that take I[N][H][W][C] and give O[N][Q][P][M]
+VARIANTS = {"kn2row": KN2ROW, "kn2row_2pass": KN2ROW_2PASS, "im2col": IM2COL, "direct": DIRECT, "kn2col": KN2COL,
+            "im2row": IM2ROW}
 
 OK, ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_DEVICE, ERR_ALIGN = range(7)
 
 EXPORTS = (
     "conv_mcmk_strerror", "conv_mcmk_check", "conv_mcmk_describe_plan", "conv_mcmk_workspace_bytes", "conv_mcmk_packed_kernel_bytes",
     "conv_mcmk_prepack", "conv_mcmk_kn2row", "conv_mcmk_kn2row_2pass", "conv_mcmk_im2col",
-    "conv_mcmk_direct", "conv_mcmk_kn2col", "conv_mcmk_cvt_f32_bf16",
+    "conv_mcmk_direct", "conv_mcmk_kn2col", "conv_mcmk_im2row", "conv_mcmk_cvt_f32_bf16",
 )
 
 
@@ -63,7 +65,7 @@ def lib():
         L.conv_mcmk_prepack.argtypes = [dp, i, vp, vp, vp]
         L.conv_mcmk_prepack.restype = i
         for name in ("conv_mcmk_kn2row", "conv_mcmk_kn2row_2pass", "conv_mcmk_im2col", "conv_mcmk_direct",
-                     "conv_mcmk_kn2col"):
+                     "conv_mcmk_kn2col", "conv_mcmk_im2row"):
             fn = getattr(L, name)
             fn.argtypes = [dp, vp, vp, vp, vp, sz, vp]
             fn.restype = i
@@ -144,13 +146,17 @@ def conv_mcmk_kn2col(d, I, Kp, O, ws=None, stream=None):
     _run("conv_mcmk_kn2col", d, I, Kp, O, ws, stream)
 
 
+def conv_mcmk_im2row(d, I, Kp, O, ws=None, stream=None):
+    _run("conv_mcmk_im2row", d, I, Kp, O, ws, stream)
+
+
 def conv_mcmk_cvt_f32_bf16(src, dst, count=None, stream=None):
     n = src.numel() if count is None else count
     _raise(lib().conv_mcmk_cvt_f32_bf16(_ptr(src), _ptr(dst), n, _stream(stream)))
 
 
 RUNNERS = {KN2ROW: conv_mcmk_kn2row, KN2ROW_2PASS: conv_mcmk_kn2row_2pass, IM2COL: conv_mcmk_im2col,
-           DIRECT: conv_mcmk_direct, KN2COL: conv_mcmk_kn2col}
+           DIRECT: conv_mcmk_direct, KN2COL: conv_mcmk_kn2col, IM2ROW: conv_mcmk_im2row}
 
 
 class Plan:
@@ -171,7 +177,7 @@ class Plan:
         ws_bytes = conv_mcmk_workspace_bytes(d, variant)
         self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev) if ws_bytes else None
         q, p = d.h + 2 * d.pad - d.k + 1, d.w + 2 * d.pad - d.k + 1
-        shape = (d.n, q, p, d.m) if variant == KN2COL else (d.n, d.m, q, p)
+        shape = (d.n, q, p, d.m) if variant in CHANNELS_LAST else (d.n, d.m, q, p)
         self.out = torch.empty(shape, dtype=torch.float32, device=dev)
 
     def run(self, I_dev, stream=None):

@@ -19,10 +19,21 @@ __device__ inline uint16_t f32_to_bf16_rne(float f)
 // ---------------------------------------------------------------------------------------------
 // Kernel re-ordering (section III-A: done once, ahead of time).
 // Output element index e decodes as [t][mb][cg][lane][v]; see conv_mcmk.h for the layout.
-//   im2col = false: A_t[m][c] = K[m][c][i][j], t = i*k + j, contraction length kc = C
-//   im2col = true : t = 0,   A[m][(c*k+i)*k+j] = K[m][c][i][j], contraction length kc = C*k*k
+//   order 0 (kn2row, kn2col): A_t[m][c] = K[m][c][i][j], t = i*k + j, contraction length kc = C
+//   order 1 (im2col): t = 0,   A[m][(c*k+i)*k+j] = K[m][c][i][j], contraction length kc = C*k*k
+//   order 2 (im2row): t = 0,   A[m][(i*k+j)*C+c] = K[m][c][i][j], contraction length kc = C*k*k
+__device__ inline float packed_source(const float *__restrict__ K, int m, int c, int k, int order, int t,
+                                      int row, int kk)
+{
+    if (row >= m) return 0.0f;
+    if (order == 0) return kk < c ? K[((size_t)row * c + kk) * k * k + t] : 0.0f;
+    if (kk >= c * k * k) return 0.0f;
+    if (order == 1) return K[(size_t)row * c * k * k + kk];
+    return K[((size_t)row * c + kk % c) * k * k + kk / c];
+}
+
 __global__ void prepack_f32_kernel(const float *__restrict__ K, float *__restrict__ Kp,
-                                   int m, int c, int k, int mb, int cg, int taps, bool im2col)
+                                   int m, int c, int k, int mb, int cg, int taps, int order)
 {
     const size_t total = (size_t)taps * mb * cg * 256;
     for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total;
@@ -35,22 +46,14 @@ __global__ void prepack_f32_kernel(const float *__restrict__ K, float *__restric
         const int t = (int)rest;
         const int row = imb * 16 + (lane & 15);
         const int kk = icg * 16 + 4 * v + (lane >> 4);
-        float val = 0.0f;
-        if (row < m) {
-            if (im2col) {
-                if (kk < c * k * k) val = K[(size_t)row * c * k * k + kk];
-            } else if (kk < c) {
-                val = K[((size_t)row * c + kk) * k * k + t];
-            }
-        }
-        Kp[e] = val;
+        Kp[e] = packed_source(K, m, c, k, order, t, row, kk);
     }
 }
 
 // bfloat16 form: element index e decodes as [t][mb][cg][lane][e8]; 32-channel groups,
 //   Kp = bf16(A_t[mb*16 + lane%16][cg*32 + 8*(lane/16) + e8]).
 __global__ void prepack_bf16_kernel(const float *__restrict__ K, uint16_t *__restrict__ Kp,
-                                    int m, int c, int k, int mb, int cg, int taps, bool im2col)
+                                    int m, int c, int k, int mb, int cg, int taps, int order)
 {
     const size_t total = (size_t)taps * mb * cg * 512;
     for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total;
@@ -63,15 +66,7 @@ __global__ void prepack_bf16_kernel(const float *__restrict__ K, uint16_t *__res
         const int t = (int)rest;
         const int row = imb * 16 + (lane & 15);
         const int kk = icg * 32 + 8 * (lane >> 4) + e8;
-        float val = 0.0f;
-        if (row < m) {
-            if (im2col) {
-                if (kk < c * k * k) val = K[(size_t)row * c * k * k + kk];
-            } else if (kk < c) {
-                val = K[((size_t)row * c + kk) * k * k + t];
-            }
-        }
-        Kp[e] = f32_to_bf16_rne(val);
+        Kp[e] = f32_to_bf16_rne(packed_source(K, m, c, k, order, t, row, kk));
     }
 }
 
@@ -112,6 +107,37 @@ __global__ void im2col_build_kernel(const T *__restrict__ I, T *__restrict__ col
                 *reinterpret_cast<Pack *>(dst + (size_t)(i * k + j) * qp) = out;
             }
         }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// im2row (section II-B, last paragraph): patches unrolled into ROWS, from a channels-last input:
+//   rows[n][q*P+p][(i*k+j)*C + c] = I[n][q-pad+i][p-pad+j][c]  (zero outside the image).
+// One thread copies one VEC-wide channel vector (VEC elements = 16 bytes; C % VEC == 0), so both the
+// read and the write are contiguous runs of C elements.
+template <typename T, int VEC>
+__global__ void im2row_build_kernel(const T *__restrict__ I, T *__restrict__ rows,
+                                    int n, int c, int h, int w, int k, int pad, int q, int p)
+{
+    struct alignas(sizeof(T) * VEC) Pack { T v[VEC]; };
+    const int cv = c / VEC;
+    const size_t total = (size_t)n * q * p * k * k * cv;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total;
+         e += (size_t)gridDim.x * blockDim.x) {
+        const int ic = (int)(e % cv);
+        size_t rest = e / cv;
+        const int j = (int)(rest % k);  rest /= k;
+        const int i = (int)(rest % k);  rest /= k;
+        const int op = (int)(rest % p); rest /= p;
+        const int oq = (int)(rest % q);
+        const size_t in = rest / q;
+        const int y = oq - pad + i, x = op - pad + j;
+        Pack out;
+#pragma unroll
+        for (int u = 0; u < VEC; ++u) out.v[u] = T(0);
+        if (y >= 0 && y < h && x >= 0 && x < w)
+            out = *reinterpret_cast<const Pack *>(I + ((in * h + y) * w + x) * (size_t)c + (size_t)ic * VEC);
+        *reinterpret_cast<Pack *>(rows + e * VEC) = out;
     }
 }
 

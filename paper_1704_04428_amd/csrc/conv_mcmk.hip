@@ -50,6 +50,9 @@ int validate(const conv_mcmk_desc *d, int variant, Dims *out)
     case CONV_MCMK_KN2ROW_2PASS:
     case CONV_MCMK_IM2COL:
         break;
+    case CONV_MCMK_IM2ROW:
+        if (d->c % (d->dtype == CONV_MCMK_BF16 ? 8 : 4) != 0) return CONV_MCMK_ERR_UNSUPPORTED;
+        break;
     case CONV_MCMK_DIRECT:
         if (d->dtype != CONV_MCMK_F32) return CONV_MCMK_ERR_UNSUPPORTED;
         break;
@@ -204,10 +207,11 @@ int launch_fused(const conv_mcmk_desc *d, const Dims &dm, const void *in, const 
 // Plain GEMM [rows x kc] . [kc x cols] per image on the same tile kernel: a 1x1 "convolution" over a
 // 1 x cols image.
 int launch_gemm(const conv_mcmk_desc *d, const Dims &dm, const void *bmat, const void *apk, float *cmat,
-                int kc, long long cols, int row_groups, hipStream_t st)
+                int kc, long long cols, int row_groups, hipStream_t st, bool channels_last = false)
 {
     if (cols >= (1LL << 31)) return CONV_MCMK_ERR_SHAPE;
-    return launch_tile(d, dm, 1, kGemmShape, 1, bmat, apk, cmat, kc, 1, (int)cols, 1, (int)cols, 0, row_groups, st);
+    return launch_tile(d, dm, 1, kGemmShape, 1, bmat, apk, cmat, kc, 1, (int)cols, 1, (int)cols, 0, row_groups, st,
+                       channels_last);
 }
 
 int common_ptr_checks(const void *I, const void *K, const void *O)
@@ -272,6 +276,10 @@ int conv_mcmk_describe_plan(const conv_mcmk_desc *d, int variant, char *buf, siz
         snprintf(buf, n, "im2col %s: patch matrix [%d x %d] per image, GEMM [%d x %d].[%d x %d] (tile 1x%d, waves %dx%d)",
                  type, d->c * dm.taps, dm.q * dm.p, d->m, d->c * dm.taps, d->c * dm.taps, dm.q * dm.p, g.tw, g.wm, g.wp);
         break;
+    case CONV_MCMK_IM2ROW:
+        snprintf(buf, n, "im2row %s: patch matrix [%d x %d] per image (channels last), GEMM [%d x %d].[%d x %d] (tile 1x%d, waves %dx%d)",
+                 type, dm.q * dm.p, d->c * dm.taps, dm.q * dm.p, d->c * dm.taps, d->c * dm.taps, d->m, g.tw, g.wm, g.wp);
+        break;
     default:
         snprintf(buf, n, "direct f32: one thread per output element, %lld outputs", (long long)d->n * d->m * dm.q * dm.p);
         break;
@@ -286,7 +294,8 @@ size_t conv_mcmk_workspace_bytes(const conv_mcmk_desc *d, int variant)
     const size_t elt = d->dtype == CONV_MCMK_BF16 ? 2 : 4;
     switch (variant) {
     case CONV_MCMK_KN2ROW_2PASS: return (size_t)d->n * dm.taps * d->m * d->h * d->w * sizeof(float);
-    case CONV_MCMK_IM2COL: return (size_t)d->n * d->c * dm.taps * dm.q * dm.p * elt;
+    case CONV_MCMK_IM2COL:
+    case CONV_MCMK_IM2ROW: return (size_t)d->n * d->c * dm.taps * dm.q * dm.p * elt;
     default: return 0;
     }
 }
@@ -303,6 +312,7 @@ size_t conv_mcmk_packed_kernel_bytes(const conv_mcmk_desc *d, int variant)
     case CONV_MCMK_KN2COL:
         return (size_t)dm.taps * dm.mb * ceil_div(d->c, group) * 16 * group * elt;
     case CONV_MCMK_IM2COL:
+    case CONV_MCMK_IM2ROW:
         return (size_t)dm.mb * ceil_div((long long)d->c * dm.taps, group) * 16 * group * elt;
     default: return 0;
     }
@@ -317,20 +327,20 @@ int conv_mcmk_prepack(const conv_mcmk_desc *d, int variant, const void *K_dev, v
     if (!K_dev || !Kp_dev) return CONV_MCMK_ERR_NULL;
     if (misaligned(K_dev) || misaligned(Kp_dev)) return CONV_MCMK_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const bool im2col = variant == CONV_MCMK_IM2COL;
+    const int order = variant == CONV_MCMK_IM2COL ? 1 : variant == CONV_MCMK_IM2ROW ? 2 : 0;
     const bool bf16 = d->dtype == CONV_MCMK_BF16;
     const int group = bf16 ? 32 : 16;
-    const int taps = im2col ? 1 : dm.taps;
-    const int cg = im2col ? ceil_div((long long)d->c * dm.taps, group) : ceil_div(d->c, group);
+    const int taps = order ? 1 : dm.taps;
+    const int cg = order ? ceil_div((long long)d->c * dm.taps, group) : ceil_div(d->c, group);
     const size_t total = (size_t)taps * dm.mb * cg * 16 * group;
     if (bf16)
         hipLaunchKernelGGL(prepack_bf16_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st,
                            static_cast<const float *>(K_dev), static_cast<uint16_t *>(Kp_dev),
-                           d->m, d->c, d->k, dm.mb, cg, taps, im2col);
+                           d->m, d->c, d->k, dm.mb, cg, taps, order);
     else
         hipLaunchKernelGGL(prepack_f32_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st,
                            static_cast<const float *>(K_dev), static_cast<float *>(Kp_dev),
-                           d->m, d->c, d->k, dm.mb, cg, taps, im2col);
+                           d->m, d->c, d->k, dm.mb, cg, taps, order);
     return launch_status();
 }
 
@@ -403,6 +413,30 @@ int conv_mcmk_im2col(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_
 #undef MCMK_IM2COL
     if ((rc = launch_status())) return rc;
     return launch_gemm(d, dm, ws, Kp_dev, static_cast<float *>(O_dev), d->c * dm.taps, (long long)dm.q * dm.p, 1, st);
+}
+
+int conv_mcmk_im2row(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_dev, void *O_dev,
+                     void *ws, size_t ws_bytes, void *stream)
+{
+    Dims dm;
+    int rc = validate(d, CONV_MCMK_IM2ROW, &dm);
+    if (rc) return rc;
+    if ((rc = common_ptr_checks(I_dev, Kp_dev, O_dev))) return rc;
+    if ((rc = workspace_check(d, CONV_MCMK_IM2ROW, ws, ws_bytes))) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool bf16 = d->dtype == CONV_MCMK_BF16;
+    const int vec = bf16 ? 8 : 4;
+    const size_t total = (size_t)d->n * dm.q * dm.p * dm.taps * (d->c / vec);
+    const dim3 grid(grid_for(total, 256)), block(256);
+    if (bf16)
+        hipLaunchKernelGGL((im2row_build_kernel<uint16_t, 8>), grid, block, 0, st, static_cast<const uint16_t *>(I_dev),
+                           static_cast<uint16_t *>(ws), d->n, d->c, d->h, d->w, d->k, d->pad, dm.q, dm.p);
+    else
+        hipLaunchKernelGGL((im2row_build_kernel<float, 4>), grid, block, 0, st, static_cast<const float *>(I_dev),
+                           static_cast<float *>(ws), d->n, d->c, d->h, d->w, d->k, d->pad, dm.q, dm.p);
+    if ((rc = launch_status())) return rc;
+    // O[n][q*P+p][m] = rows[n][q*P+p][:] . Khat[:][m]: the channels-last GEMM
+    return launch_gemm(d, dm, ws, Kp_dev, static_cast<float *>(O_dev), d->c * dm.taps, (long long)dm.q * dm.p, 1, st, true);
 }
 
 int conv_mcmk_direct(const conv_mcmk_desc *d, const void *I_dev, const void *K_dev, void *O_dev,

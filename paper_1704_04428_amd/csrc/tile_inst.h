@@ -63,6 +63,9 @@ int MCMK_FN(const TileRequest &rq)
         case 3: return launch_shape<16, 16, 4, 2, 16, true>(rq);
         case 4: return launch_shape<16, 16, 2, 4, 16, true>(rq);
         case 5: return launch_shape<16, 16, 1, 4, 16, true>(rq);
+#if MCMK_KS == 1
+        case 6: return launch_shape<1, 224, 4, 2, 32, true>(rq);
+#endif
         default: return 2;
         }
     }

@@ -43,7 +43,7 @@ def run_variant(variant, I, K, pad, dtype=B.F32, return_ws=False):
         raise B.ConvMcmkError(rc, B.strerror(rc))
     q, p = h + 2 * pad - k + 1, w + 2 * pad - k + 1
     dev = torch.device("cuda:0")
-    channels_last = variant == B.KN2COL
+    channels_last = variant in B.CHANNELS_LAST
     if channels_last:
         I = I.transpose(0, 2, 3, 1)                      # the library sees I[N][H][W][C]
     I_dev = torch.from_numpy(np.ascontiguousarray(I)).to(dev)

@@ -42,7 +42,7 @@ def test_check_accepts_benchmark_layers(lib):
     from paper_1704_04428_amd import workloads as wl
     for L in wl.LAYERS.values():
         d = B.desc(L.n, L.c, L.h, L.w, L.m, L.k, L.pad)
-        for v in (B.KN2ROW, B.KN2ROW_2PASS, B.IM2COL, B.DIRECT, B.KN2COL):
+        for v in (B.KN2ROW, B.KN2ROW_2PASS, B.IM2COL, B.DIRECT, B.KN2COL, B.IM2ROW):
             assert B.conv_mcmk_check(d, v) == B.OK, (L.name, v)
 
 
@@ -79,6 +79,9 @@ def test_sizes(lib):
     assert B.conv_mcmk_packed_kernel_bytes(d, B.KN2ROW_2PASS) == 9 * mb * cg * 256 * 4
     assert B.conv_mcmk_packed_kernel_bytes(d, B.KN2COL) == 9 * mb * cg * 256 * 4
     assert B.conv_mcmk_workspace_bytes(d, B.KN2COL) == 0
+    assert B.conv_mcmk_workspace_bytes(d, B.IM2ROW) == B.conv_mcmk_workspace_bytes(d, B.IM2COL)
+    assert B.conv_mcmk_packed_kernel_bytes(d, B.IM2ROW) == B.conv_mcmk_packed_kernel_bytes(d, B.IM2COL)
+    assert B.conv_mcmk_check(B.desc(2, 21, 9, 11, 35, 3, 1), B.IM2ROW) == B.ERR_UNSUPPORTED      # channel vectors
     assert B.conv_mcmk_packed_kernel_bytes(d, B.IM2COL) == mb * 12 * 256 * 4              # ceil(180/16) = 12
     assert B.conv_mcmk_packed_kernel_bytes(d, B.DIRECT) == 0
     assert B.conv_mcmk_workspace_bytes(B.desc(0, 1, 1, 1, 1, 1, 0), B.IM2COL) == 0
@@ -97,7 +100,7 @@ def test_compute_calls_validate_before_launch(lib):
     d = B.desc(1, 4, 8, 8, 4, 3, 1)
     null = ctypes.c_void_p(0)
     for name in ("conv_mcmk_kn2row", "conv_mcmk_kn2row_2pass", "conv_mcmk_im2col", "conv_mcmk_direct",
-                 "conv_mcmk_kn2col"):
+                 "conv_mcmk_kn2col", "conv_mcmk_im2row"):
         fn = getattr(lib, name)
         assert fn(ctypes.byref(d), null, null, null, null, 0, null) == B.ERR_NULL
         bad = B.desc(1, 4, 8, 8, 4, 3, 1, stride=2)
@@ -131,6 +134,8 @@ def test_plan_selection_for_benchmark_layers(lib, monkeypatch):
     assert "shift-add" in B.conv_mcmk_describe_plan(d, B.KN2ROW_2PASS)
     assert "patch matrix [72 x 100]" in B.conv_mcmk_describe_plan(d, B.IM2COL)
     assert "800 outputs" in B.conv_mcmk_describe_plan(d, B.DIRECT)
+    assert "patch matrix [100 x 72]" in B.conv_mcmk_describe_plan(d, B.IM2ROW)
+    assert B.conv_mcmk_describe_plan(d, B.KN2COL).startswith("kn2col fused f32")
     with pytest.raises(B.ConvMcmkError):
         B.conv_mcmk_describe_plan(B.desc(1, 8, 10, 10, 8, 3, 1, stride=2), B.KN2ROW)
     monkeypatch.setenv("CONV_MCMK_TILE", "5")

@@ -59,19 +59,20 @@ def test_bf16_matches_oracle(name, variant, case):
     assert_within_bound(got, ref_r, abs_r, TOL_F32, f"bf16 {name} {case} vs rounded inputs")
 
 
+@pytest.mark.parametrize("variant", [B.KN2COL, B.IM2ROW])
 @pytest.mark.parametrize("case", KN2COL_CASES)
-def test_bf16_kn2col_matches_oracle(case):
-    announce("bf16 kn2col", case)
+def test_bf16_channels_last_matches_oracle(case, variant):
+    announce("bf16 channels-last", variant, case)
     I, K = _inputs(case, 3500 + sum(case))
     pad = case[-1]
-    got = run_variant(B.KN2COL, I, K, pad, dtype=B.BF16)
+    got = run_variant(variant, I, K, pad, dtype=B.BF16)
     ref, absref = oracle.mcmk(I, K, pad)
     assert_within_bound(got, ref, absref, TOL_BF16, f"bf16 kn2col {case} vs fp32 inputs")
     ref_r, abs_r = oracle.mcmk(steps.round_to_bf16(I), steps.round_to_bf16(K), pad)
     assert_within_bound(got, ref_r, abs_r, TOL_F32, f"bf16 kn2col {case} vs rounded inputs")
 
 
-@pytest.mark.parametrize("name,variant", MFMA + [("kn2col", B.KN2COL)])
+@pytest.mark.parametrize("name,variant", MFMA + [("kn2col", B.KN2COL), ("im2row", B.IM2ROW)])
 def test_bf16_integer_data_is_bit_exact(name, variant):
     case = (2, 40, 17, 19, 35, 3, 1)
     announce("bf16 exact-int", name, case)
@@ -132,7 +133,7 @@ def test_bf16_im2col_workspace_holds_the_rounded_patch_matrix():
         np.testing.assert_array_equal(cols[i], want.reshape(cols[i].shape))
 
 
-@pytest.mark.parametrize("name,variant", MFMA + [("kn2col", B.KN2COL)])
+@pytest.mark.parametrize("name,variant", MFMA + [("kn2col", B.KN2COL), ("im2row", B.IM2ROW)])
 @pytest.mark.parametrize("layer", ["cfg5a_vgg_deep56", "cfg5b_vgg_deep28", "cfg5c_vgg_deep14"])
 def test_bf16_full_size_sampled(layer, name, variant):
     L = wl.LAYERS[layer]

@@ -13,7 +13,7 @@ from gpu_util import TOL_F32, announce, assert_within_bound, run_variant
 pytestmark = pytest.mark.gpu
 
 VARIANTS = [("kn2row", B.KN2ROW), ("kn2row_2pass", B.KN2ROW_2PASS), ("im2col", B.IM2COL), ("direct", B.DIRECT),
-            ("kn2col", B.KN2COL)]
+            ("kn2col", B.KN2COL), ("im2row", B.IM2ROW)]
 
 
 @pytest.mark.parametrize("name,variant", VARIANTS)

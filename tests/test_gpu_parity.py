@@ -16,7 +16,7 @@ from gpu_util import TOL_F32, announce, assert_within_bound, run_variant
 pytestmark = pytest.mark.gpu
 
 ALL = [("kn2row", B.KN2ROW), ("kn2row_2pass", B.KN2ROW_2PASS), ("im2col", B.IM2COL), ("direct", B.DIRECT),
-       ("kn2col", B.KN2COL)]
+       ("kn2col", B.KN2COL), ("im2row", B.IM2ROW)]
 
 # (n, c, h, w, m, k, pad): several tiles, ragged tails in every dimension, degenerate sizes
 SMALL = [
@@ -40,8 +40,8 @@ def _skip_unless_supported(variant, case, dtype=B.F32):
     """kn2col reads whole channel vectors (4 floats / 8 bf16); other channel counts are refused."""
     n, c, h, w, m, k, pad = case
     if B.conv_mcmk_check(B.desc(n, c, h, w, m, k, pad, 1, dtype), variant) == B.ERR_UNSUPPORTED:
-        assert variant == B.KN2COL and c % 4 != 0
-        pytest.skip("kn2col needs a channel count that is a multiple of 4")
+        assert variant in B.CHANNELS_LAST and c % 4 != 0
+        pytest.skip("the channels-last variants need a channel count that is a multiple of 4")
 
 
 # channel counts kn2col accepts, otherwise as ragged as SMALL
@@ -70,18 +70,20 @@ def test_small_shapes_match_oracle(name, variant, case):
     assert_within_bound(got, ref, absref, TOL_F32, f"{name} {case}")
 
 
+@pytest.mark.parametrize("name,variant", [("kn2col", B.KN2COL), ("im2row", B.IM2ROW)])
 @pytest.mark.parametrize("case", KN2COL_CASES)
-def test_kn2col_shapes_match_oracle(case):
-    announce("kn2col", case)
+def test_channels_last_shapes_match_oracle(name, variant, case):
+    announce(name, case)
     I, K = _inputs(case, 1500 + sum(case))
     ref, absref = oracle.mcmk(I, K, case[-1])
-    got = run_variant(B.KN2COL, I, K, case[-1])
-    assert_within_bound(got, ref, absref, TOL_F32, f"kn2col {case}")
+    got = run_variant(variant, I, K, case[-1])
+    assert_within_bound(got, ref, absref, TOL_F32, f"{name} {case}")
 
 
 @pytest.mark.parametrize("name,variant", [a for a in ALL if a[1] not in (B.KN2ROW, B.KN2COL)])
-@pytest.mark.parametrize("case", EVEN_K)
+@pytest.mark.parametrize("case", EVEN_K + [(1, 8, 12, 13, 10, 2, 1), (2, 4, 11, 10, 20, 4, 1)])
 def test_even_kernel_sizes(name, variant, case):
+    _skip_unless_supported(variant, case)
     announce("even-k", name, case)
     I, K = _inputs(case, 2000 + sum(case))
     ref, absref = oracle.mcmk(I, K, case[-1])
@@ -155,10 +157,10 @@ def _expected_packing(K, im2col):
     return out
 
 
-@pytest.mark.parametrize("variant", [B.KN2ROW, B.KN2ROW_2PASS, B.IM2COL])
+@pytest.mark.parametrize("variant", [B.KN2ROW, B.KN2ROW_2PASS, B.IM2COL, B.KN2COL, B.IM2ROW])
 def test_prepack_layout(variant):
     import torch
-    m, c, k = 35, 21, 3
+    m, c, k = 35, 20, 3
     announce("prepack", variant)
     K = wl.normal(9, m * c * k * k, 1.0).reshape(m, c, k, k)
     d = B.desc(1, c, 8, 8, m, k, 1)
@@ -167,7 +169,10 @@ def test_prepack_layout(variant):
     B.conv_mcmk_prepack(d, variant, torch.from_numpy(K).cuda(), Kp)
     torch.cuda.synchronize()
     got = Kp.view(torch.float32).cpu().numpy()
-    want = _expected_packing(K, variant == B.IM2COL).reshape(-1)
+    if variant == B.IM2ROW:          # one row per kernel, contraction index ordered (i, j, c)
+        want = _expected_packing(np.ascontiguousarray(K.transpose(0, 2, 3, 1)).reshape(m, k * k * c, 1, 1), True).reshape(-1)
+    else:
+        want = _expected_packing(K, variant == B.IM2COL).reshape(-1)
     assert got.size == want.size
     np.testing.assert_array_equal(got, want)
 
@@ -198,6 +203,18 @@ def test_im2col_workspace_holds_the_patch_matrix():
     cols = ws.view(np.float32).reshape(n, c * k * k, h * w)
     for i in range(n):
         np.testing.assert_array_equal(cols[i], steps.input_patch_matrix(I[i], k, pad).astype(np.float32))
+
+
+def test_im2row_workspace_holds_the_patch_rows():
+    case = (2, 8, 9, 13, 10, 3, 1)
+    announce("im2row-workspace", case)
+    n, c, h, w, m, k, pad = case
+    I, K = _inputs(case, 4444)
+    _, ws = run_variant(B.IM2ROW, I, K, pad, return_ws=True)
+    rows = ws.view(np.float32).reshape(n, h * w, k * k * c)
+    for i in range(n):
+        want = steps.input_patch_matrix_rows(np.ascontiguousarray(I[i].transpose(1, 2, 0)), k, pad)
+        np.testing.assert_array_equal(rows[i], want.astype(np.float32))
 
 
 def test_cvt_f32_bf16_bit_exact():
@@ -277,7 +294,7 @@ def test_stretched_shapes(case):
     K = wl.normal(701 + c, m * c * k * k, 0.5).reshape(m, c, k, k)
     ref, absref = oracle.mcmk(I, K, pad)
     for name, variant in ALL:
-        if variant == B.KN2COL and c % 4:
+        if variant in B.CHANNELS_LAST and c % 4:
             continue
         got = run_variant(variant, I, K, pad)
         assert_within_bound(got, ref, absref, TOL_F32, f"{name} {case}")

@@ -171,6 +171,21 @@ def test_im2col_reformulation_matches(case):
 
 
 @pytest.mark.parametrize("case", CASES)
+def test_im2row_reformulation_matches(case):
+    n, c, h, w, m, k, pad = case
+    I = wl.uniform(55, n * c * h * w, -1, 1).reshape(n, c, h, w)
+    K = wl.normal(56, m * c * k * k, 0.5).reshape(m, c, k, k)
+    O, A = oracle.mcmk(I, K, pad)
+    for i in range(n):
+        got = steps.im2row_mcmk(np.ascontiguousarray(I[i].transpose(1, 2, 0)), K, pad)      # [Q][P][M]
+        assert np.all(np.abs(got.transpose(2, 0, 1) - O[i]) <= 1e-13 * A[i] + 1e-300)
+    rows = steps.input_patch_matrix_rows(np.ascontiguousarray(I[0].transpose(1, 2, 0)), k, pad)
+    cols = steps.input_patch_matrix(I[0], k, pad)
+    # same patches, transposed and with (i, j, c) instead of (c, i, j) ordering
+    np.testing.assert_array_equal(rows.reshape(-1, k * k, c).transpose(2, 1, 0).reshape(c * k * k, -1), cols)
+
+
+@pytest.mark.parametrize("case", CASES)
 def test_kn2row_reformulation_matches(case):
     n, c, h, w, m, k, pad = case
     I = wl.uniform(61, n * c * h * w, -1, 1).reshape(n, c, h, w)
