@@ -298,3 +298,45 @@ def test_stretched_shapes(case):
             continue
         got = run_variant(variant, I, K, pad)
         assert_within_bound(got, ref, absref, TOL_F32, f"{name} {case}")
+
+
+@pytest.mark.parametrize("case", [(2, 40, 28, 28, 48, 3, 1),        # single launch
+                                  (8, 128, 14, 14, 128, 3, 1)])     # channel split: zero-fill kernel + atomics
+def test_calls_can_be_captured_into_a_graph(case):
+    """The library launches only kernels on the caller's stream (no allocation, no synchronisation,
+    no memset node), so a call can be captured once and replayed; every replay must reproduce the
+    eager result bit for bit, also after the input changes."""
+    import torch
+    n, c, h, w, m, k, pad = case
+    announce("graph", case, B.conv_mcmk_describe_plan(B.desc(n, c, h, w, m, k, pad), B.KN2ROW))
+    d = B.desc(n, c, h, w, m, k, pad)
+    dev = torch.device("cuda:0")
+    I1, K = _inputs(case, 8100)
+    I2, _ = _inputs(case, 8200)
+    K_dev = torch.from_numpy(K).to(dev)
+    plan = B.Plan(d, B.KN2ROW, K_dev)
+    I_static = torch.from_numpy(I1).to(dev)
+    eager1 = plan.run(I_static).clone()
+    I_static.copy_(torch.from_numpy(I2).to(dev))
+    eager2 = plan.run(I_static).clone()
+    torch.cuda.synchronize()
+    I_static.copy_(torch.from_numpy(I1).to(dev))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        plan.run(I_static)                      # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        plan.run(I_static)
+    for rep in range(3):
+        for src, want in ((I1, eager1), (I2, eager2)):
+            I_static.copy_(torch.from_numpy(src).to(dev))
+            plan.out.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(plan.out, want), f"replay {rep} differs from the eager result"
+    ref, absref = oracle.mcmk(I2, K, pad)
+    assert_within_bound(plan.out.cpu().numpy(), ref, absref, TOL_F32, f"graph replay {case}")
