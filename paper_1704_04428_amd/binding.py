@@ -49,6 +49,10 @@ def lib():
             raise RuntimeError(
                 f"{LIB_PATH} is missing: build it with `python -m paper_1704_04428_amd.build` "
                 "(there is no CPU fallback)")
+        # torch first: it brings its own copy of the HIP runtime, and the device pointers and streams
+        # handed to the library belong to that copy.  Loading the library before torch would bind its
+        # kernels to whichever libamdhip64 the system resolves instead, and every launch would fail.
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         dp = ctypes.POINTER(Desc)
         vp, sz, i = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
