@@ -15,6 +15,7 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument",
+    "-Rpass-analysis=kernel-resource-usage",       # per-kernel register / LDS / spill report, kept beside the objects
 ]
 JOBS = 8
 TIMEOUT_S = 900      # per translation unit; a compile that takes longer is a bug, not patience
@@ -27,8 +28,33 @@ def units():
 def _compile(name: str) -> str:
     obj = os.path.join(OBJ, name[:-4] + ".o")
     cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, name), "-o", obj]
-    subprocess.run(cmd, check=True, timeout=TIMEOUT_S, stdout=subprocess.DEVNULL, stderr=subprocess.PIPE)
+    done = subprocess.run(cmd, check=True, timeout=TIMEOUT_S, stdout=subprocess.DEVNULL, stderr=subprocess.PIPE)
+    with open(os.path.join(OBJ, name[:-4] + ".usage.txt"), "wb") as f:
+        f.write(done.stderr)
     return obj
+
+
+def resource_usage() -> dict:
+    """{mangled kernel name: {"VGPRs": n, "ScratchSize": n, "LDS": n, "Occupancy": n, ...}} from the last build."""
+    import re
+    out = {}
+    if not os.path.isdir(OBJ):
+        return out
+    for fn in sorted(os.listdir(OBJ)):
+        if not fn.endswith(".usage.txt"):
+            continue
+        name = None
+        with open(os.path.join(OBJ, fn), errors="replace") as f:
+            for line in f:
+                m = re.search(r"remark: .*Function Name: (\S+)", line)
+                if m:
+                    name = m.group(1)
+                    out[name] = {}
+                    continue
+                m = re.search(r"remark:\s+([A-Za-z ]+?)(?: \[[^\]]*\])?: (\d+)", line)
+                if m and name:
+                    out[name][m.group(1).strip().replace(" ", "")] = int(m.group(2))
+    return out
 
 
 def build(force: bool = True) -> str:

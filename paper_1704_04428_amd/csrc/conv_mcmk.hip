@@ -87,7 +87,7 @@ int grid_for(size_t total, int block)
 struct Candidate {
     int shape;     // index into kTileShapes
     int csplit;    // 1 or 2
-    int th, tw, wm, wp;
+    int th, tw, wm, wp, kg;
 };
 
 int run_tile(int dtype, int ks, const TileRequest &rq)
@@ -155,31 +155,35 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
     const long long tiles = (long long)d->n * ceil_div(dm.p, c.tw) * ceil_div(dm.q, c.th) * ceil_div(dm.mb, c.wm);
     const long long wgs = tiles * c.csplit;
     const int npb = ceil_div(c.th * c.tw, 16);
-    const int waves = c.wm * c.wp;
+    const int group_waves = c.wm * c.wp;
+    const int waves = group_waves * c.kg;
     int simd_blocks[4] = {0, 0, 0, 0};
     for (int w = 0; w < waves; ++w) {
-        const int wp = w / c.wm;
+        const int g = w / group_waves;                                  // channel group, rotated by g
+        const int wp = ((w % group_waves + g * c.wm) % group_waves) / c.wm;
         const int rem = npb % c.wp, pbw = ceil_div(npb, c.wp);
         simd_blocks[w % 4] += (rem == 0 || wp < rem) ? pbw : pbw - 1;
     }
     int simd_load = 0;
     for (int i = 0; i < 4; ++i) simd_load = simd_blocks[i] > simd_load ? simd_blocks[i] : simd_load;
     const bool bf16 = d->dtype == CONV_MCMK_BF16;
-    const int chunks = ceil_div(ceil_div(d->c, bf16 ? 32 : 16), c.csplit);
+    // chunks each wave works through (the channel groups of a workgroup share them out)
+    const int chunks = ceil_div(ceil_div(ceil_div(d->c, bf16 ? 32 : 16), c.csplit), c.kg);
     // fp32: 4 MFMAs of 32 cycles per tap and 16-channel chunk; bf16: 1 MFMA of 16 cycles per tap and 32-channel chunk
     const double steps = (double)chunks * ks * ks * (bf16 ? 0.5 : 4.0);
     const long long per_cu = (wgs + kNumCU - 1) / kNumCU;
-    const int can_hold = 16 / waves;                                   // workgroups a CU can hold
+    const int can_hold = c.kg > 1 ? 1 : 16 / waves;                    // workgroups a CU can hold (LDS, VGPRs)
     const long long held = per_cu < can_hold ? per_cu : can_hold;
     const double waves_per_simd = (double)held * waves / 4.0;
     const double pipe_use = waves_per_simd >= 2.0 ? 0.9 : 0.7;
     double us = (double)per_cu * simd_load * steps * 0.0139 / pipe_use + 6.0;
     if (c.csplit > 1) us += 3.0 + 2.0 * (double)d->n * d->m * dm.q * dm.p * 6.25e-6;
+    if (c.kg > 1) us += 1.5;                                            // the closing exchange through LDS
     return us;
 }
 
 // The candidate the cost estimate prefers for the fused kernel (or the one CONV_MCMK_TILE forces:
-// tuning aid, menu index = shape + 6 * (csplit - 1)).
+// tuning aid, menu index = shape + 7 * (csplit - 1)).
 Candidate choose_fused(const conv_mcmk_desc *d, const Dims &dm)
 {
     Candidate best{};
@@ -189,7 +193,12 @@ Candidate choose_fused(const conv_mcmk_desc *d, const Dims &dm)
     if (force && (force[0] < '0' || force[0] > '9')) force = nullptr;
     for (int cs = 1; cs <= 2; ++cs)
         for (int sh = 0; sh < kConvShapes; ++sh, ++index) {
-            const Candidate c{sh, cs, kTileShapes[sh].th, kTileShapes[sh].tw, kTileShapes[sh].wm, kTileShapes[sh].wp};
+            const Candidate c{sh, cs, kTileShapes[sh].th, kTileShapes[sh].tw, kTileShapes[sh].wm, kTileShapes[sh].wp,
+                              kTileShapes[sh].kg};
+            // channel groups exist for fp32 and kernel sides up to 3 only (four groups of double-buffered
+            // 5x5 halo tiles would not fit the 160 KB of LDS) and are an alternative to, not a partner
+            // of, the two-way split
+            if (c.kg > 1 && (d->dtype == CONV_MCMK_BF16 || cs > 1 || d->k > 3)) continue;
             const double cost = (force && atoi(force) == index) ? 0.0 : tile_cost(d, dm, c, d->k);
             if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = c; }
         }
@@ -263,8 +272,8 @@ int conv_mcmk_describe_plan(const conv_mcmk_desc *d, int variant, char *buf, siz
     case CONV_MCMK_KN2COL: {
         const Candidate c = choose_fused(d, dm);
         const long long wgs = (long long)d->n * ceil_div(dm.p, c.tw) * ceil_div(dm.q, c.th) * ceil_div(dm.mb, c.wm) * c.csplit;
-        snprintf(buf, n, "%s fused %s: tile %dx%d, waves %dx%d, channel split %d, %lld workgroups, est %.1f us",
-                 variant == CONV_MCMK_KN2COL ? "kn2col" : "kn2row", type, c.th, c.tw, c.wm, c.wp, c.csplit, wgs,
+        snprintf(buf, n, "%s fused %s: tile %dx%d, waves %dx%d, channel groups %d, channel split %d, %lld workgroups, est %.1f us",
+                 variant == CONV_MCMK_KN2COL ? "kn2col" : "kn2row", type, c.th, c.tw, c.wm, c.wp, c.kg, c.csplit, wgs,
                  tile_cost(d, dm, c, d->k));
         break;
     }

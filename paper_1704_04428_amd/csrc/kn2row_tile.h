@@ -46,10 +46,11 @@ struct TileArgs {
                           // adds its partial sums into a zeroed output (a + b is order-independent)
 };
 
-template <int KS, int TH, int TW, int WM, int WP, int CCH = 16>
+template <int KS, int TH, int TW, int WM, int WP, int CCH = 16, int KG = 1>
 struct TileShape {
     static constexpr int kCC = CCH;                      // channels per chunk, a multiple of 16
-    static constexpr int kThreads = 64 * WM * WP;
+    static constexpr int kGroupThreads = 64 * WM * WP;   // one channel group: WM x WP waves
+    static constexpr int kThreads = kGroupThreads * KG;
     static constexpr int kHT = TH + KS - 1;
     static constexpr int kWT = TW + KS - 1;
     static constexpr int kPos = kHT * kWT;               // halo-tile positions per channel
@@ -59,21 +60,27 @@ struct TileShape {
     static constexpr int kBuf = kCC * kCHS;              // words per LDS buffer
     static constexpr int kNPB = (TH * TW + 15) / 16;     // 16-position blocks per tile
     static constexpr int kPBW = (kNPB + WP - 1) / WP;    // blocks per wave
-    static constexpr int kSlots = (kCC * kPos + kThreads - 1) / kThreads;
-    static constexpr size_t kLdsBytes = 2 * (size_t)kBuf * sizeof(float);
+    static constexpr int kSlots = (kCC * kPos + kGroupThreads - 1) / kGroupThreads;
+    static constexpr size_t kLdsBytes = 2 * (size_t)KG * kBuf * sizeof(float);
 };
 
 // CL = false: input [n][c][h][w], output [n][rows][q][p] (kn2row).
 // CL = true : channels last (c a multiple of 4), input [n][h][w][c], output [n][q][p][rows] -- the layout of the paper's
 //             kn2col variant (section III-A, last paragraph); the packed kernel and the whole
 //             accumulation are the same, only the staging gather and the final store differ.
-template <int KS, int TH, int TW, int WM, int WP, int CCH = 16, bool CL = false>
-__global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a)
+// KG > 1: the workgroup holds KG channel groups of WM x WP waves each.  Group g takes the chunks
+//         g, g+KG, g+2KG, ... of the tile (its own LDS buffers, its own staging), and the groups'
+//         partial sums are added through LDS at the end in a fixed order.  This is the split of the
+//         contraction for layers with too few tiles to fill the chip (small images, deep channels):
+//         no atomics, no zero fill, and -- because group g's waves are rotated by g along the position
+//         axis -- every SIMD ends up with the same number of position blocks.
+template <int KS, int TH, int TW, int WM, int WP, int CCH = 16, bool CL = false, int KG = 1>
+__global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileArgs a)
 {
-    using S = TileShape<KS, TH, TW, WM, WP, CCH>;
+    using S = TileShape<KS, TH, TW, WM, WP, CCH, KG>;
     static_assert(CCH % 16 == 0, "a chunk is a whole number of packed 16-channel groups");
     constexpr int NQ = CCH / 16;                   // packed A vectors per tap and chunk
-    constexpr int CC = S::kCC, NT = S::kThreads, WT = S::kWT, POS = S::kPos, CHS = S::kCHS;
+    constexpr int CC = S::kCC, NT = S::kGroupThreads, WT = S::kWT, POS = S::kPos, CHS = S::kCHS;
     constexpr int PBW = S::kPBW, NPB = S::kNPB, SLOTS = S::kSlots, BUF = S::kBuf;
     // position blocks are dealt evenly to the WP waves: the first REM waves own PBW blocks, the
     // others PBW-1 (all own PBW when the split is exact)
@@ -81,13 +88,18 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a
     constexpr bool kRagged = REM != 0;
     static_assert(NPB >= WP, "every wave needs at least one position block");
 
-    extern __shared__ float lds[];
+    extern __shared__ float lds_all[];
 
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = threadIdx.x & 63;
+    const int wave_all = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int kg = wave_all / (WM * WP);                          // channel group of this wave
+    // waves go to SIMD (wave index % 4); rotating the group's waves by kg along the position axis
+    // gives each SIMD one wave of every position share
+    const int wave = (wave_all % (WM * WP) + kg * WM) % (WM * WP);
+    const int tid = wave * 64 + lane;                             // thread index inside the group
     const int wm = wave % WM;
     const int wp = wave / WM;
+    float *const lds = lds_all + (size_t)kg * 2 * BUF;            // this group's two buffers
 
     // ---- which tile.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2), so
     // the launch index is re-mapped to give every XCD a contiguous run of tiles: the row tiles that
@@ -122,6 +134,7 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a
     const __amdgpu_buffer_rsrc_t in_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(in_img), 0, (int)((size_t)a.c * plane * sizeof(float)), 0x00020000);
     const uint32_t chunk_bytes = (uint32_t)(CC * plane * sizeof(float));
+    const int chunks_total = (a.cg + NQ - 1) / NQ;
     // When the thread count is a multiple of the positions per channel every thread keeps one
     // position and walks the channels in steps of NT/POS: one offset pair serves all its slots.
     constexpr bool kRegular = (NT % POS) == 0;
@@ -173,8 +186,10 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a
             for (int s = 0; s < SLOTS; ++s) {
                 const uint32_t off = kRegular ? g_off[0] + (uint32_t)(s * CSTEP) * (uint32_t)(plane * sizeof(float))
                                               : g_off[kRegular ? 0 : s];
+                // prefetches run past the last chunk; clamped to the first chunk index beyond the data,
+                // they stay out of range (zeros, never used) without the offset growing any further
                 stage[s] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                    in_rsrc, (int)(off + (uint32_t)chunk * chunk_bytes), 0, 0));
+                    in_rsrc, (int)(off + (uint32_t)min(chunk, chunks_total) * chunk_bytes), 0, 0));
             }
         }
     };
@@ -241,10 +256,11 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a
     for (int b = 0; b < PBW; ++b) acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     AFrag a_queue[kDepth];
-    load_chunk(chunk_lo);
+    const int chunk_first = chunk_lo + kg;                        // this group's chunks: first, +KG, +2KG, ...
+    load_chunk(chunk_first);
 #pragma unroll
-    for (int d = 0; d < kDepth; ++d) a_queue[d] = load_a(chunk_lo + d / T, d % T);
-    store_chunk(lds + (chunk_lo & 1) * BUF);
+    for (int d = 0; d < kDepth; ++d) a_queue[d] = load_a(chunk_first + KG * (d / T), d % T);
+    store_chunk(lds);
     __syncthreads();
 
     // One chunk of matrix-core work for NB position blocks (NB is PBW, or PBW-1 for the wave that
@@ -253,7 +269,7 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a
         constexpr int NB = decltype(nb_tag)::value;
         constexpr int VQ = CCH / 4;                // channel quads per chunk
         constexpr int G = T * VQ;                  // steps per chunk: (tap, channel quad)
-        const float *bsrc = lds + (chunk & 1) * BUF;
+        const float *bsrc = lds + (((chunk - chunk_first) / KG) & 1) * BUF;
         float bq[2][NB];                           // B fragments: this step's and the next one's
 #pragma unroll
         for (int b = 0; b < NB; ++b) bq[0][b] = bsrc[b_off[b]];
@@ -262,7 +278,7 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a
             const AFrag a_cur = a_queue[0];
 #pragma unroll
             for (int d = 0; d + 1 < kDepth; ++d) a_queue[d] = a_queue[d + 1];
-            a_queue[kDepth - 1] = load_a(chunk + (t + kDepth) / T, (t + kDepth) % T);
+            a_queue[kDepth - 1] = load_a(chunk + KG * ((t + kDepth) / T), (t + kDepth) % T);
 #pragma unroll
             for (int v = 0; v < VQ; ++v) {
                 const int g = t * VQ + v;          // step number inside the chunk
@@ -293,12 +309,36 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_f32(const TileArgs a
     // The loop body has no data-dependent branch around its loads: the prefetches for "the next
     // chunk" are issued in the last iteration too (A from the last chunk again, input from beyond
     // the last channel, which the buffer range check turns into zeros) and simply go unused.
-    for (int chunk = chunk_lo; chunk < chunk_hi; ++chunk) {
-        load_chunk(chunk + 1);
-        if (kRagged && nb_wave != PBW) compute_chunk(std::integral_constant<int, kRagged ? PBW - 1 : PBW>{}, chunk);
-        else compute_chunk(std::integral_constant<int, PBW>{}, chunk);
-        store_chunk(lds + ((chunk + 1) & 1) * BUF);
+    const int nsteps = (chunk_hi - chunk_lo + KG - 1) / KG;       // the same for every group: barriers match
+    for (int step = 0; step < nsteps; ++step) {
+        const int chunk = chunk_first + step * KG;
+        load_chunk(chunk + KG);
+        if (KG == 1 || chunk < chunk_hi) {                        // wave-uniform
+            if (kRagged && nb_wave != PBW) compute_chunk(std::integral_constant<int, kRagged ? PBW - 1 : PBW>{}, chunk);
+            else compute_chunk(std::integral_constant<int, PBW>{}, chunk);
+        }
+        store_chunk(lds + ((step + 1) & 1) * BUF);
         __syncthreads();
+    }
+
+    // ---- add the channel groups' partial sums: groups 1.. park theirs in LDS (the staging buffers
+    // are free now), group 0 adds them in group order and goes on to write the tile
+    if constexpr (KG > 1) {
+        f32x4 *park = reinterpret_cast<f32x4 *>(lds_all);
+        const int slot = (wm + WM * wp) * PBW;                    // same (wm, wp) in every group
+        if (kg > 0) {
+#pragma unroll
+            for (int b = 0; b < PBW; ++b) park[(((kg - 1) * WM * WP * PBW) + slot + b) * 64 + lane] = acc[b];
+        }
+        __syncthreads();
+        if (kg > 0) return;
+#pragma unroll
+        for (int g = 1; g < KG; ++g)
+#pragma unroll
+            for (int b = 0; b < PBW; ++b) {
+                const f32x4 other = park[(((g - 1) * WM * WP * PBW) + slot + b) * 64 + lane];
+                acc[b] += other;
+            }
     }
 
     // ---- write the tile: accumulator register v of lane l is row 4*(l/16)+v, position l%16

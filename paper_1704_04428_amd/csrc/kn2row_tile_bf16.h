@@ -137,7 +137,7 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs 
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
                     stage[s][e] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(
-                        in_rsrc, (int)(g_off[s] + (uint32_t)e * plane_bytes + (uint32_t)chunk * chunk_bytes), 0, 0);
+                        in_rsrc, (int)(g_off[s] + (uint32_t)e * plane_bytes + (uint32_t)min(chunk, a.cg) * chunk_bytes), 0, 0);
         }
     };
     auto store_chunk = [&](unsigned char *buf) {

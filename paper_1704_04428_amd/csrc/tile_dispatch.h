@@ -8,16 +8,19 @@
 
 namespace mcmk {
 
-// Tile shapes every instantiation file provides.  Index kGemmShape is the plain-GEMM shape
-// (1 x 224 positions, 32-channel chunks) and exists for kernel side 1 only.
+// Tile shapes every instantiation file provides: tile rows x columns, waves along the rows and along
+// the positions, and the number of channel groups (in-workgroup split of the contraction; fp32 only).
+// Index kGemmShape is the plain-GEMM shape (1 x 224 positions, 32-channel chunks) and exists for
+// kernel side 1 only.
 struct TileShapeDesc {
-    int th, tw, wm, wp;
+    int th, tw, wm, wp, kg;
 };
 constexpr TileShapeDesc kTileShapes[] = {
-    {14, 14, 4, 2}, {14, 14, 2, 4}, {14, 14, 1, 4}, {16, 16, 4, 2}, {16, 16, 2, 4}, {16, 16, 1, 4}, {1, 224, 4, 2},
+    {14, 14, 4, 2, 1}, {14, 14, 2, 4, 1}, {14, 14, 1, 4, 1}, {16, 16, 4, 2, 1}, {16, 16, 2, 4, 1}, {16, 16, 1, 4, 1},
+    {14, 14, 1, 4, 4}, {1, 224, 4, 2, 1},
 };
-constexpr int kConvShapes = 6;
-constexpr int kGemmShape = 6;
+constexpr int kConvShapes = 7;
+constexpr int kGemmShape = 7;
 
 struct TileRequest {
     TileArgs args;       // tiles_x, tiles_y and row_tiles are filled in by the launcher

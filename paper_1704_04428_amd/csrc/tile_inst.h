@@ -10,7 +10,7 @@
 namespace mcmk {
 namespace {
 
-template <int TH, int TW, int WM, int WP, int CCH = 16, bool CL = false>
+template <int TH, int TW, int WM, int WP, int CCH = 16, bool CL = false, int KG = 1>
 int launch_shape(const TileRequest &rq)
 {
     TileArgs a = rq.args;
@@ -36,8 +36,20 @@ int launch_shape(const TileRequest &rq)
     hipLaunchKernelGGL((kn2row_tile_bf16<MCMK_KS, TH, TW, WM, WP, CL>), dim3((unsigned)blocks), dim3(S::kThreads),
                        S::kLdsBytes, rq.stream, a);
 #else
-    using S = TileShape<MCMK_KS, TH, TW, WM, WP, CCH>;
-    hipLaunchKernelGGL((kn2row_tile_f32<MCMK_KS, TH, TW, WM, WP, CCH, CL>), dim3((unsigned)blocks), dim3(S::kThreads),
+    using S = TileShape<MCMK_KS, TH, TW, WM, WP, CCH, KG>;
+    if (S::kLdsBytes > 65536) {
+        // more than 64 KiB of dynamic LDS has to be allowed per kernel, once per device
+        static bool allowed[64] = {};
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 1;
+        if (!allowed[dev]) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&kn2row_tile_f32<MCMK_KS, TH, TW, WM, WP, CCH, CL, KG>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::kLdsBytes) != hipSuccess)
+                return 1;
+            allowed[dev] = true;
+        }
+    }
+    hipLaunchKernelGGL((kn2row_tile_f32<MCMK_KS, TH, TW, WM, WP, CCH, CL, KG>), dim3((unsigned)blocks), dim3(S::kThreads),
                        S::kLdsBytes, rq.stream, a);
 #endif
     return hipGetLastError() == hipSuccess ? 0 : 1;
@@ -63,8 +75,11 @@ int MCMK_FN(const TileRequest &rq)
         case 3: return launch_shape<16, 16, 4, 2, 16, true>(rq);
         case 4: return launch_shape<16, 16, 2, 4, 16, true>(rq);
         case 5: return launch_shape<16, 16, 1, 4, 16, true>(rq);
+#if !MCMK_BF16 && MCMK_KS <= 3
+        case 6: return launch_shape<14, 14, 1, 4, 16, true, 4>(rq);
+#endif
 #if MCMK_KS == 1
-        case 6: return launch_shape<1, 224, 4, 2, 32, true>(rq);
+        case 7: return launch_shape<1, 224, 4, 2, 32, true>(rq);
 #endif
         default: return 2;
         }
@@ -76,8 +91,11 @@ int MCMK_FN(const TileRequest &rq)
     case 3: return launch_shape<16, 16, 4, 2>(rq);
     case 4: return launch_shape<16, 16, 2, 4>(rq);
     case 5: return launch_shape<16, 16, 1, 4>(rq);
+#if !MCMK_BF16 && MCMK_KS <= 3
+    case 6: return launch_shape<14, 14, 1, 4, 16, false, 4>(rq);   // four channel groups in the workgroup
+#endif
 #if MCMK_KS == 1
-    case 6: return launch_shape<1, 224, 4, 2, 32>(rq);     // plain GEMM: deeper chunks, fewer barriers
+    case 7: return launch_shape<1, 224, 4, 2, 32>(rq);     // plain GEMM: deeper chunks, fewer barriers
 #endif
     default: return 2;
     }

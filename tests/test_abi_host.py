@@ -121,10 +121,11 @@ def test_plan_selection_for_benchmark_layers(lib, monkeypatch):
     from paper_1704_04428_amd import workloads as wl
     monkeypatch.delenv("CONV_MCMK_TILE", raising=False)
     want = {
-        "cfg4_vgg_early": "tile 14x14, waves 4x2, channel split 1, 256 workgroups",
-        "cfg5a_vgg_deep56": "tile 14x14, waves 4x2, channel split 1, 512 workgroups",
-        "cfg5b_vgg_deep28": "tile 14x14, waves 4x2, channel split 1, 256 workgroups",
-        "cfg5c_vgg_deep14": "tile 14x14, waves 2x4, channel split 2, 256 workgroups",
+        "cfg4_vgg_early": "tile 14x14, waves 4x2, channel groups 1, channel split 1, 256 workgroups",
+        "cfg5a_vgg_deep56": "tile 14x14, waves 4x2, channel groups 1, channel split 1, 512 workgroups",
+        "cfg5b_vgg_deep28": "tile 14x14, waves 4x2, channel groups 1, channel split 1, 256 workgroups",
+        # 14x14 images: 64 tiles of 64 kernels cannot fill 256 CUs, so the contraction is split four ways
+        "cfg5c_vgg_deep14": "tile 14x14, waves 1x4, channel groups 4, channel split 1, 256 workgroups",
     }
     for name, text in want.items():
         L = wl.LAYERS[name]
@@ -139,4 +140,22 @@ def test_plan_selection_for_benchmark_layers(lib, monkeypatch):
     with pytest.raises(B.ConvMcmkError):
         B.conv_mcmk_describe_plan(B.desc(1, 8, 10, 10, 8, 3, 1, stride=2), B.KN2ROW)
     monkeypatch.setenv("CONV_MCMK_TILE", "5")
-    assert "tile 16x16, waves 1x4, channel split 1" in B.conv_mcmk_describe_plan(d, B.KN2ROW)
+    assert "tile 16x16, waves 1x4, channel groups 1, channel split 1" in B.conv_mcmk_describe_plan(d, B.KN2ROW)
+    monkeypatch.setenv("CONV_MCMK_TILE", "6")
+    assert "channel groups 4" in B.conv_mcmk_describe_plan(d, B.KN2ROW)
+    # an entry the operand type does not have is ignored: the selector's own choice stands
+    assert "channel groups 1" in B.conv_mcmk_describe_plan(B.desc(1, 8, 10, 10, 8, 3, 1, 1, B.BF16), B.KN2ROW)
+
+
+def test_kernel_register_budget():
+    """The compiler's per-kernel report of the last build: nothing spills to scratch, and the 8-wave
+    tile kernels stay within 128 vector registers (two workgroups per compute unit need that)."""
+    from paper_1704_04428_amd import build
+    usage = build.resource_usage()
+    if not usage:
+        pytest.skip("no compiler resource report beside the objects (library built elsewhere)")
+    spilling = {k: v for k, v in usage.items() if v.get("VGPRsSpill", 0) or v.get("ScratchSize", 0)}
+    assert not spilling, spilling
+    wide = [v for k, v in usage.items() if "kn2row_tile_f32ILi3ELi14ELi14ELi4ELi2ELi16E" in k]
+    assert len(wide) == 2                                   # NCHW and channels-last
+    assert all(v["VGPRs"] + v.get("AGPRs", 0) <= 128 for v in wide), wide
