@@ -4,8 +4,9 @@ Only tests, the smoke check and the benchmark's cpu_baseline leg may import this
 package.  It imports nothing from the GPU package and the GPU package imports
 nothing from here.
 
-  mcmk(I, K, pad)              whole output in float64 (+ sum |K||I| per element)
-  mcmk_at(I, K, pad, points)   selected outputs
+  mcmk(I, K, pad, stride=1)              whole output in float64 (+ sum |K||I| per element)
+  mcmk_at(I, K, pad, points, stride=1)   selected outputs
+  bias_relu(O, bias, relu)               the per-kernel offset and the rectifier applied to an output
   oracle.steps                 the im2col and kn2row algorithms step by step (numpy, float64)
 """
 from __future__ import annotations
@@ -29,9 +30,9 @@ def _load():
         fp = ctypes.POINTER(ctypes.c_float)
         dp = ctypes.POINTER(ctypes.c_double)
         ip = ctypes.POINTER(ctypes.c_int)
-        lib.mcmk_oracle_f64.argtypes = [i] * 7 + [fp, fp, dp, dp]
+        lib.mcmk_oracle_f64.argtypes = [i] * 8 + [fp, fp, dp, dp]
         lib.mcmk_oracle_f64.restype = i
-        lib.mcmk_oracle_f64_at.argtypes = [i] * 7 + [fp, fp, i, ip, dp, dp]
+        lib.mcmk_oracle_f64_at.argtypes = [i] * 8 + [fp, fp, i, ip, dp, dp]
         lib.mcmk_oracle_f64_at.restype = i
         _lib = lib
     return _lib
@@ -63,7 +64,7 @@ def _d(a):
     return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
 
 
-def mcmk(I, K, pad):
+def mcmk(I, K, pad, stride=1):
     """Eq. 1-3 evaluated directly.  Returns (O, absO), both float64 [N][M][Q][P]
     (batch axis dropped when I is 3-D); absO = sum of |K||I| over the same terms."""
     squeeze = np.ndim(I) == 3
@@ -71,18 +72,18 @@ def mcmk(I, K, pad):
     K = _check(I, K)
     n, c, h, w = I.shape
     m, _, k, _ = K.shape
-    q, p = h + 2 * pad - k + 1, w + 2 * pad - k + 1
-    if q < 1 or p < 1:
+    if h + 2 * pad - k + 1 < 1 or w + 2 * pad - k + 1 < 1 or stride < 1:
         raise ValueError("empty output")
+    q, p = (h + 2 * pad - k) // stride + 1, (w + 2 * pad - k) // stride + 1
     O = np.empty((n, m, q, p), dtype=np.float64)
     A = np.empty_like(O)
-    rc = _load().mcmk_oracle_f64(n, c, h, w, m, k, pad, _f(I), _f(K), _d(O), _d(A))
+    rc = _load().mcmk_oracle_f64(n, c, h, w, m, k, pad, stride, _f(I), _f(K), _d(O), _d(A))
     if rc:
         raise ValueError(f"oracle rejected the shape (code {rc})")
     return (O[0], A[0]) if squeeze else (O, A)
 
 
-def mcmk_at(I, K, pad, points):
+def mcmk_at(I, K, pad, points, stride=1):
     """Selected outputs: points is [npts][4] of (n, m, q, p).  Returns (O, absO), float64 [npts]."""
     I = _as4d(I)
     K = _check(I, K)
@@ -91,8 +92,20 @@ def mcmk_at(I, K, pad, points):
     pts = np.ascontiguousarray(points, dtype=np.int32).reshape(-1, 4)
     O = np.empty(len(pts), dtype=np.float64)
     A = np.empty_like(O)
-    rc = _load().mcmk_oracle_f64_at(n, c, h, w, m, k, pad, _f(I), _f(K), len(pts),
+    rc = _load().mcmk_oracle_f64_at(n, c, h, w, m, k, pad, stride, _f(I), _f(K), len(pts),
                                     pts.ctypes.data_as(ctypes.POINTER(ctypes.c_int)), _d(O), _d(A))
     if rc:
         raise ValueError(f"oracle rejected the request (code {rc})")
     return O, A
+
+
+def bias_relu(O, bias=None, relu=False):
+    """What commonly follows the convolution in a network layer (not part of the paper's method, which
+    stops at Eq. 3): add bias[m] to every element of plane m of O[...][M][Q][P], then clamp negative
+    values to zero.  float64 in, float64 out."""
+    O = np.asarray(O, dtype=np.float64)
+    if bias is not None:
+        O = O + np.asarray(bias, dtype=np.float64).reshape((-1, 1, 1))
+    if relu:
+        O = np.maximum(O, 0.0)
+    return O

@@ -21,7 +21,11 @@
  *     side; contributions from outside the image are dropped, which is the
  *     same thing as the out-of-bounds discard of section III-A;
  *   - layouts: I[N][C][H][W], K[M][C][k][k] (row tap, then column tap),
- *     O[N][M][Q][P], Q = H + 2 pad - k + 1 rows, P = W + 2 pad - k + 1 columns.
+ *     O[N][M][Q][P], Q = H + 2 pad - k + 1 rows, P = W + 2 pad - k + 1 columns;
+ *   - strides: the paper leaves them out (section II-A treats unit stride only).
+ *     The generalisation taken here is the usual one: output (q, p) of a
+ *     stride-s convolution is output (s q, s p) of the unit-stride one, for
+ *     Q = floor((H + 2 pad - k) / s) + 1 rows and likewise P columns.
  *
  * Pinned by tests/test_oracle_pins.py (hand-worked examples, delta kernels,
  * linearity, constant-input closed form, im2col and kn2row reformulations,
@@ -30,15 +34,17 @@
 #include <math.h>
 #include <stddef.h>
 
-static int bad_shape(int n, int c, int h, int w, int m, int k, int pad)
+static int bad_shape(int n, int c, int h, int w, int m, int k, int pad, int stride)
 {
-    if (n < 1 || c < 1 || h < 1 || w < 1 || m < 1 || k < 1 || pad < 0) return 1;
+    if (n < 1 || c < 1 || h < 1 || w < 1 || m < 1 || k < 1 || pad < 0 || stride < 1) return 1;
     if (h + 2 * pad - k + 1 < 1 || w + 2 * pad - k + 1 < 1) return 1;
     return 0;
 }
 
+static int out_size(int in, int k, int pad, int stride) { return (in + 2 * pad - k) / stride + 1; }
+
 /* One output element: Eq. 1 inside Eq. 2.  Also returns sum |K||I| over the same terms. */
-static void one_output(int c, int h, int w, int k, int pad,
+static void one_output(int c, int h, int w, int k, int pad, int stride,
                        const float *img /* [C][H][W] */, const float *ker /* [C][k][k] */,
                        int q, int p, double *value, double *absvalue)
 {
@@ -46,8 +52,8 @@ static void one_output(int c, int h, int w, int k, int pad,
     for (int ch = 0; ch < c; ++ch)
         for (int i = 0; i < k; ++i)
             for (int j = 0; j < k; ++j) {
-                int y = q - pad + i;
-                int x = p - pad + j;
+                int y = q * stride - pad + i;
+                int x = p * stride - pad + j;
                 if (y < 0 || y >= h || x < 0 || x >= w) continue;
                 double a = (double)img[((size_t)ch * h + y) * w + x];
                 double b = (double)ker[((size_t)ch * k + i) * k + j];
@@ -62,18 +68,18 @@ static void one_output(int c, int h, int w, int k, int pad,
  * Whole output.  O and absO are [N][M][Q][P] doubles; absO may be NULL.
  * Returns 0, or 1 when the shape is not a valid convolution.
  */
-int mcmk_oracle_f64(int n, int c, int h, int w, int m, int k, int pad,
+int mcmk_oracle_f64(int n, int c, int h, int w, int m, int k, int pad, int stride,
                     const float *I, const float *K, double *O, double *absO)
 {
-    if (bad_shape(n, c, h, w, m, k, pad) || !I || !K || !O) return 1;
-    const int Q = h + 2 * pad - k + 1, P = w + 2 * pad - k + 1;
+    if (bad_shape(n, c, h, w, m, k, pad, stride) || !I || !K || !O) return 1;
+    const int Q = out_size(h, k, pad, stride), P = out_size(w, k, pad, stride);
 #pragma omp parallel for collapse(2) schedule(static)
     for (int in = 0; in < n; ++in)
         for (int im = 0; im < m; ++im)
             for (int q = 0; q < Q; ++q)
                 for (int p = 0; p < P; ++p) {
                     double v, a;
-                    one_output(c, h, w, k, pad, I + (size_t)in * c * h * w,
+                    one_output(c, h, w, k, pad, stride, I + (size_t)in * c * h * w,
                                K + (size_t)im * c * k * k, q, p, &v, &a);
                     size_t o = (((size_t)in * m + im) * Q + q) * P + p;
                     O[o] = v;
@@ -87,12 +93,12 @@ int mcmk_oracle_f64(int n, int c, int h, int w, int m, int k, int pad,
  * get npts doubles.  Used where the full output is too slow to compute.
  * Returns 0, 1 for a bad shape, 2 for a point outside the output.
  */
-int mcmk_oracle_f64_at(int n, int c, int h, int w, int m, int k, int pad,
+int mcmk_oracle_f64_at(int n, int c, int h, int w, int m, int k, int pad, int stride,
                        const float *I, const float *K,
                        int npts, const int *pts, double *O, double *absO)
 {
-    if (bad_shape(n, c, h, w, m, k, pad) || !I || !K || !O || !pts || npts < 0) return 1;
-    const int Q = h + 2 * pad - k + 1, P = w + 2 * pad - k + 1;
+    if (bad_shape(n, c, h, w, m, k, pad, stride) || !I || !K || !O || !pts || npts < 0) return 1;
+    const int Q = out_size(h, k, pad, stride), P = out_size(w, k, pad, stride);
     for (int t = 0; t < npts; ++t) {
         const int *pt = pts + 4 * t;
         if (pt[0] < 0 || pt[0] >= n || pt[1] < 0 || pt[1] >= m ||
@@ -102,7 +108,7 @@ int mcmk_oracle_f64_at(int n, int c, int h, int w, int m, int k, int pad,
     for (int t = 0; t < npts; ++t) {
         const int *pt = pts + 4 * t;
         double v, a;
-        one_output(c, h, w, k, pad, I + (size_t)pt[0] * c * h * w,
+        one_output(c, h, w, k, pad, stride, I + (size_t)pt[0] * c * h * w,
                    K + (size_t)pt[1] * c * k * k, pt[2], pt[3], &v, &a);
         O[t] = v;
         if (absO) absO[t] = a;

@@ -28,13 +28,13 @@ def _rand_int_case(seed, n, c, h, w, m, k):
 
 def test_golden_hand_worked(golden_dir):
     files = sorted(glob.glob(os.path.join(golden_dir, "*.json")))
-    assert len(files) >= 3
+    assert len(files) >= 4
     for path in files:
         with open(path) as f:
             g = json.load(f)
         I = np.array(g["I"], dtype=np.float32)
         K = np.array(g["K"], dtype=np.float32)
-        O, _ = oracle.mcmk(I, K, g["pad"])
+        O, _ = oracle.mcmk(I, K, g["pad"], g.get("stride", 1))
         np.testing.assert_array_equal(O, np.array(g["O"], dtype=np.float64), err_msg=path)
 
 
@@ -314,3 +314,88 @@ def test_generator_is_reproducible_and_distributed_as_stated():
     assert [int(v) for v in z] == [0xE220A8397B1DCDAF, 0x6E789E6AA1B965F4]
     z = wl.splitmix64(1234567, np.arange(2))
     assert [int(v) for v in z] == [6457827717110365317, 3203168211198807973]
+
+
+# ------------------------------------------------------------------ strides (generalisation; section II-A treats unit stride only)
+
+STRIDED = [
+    # n, c, h, w, m, k, pad, stride
+    (1, 2, 7, 9, 2, 3, 1, 2),
+    (2, 3, 8, 11, 3, 3, 0, 2),
+    (1, 2, 9, 8, 2, 5, 2, 3),
+    (1, 3, 6, 7, 2, 1, 0, 2),
+    (1, 2, 10, 6, 2, 2, 1, 2),
+    (1, 1, 5, 5, 1, 3, 1, 4),
+    (1, 2, 12, 13, 2, 7, 3, 2),
+]
+
+
+@pytest.mark.parametrize("case", STRIDED)
+def test_strided_output_is_the_unit_stride_output_subsampled(case):
+    """The definition of a stride: the same sums, kept at every s-th row and column only.  The
+    unit-stride oracle is pinned above; integer data makes the comparison exact."""
+    n, c, h, w, m, k, pad, s = case
+    I, K = _rand_int_case(300 + s, n, c, h, w, m, k)
+    full, full_abs = oracle.mcmk(I, K, pad)
+    O, A = oracle.mcmk(I, K, pad, s)
+    assert O.shape == (n, m, (h + 2 * pad - k) // s + 1, (w + 2 * pad - k) // s + 1)
+    np.testing.assert_array_equal(O, full[:, :, ::s, ::s])
+    np.testing.assert_array_equal(A, full_abs[:, :, ::s, ::s])
+
+
+def test_strided_delta_kernel_picks_every_second_pixel():
+    c, h, w, k, pad, s = 2, 7, 8, 3, 1, 2
+    I = wl.uniform(311, c * h * w, -1.0, 1.0).reshape(c, h, w)
+    for i0 in range(k):
+        for j0 in range(k):
+            K = np.zeros((1, c, k, k), dtype=np.float32)
+            K[0, 1, i0, j0] = 1.0
+            O, _ = oracle.mcmk(I, K, pad, s)
+            for q in range(O.shape[1]):
+                for p in range(O.shape[2]):
+                    y, x = s * q - pad + i0, s * p - pad + j0
+                    want = float(I[1, y, x]) if 0 <= y < h and 0 <= x < w else 0.0
+                    assert O[0, q, p] == want
+
+
+@pytest.mark.parametrize("case", STRIDED)
+def test_strided_reformulations_match(case):
+    """im2col / im2row keep only the patches a stride uses; kn2row / kn2col keep the GEMM and
+    subsample in the post pass.  All four must reproduce the strided sum."""
+    n, c, h, w, m, k, pad, s = case
+    I = wl.uniform(321, n * c * h * w, -1, 1).reshape(n, c, h, w)
+    K = wl.normal(322, m * c * k * k, 0.5).reshape(m, c, k, k)
+    O, A = oracle.mcmk(I, K, pad, s)
+    for i in range(n):
+        hwc = np.ascontiguousarray(I[i].transpose(1, 2, 0))
+        for got in (steps.im2col_mcmk(I[i], K, pad, s), steps.kn2row_mcmk(I[i], K, pad, s),
+                    steps.im2row_mcmk(hwc, K, pad, s).transpose(2, 0, 1), steps.kn2col_mcmk(hwc, K, pad, s).transpose(2, 0, 1)):
+            assert got.shape == O[i].shape
+            assert np.all(np.abs(got - O[i]) <= 1e-13 * A[i] + 1e-300)
+
+
+def test_strided_sampled_outputs_equal_full_output():
+    n, c, h, w, m, k, pad, s = 2, 3, 9, 10, 4, 3, 1, 2
+    I = wl.uniform(331, n * c * h * w, -1, 1).reshape(n, c, h, w)
+    K = wl.normal(332, m * c * k * k, 0.5).reshape(m, c, k, k)
+    O, A = oracle.mcmk(I, K, pad, s)
+    pts = [(a, b, q, p) for a in range(n) for b in range(m) for q in range(O.shape[2]) for p in range(O.shape[3])][::7]
+    Os, As = oracle.mcmk_at(I, K, pad, pts, s)
+    np.testing.assert_array_equal(Os, np.array([O[t] for t in pts]))
+    np.testing.assert_array_equal(As, np.array([A[t] for t in pts]))
+    with pytest.raises(ValueError):
+        oracle.mcmk_at(I, K, pad, [(0, 0, O.shape[2], 0)], s)          # a row the strided output does not have
+
+
+# ------------------------------------------------------------------ bias and rectifier (layer epilogue; not in the paper)
+
+def test_bias_relu_closed_forms():
+    O = np.array([[[-2.0, 0.5], [1.5, -0.25]], [[3.0, -3.0], [0.0, 1.0]]])       # [M=2][2][2]
+    bias = np.array([1.0, -2.0])
+    np.testing.assert_array_equal(oracle.bias_relu(O), O)
+    np.testing.assert_array_equal(oracle.bias_relu(O, bias), [[[-1.0, 1.5], [2.5, 0.75]], [[1.0, -5.0], [-2.0, -1.0]]])
+    np.testing.assert_array_equal(oracle.bias_relu(O, bias, True), [[[0.0, 1.5], [2.5, 0.75]], [[1.0, 0.0], [0.0, 0.0]]])
+    np.testing.assert_array_equal(oracle.bias_relu(O, None, True), [[[0.0, 0.5], [1.5, 0.0]], [[3.0, 0.0], [0.0, 1.0]]])
+    # a batch axis in front is carried along; the bias still goes with the kernel axis
+    np.testing.assert_array_equal(oracle.bias_relu(np.stack([O, -O]), bias, True)[1],
+                                  np.maximum(-O + bias.reshape(2, 1, 1), 0.0))
