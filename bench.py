@@ -72,11 +72,13 @@ def bench_layer(L, variants, steps, warmup, I_dev=None, K_dev=None, dtype=0):
         I_bf = torch.empty(I_dev.shape, dtype=torch.bfloat16, device=dev)
         B.conv_mcmk_cvt_f32_bf16(I_dev, I_bf)
         I_dev = I_bf
-    d = B.desc(L.n, L.c, L.h, L.w, L.m, L.k, L.pad, 1, dtype)
+    d = B.desc(L.n, L.c, L.h, L.w, L.m, L.k, L.pad, L.stride, dtype)
     I_cl = None
     out = {}
     for name in variants:
-        variant = B.VARIANTS[name]
+        # two entry points that are not variants of their own: the fused kernel with the bias /
+        # rectifier epilogue, and the 1 x 1 building block called directly
+        variant = B.KN2ROW if name in ("kn2row_bias_relu", "1x1") else B.VARIANTS[name]
         if variant in B.CHANNELS_LAST and L.c % (8 if dtype == B.BF16 else 4):
             continue
         plan = B.Plan(d, variant, K_dev)
@@ -85,12 +87,19 @@ def bench_layer(L, variants, steps, warmup, I_dev=None, K_dev=None, dtype=0):
             if I_cl is None:
                 I_cl = I_dev.permute(0, 2, 3, 1).contiguous()
             I_use = I_cl
+        if name == "kn2row_bias_relu":
+            bias = torch.full((L.m,), -0.05, dtype=torch.float32, device=dev)
+            run = lambda: B.conv_mcmk_kn2row_bias_relu(d, I_use, plan.kernel, bias, 1, plan.out)   # noqa: E731
+        elif name == "1x1":
+            run = lambda: B.conv_mcmk_1x1(d, I_use, plan.kernel, plan.out)                         # noqa: E731
+        else:
+            run = lambda: plan.run(I_use)                                                          # noqa: E731
         torch.cuda.synchronize()
         if steps is None:
-            n_steps, n_warm = auto_counts(lambda: plan.run(I_use))
+            n_steps, n_warm = auto_counts(run)
         else:
             n_steps, n_warm = steps, warmup
-        wall_ms, dev_ms = time_calls(lambda: plan.run(I_use), n_steps, n_warm)
+        wall_ms, dev_ms = time_calls(run, n_steps, n_warm)
         out[name] = {
             "ms": round(dev_ms, 5),
             "gflops": round(L.flops / (dev_ms * 1e-3) / 1e9, 1),
@@ -226,6 +235,17 @@ def main():
                 r["bf16"] = b
             log(name, json.dumps(r))
         result["table"] = table
+        # beyond the paper: stride 2, an even kernel side, the 1 x 1 block on its own, the epilogue
+        extras = {}
+        for name, layer in wl.GENERALISED_LAYERS.items():
+            variants = ["kn2row", "kn2col", "im2col"] + (["1x1"] if layer.k == 1 else [])
+            extras[name] = bench_layer(layer, variants, None, None)
+            extras[name]["bf16"] = bench_layer(layer, variants, None, None, dtype=B.BF16)
+            log(name, json.dumps(extras[name]))
+        extras["cfg5a_bias_relu"] = bench_layer(L, ["kn2row", "kn2row_bias_relu"], None, None, I_dev, K_dev) \
+            if L.name == DEFAULT_WORKLOAD else None
+        log("cfg5a_bias_relu", json.dumps(extras["cfg5a_bias_relu"]))
+        result["generalisations"] = extras
     print(json.dumps(result), flush=True)
 
 

@@ -5,11 +5,13 @@
  * The operation (paper Eq. 1-3): for every image n, kernel m and output
  * position (q, p)
  *
- *     O[n][m][q][p] = sum_c sum_i sum_j  I[n][c][q - pad + i][p - pad + j] * K[m][c][i][j]
+ *     O[n][m][q][p] = sum_c sum_i sum_j  I[n][c][s q - pad + i][s p - pad + j] * K[m][c][i][j]
  *
  * with terms whose input coordinate falls outside the image dropped (zero
- * padding), no kernel flip, stride 1.  Q = H + 2 pad - k + 1 rows and
- * P = W + 2 pad - k + 1 columns.
+ * padding) and no kernel flip.  The paper treats stride s = 1 (section II-A),
+ * where Q = H + 2 pad - k + 1 rows and P = W + 2 pad - k + 1 columns; as a
+ * generalisation the library also takes s > 1, the unit-stride result kept at
+ * every s-th row and column: Q = floor((H + 2 pad - k) / s) + 1, P likewise.
  *
  * Conventions common to every entry point
  *   - All tensors are dense, row-major, in DEVICE memory, 16-byte aligned, and
@@ -43,7 +45,7 @@ typedef struct conv_mcmk_desc {
     int32_t m;       /* kernels (output channels), >= 1 */
     int32_t k;       /* kernel side, >= 1 (square kernels) */
     int32_t pad;     /* zero padding on every side, >= 0 */
-    int32_t stride;  /* must be 1: the paper leaves strided convolution out (section II-A) */
+    int32_t stride;  /* >= 1; 1 is the paper's case (section II-A).  The fused variants take 1 and 2 */
     int32_t dtype;   /* CONV_MCMK_F32 or CONV_MCMK_BF16 */
 } conv_mcmk_desc;
 
@@ -66,8 +68,8 @@ enum {
 enum {
     CONV_MCMK_OK              = 0,
     CONV_MCMK_ERR_NULL        = 1, /* a required pointer is NULL */
-    CONV_MCMK_ERR_SHAPE       = 2, /* a dimension < 1, pad < 0, empty output, or a tensor too large (one image of 2^29 or more input elements, 2^31 or more output elements) */
-    CONV_MCMK_ERR_UNSUPPORTED = 3, /* stride != 1, unknown dtype or variant, or a k / dtype the variant does not implement */
+    CONV_MCMK_ERR_SHAPE       = 2, /* a dimension or the stride < 1, pad < 0, empty output, or a tensor too large (one image of 2^29 or more input elements, 2^31 or more output elements) */
+    CONV_MCMK_ERR_UNSUPPORTED = 3, /* unknown dtype or variant, or a k / stride / dtype / channel count the variant does not implement */
     CONV_MCMK_ERR_WORKSPACE   = 4, /* workspace missing or smaller than conv_mcmk_workspace_bytes() */
     CONV_MCMK_ERR_DEVICE      = 5, /* the HIP runtime refused a launch */
     CONV_MCMK_ERR_ALIGN       = 6  /* a pointer is not 16-byte aligned */
@@ -129,8 +131,11 @@ int conv_mcmk_prepack(const conv_mcmk_desc *desc, int variant, const void *K_dev
  *           except conv_mcmk_direct, which takes the plain float K[M][C][k][k]
  *   O_dev   output, float
  *   ws, ws_bytes  scratch of at least conv_mcmk_workspace_bytes(); may be NULL / 0 when that is 0
- * conv_mcmk_kn2row implements k = 1, 3, 5, 7 (other k: CONV_MCMK_ERR_UNSUPPORTED; the other
- * variants take any k >= 1).  conv_mcmk_direct implements CONV_MCMK_F32 only.
+ * conv_mcmk_kn2row implements k = 1 .. 7 and stride 1 or 2 (otherwise CONV_MCMK_ERR_UNSUPPORTED; the
+ * other variants take any k >= 1 and any stride >= 1).  conv_mcmk_direct implements CONV_MCMK_F32 only.
+ * With a stride the two-pass variant still forms all k*k*M x H*W products (the GEMM of section III-A
+ * has no notion of an output position) and subsamples in the post pass; im2col and im2row build
+ * only the patches that are used.
  * Results are bit-reproducible from call to call: where conv_mcmk_kn2row splits the channels over two
  * workgroups it adds exactly two partial sums into a zeroed output, which is order-independent.
  */
@@ -151,7 +156,7 @@ int conv_mcmk_direct(const conv_mcmk_desc *desc, const void *I_dev, const void *
  *   Kp_dev  conv_mcmk_prepack(desc, CONV_MCMK_KN2COL): physically the KN2ROW packing (the matrix-core
  *           operand order does not care which of the two GEMM operands the kernel matrix is called)
  *   O_dev   output O[N][Q][P][M], float
- * No workspace; k = 1, 3, 5, 7; otherwise as conv_mcmk_kn2row.
+ * No workspace; k = 1 .. 7, stride 1 or 2; otherwise as conv_mcmk_kn2row.
  */
 int conv_mcmk_kn2col(const conv_mcmk_desc *desc, const void *I_dev, const void *Kp_dev, void *O_dev,
                      void *ws, size_t ws_bytes, void *stream);
@@ -167,6 +172,28 @@ int conv_mcmk_kn2col(const conv_mcmk_desc *desc, const void *I_dev, const void *
  */
 int conv_mcmk_im2row(const conv_mcmk_desc *desc, const void *I_dev, const void *Kp_dev, void *O_dev,
                      void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * The fused variants followed by what a network layer usually applies next (neither is part of the
+ * paper's method, which ends at Eq. 3; both act on the finished fp32 sums in registers, so O is still
+ * written once):  O = O + bias[m], then O = max(O, 0) when relu != 0 (a NaN stays a NaN).
+ *   bias_dev  float[M] in device memory, 4-byte aligned, or NULL for no bias
+ *   relu      0 or 1
+ * Layouts, packed kernel, supported k / stride and errors as conv_mcmk_kn2row / conv_mcmk_kn2col.
+ * No workspace.  (The channel split over two workgroups is not used here: partial sums cannot be rectified.)
+ */
+int conv_mcmk_kn2row_bias_relu(const conv_mcmk_desc *desc, const void *I_dev, const void *Kp_dev,
+                               const float *bias_dev, int relu, void *O_dev, void *stream);
+int conv_mcmk_kn2col_bias_relu(const conv_mcmk_desc *desc, const void *I_dev, const void *Kp_dev,
+                               const float *bias_dev, int relu, void *O_dev, void *stream);
+
+/*
+ * The 1 x 1 MCMK of section III-A on its own: O[n] = A[M x C] . I[n][C x HW], the building block kn2row
+ * is made of.  desc->k must be 1 (else CONV_MCMK_ERR_UNSUPPORTED); I[N][C][H][W], O[N][M][Q][P];
+ * Kp_dev = conv_mcmk_prepack(desc, CONV_MCMK_KN2ROW).  Without padding and stride the image is treated as
+ * one row of H*W columns, so no tile is cut short at image edges; otherwise this is conv_mcmk_kn2row.
+ */
+int conv_mcmk_1x1(const conv_mcmk_desc *desc, const void *I_dev, const void *Kp_dev, void *O_dev, void *stream);
 
 /* float -> bfloat16 (round to nearest even), `count` elements, device to device. */
 int conv_mcmk_cvt_f32_bf16(const void *src_dev, void *dst_dev, size_t count, void *stream);

@@ -25,6 +25,7 @@ EXPORTS = (
     "conv_mcmk_strerror", "conv_mcmk_check", "conv_mcmk_describe_plan", "conv_mcmk_workspace_bytes", "conv_mcmk_packed_kernel_bytes",
     "conv_mcmk_prepack", "conv_mcmk_kn2row", "conv_mcmk_kn2row_2pass", "conv_mcmk_im2col",
     "conv_mcmk_direct", "conv_mcmk_kn2col", "conv_mcmk_im2row", "conv_mcmk_cvt_f32_bf16",
+    "conv_mcmk_kn2row_bias_relu", "conv_mcmk_kn2col_bias_relu", "conv_mcmk_1x1",
 )
 
 
@@ -73,6 +74,12 @@ def lib():
             fn = getattr(L, name)
             fn.argtypes = [dp, vp, vp, vp, vp, sz, vp]
             fn.restype = i
+        for name in ("conv_mcmk_kn2row_bias_relu", "conv_mcmk_kn2col_bias_relu"):
+            fn = getattr(L, name)
+            fn.argtypes = [dp, vp, vp, vp, i, vp, vp]
+            fn.restype = i
+        L.conv_mcmk_1x1.argtypes = [dp, vp, vp, vp, vp]
+        L.conv_mcmk_1x1.restype = i
         L.conv_mcmk_cvt_f32_bf16.argtypes = [vp, vp, sz, vp]
         L.conv_mcmk_cvt_f32_bf16.restype = i
         _lib = L
@@ -154,6 +161,18 @@ def conv_mcmk_im2row(d, I, Kp, O, ws=None, stream=None):
     _run("conv_mcmk_im2row", d, I, Kp, O, ws, stream)
 
 
+def conv_mcmk_kn2row_bias_relu(d, I, Kp, bias, relu, O, stream=None):
+    _raise(lib().conv_mcmk_kn2row_bias_relu(ctypes.byref(d), _ptr(I), _ptr(Kp), _ptr(bias), int(relu), _ptr(O), _stream(stream)))
+
+
+def conv_mcmk_kn2col_bias_relu(d, I, Kp, bias, relu, O, stream=None):
+    _raise(lib().conv_mcmk_kn2col_bias_relu(ctypes.byref(d), _ptr(I), _ptr(Kp), _ptr(bias), int(relu), _ptr(O), _stream(stream)))
+
+
+def conv_mcmk_1x1(d, I, Kp, O, stream=None):
+    _raise(lib().conv_mcmk_1x1(ctypes.byref(d), _ptr(I), _ptr(Kp), _ptr(O), _stream(stream)))
+
+
 def conv_mcmk_cvt_f32_bf16(src, dst, count=None, stream=None):
     n = src.numel() if count is None else count
     _raise(lib().conv_mcmk_cvt_f32_bf16(_ptr(src), _ptr(dst), n, _stream(stream)))
@@ -180,7 +199,7 @@ class Plan:
             conv_mcmk_prepack(d, variant, K_dev, self.kernel)
         ws_bytes = conv_mcmk_workspace_bytes(d, variant)
         self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev) if ws_bytes else None
-        q, p = d.h + 2 * d.pad - d.k + 1, d.w + 2 * d.pad - d.k + 1
+        q, p = (d.h + 2 * d.pad - d.k) // d.stride + 1, (d.w + 2 * d.pad - d.k) // d.stride + 1
         shape = (d.n, q, p, d.m) if variant in CHANNELS_LAST else (d.n, d.m, q, p)
         self.out = torch.empty(shape, dtype=torch.float32, device=dev)
 

@@ -77,9 +77,11 @@ __global__ void prepack_bf16_kernel(const float *__restrict__ K, uint16_t *__res
 // them for all k*k taps, so the input patch is read once (through L1/L2) and every store is a
 // full VEC-wide, coalesced row segment of one of the k*k matrix rows -- the k*k-fold replication
 // is pure write traffic.  VEC > 1 needs P % VEC == 0 (16-byte aligned stores); the host picks.
+// With a stride only the patches of the outputs that exist are built: column (q, p) is centred on
+// input (stride*q, stride*p).
 template <typename T, int VEC>
 __global__ void im2col_build_kernel(const T *__restrict__ I, T *__restrict__ cols,
-                                    int n, int c, int h, int w, int k, int pad, int q, int p)
+                                    int n, int c, int h, int w, int k, int pad, int stride, int q, int p)
 {
     struct alignas(sizeof(T) * VEC) Pack { T v[VEC]; };
     const int pv = p / VEC;                                   // column groups per row
@@ -93,15 +95,15 @@ __global__ void im2col_build_kernel(const T *__restrict__ I, T *__restrict__ col
         const size_t nc = rest / q;                           // image * C + channel
         const T *src = I + nc * (size_t)h * w;
         T *dst = cols + nc * (size_t)k * k * qp + (size_t)oq * p + (size_t)xg * VEC;
-        const int x0 = xg * VEC - pad;
+        const int x0 = xg * VEC * stride - pad;
         for (int i = 0; i < k; ++i) {
-            const int y = oq - pad + i;
+            const int y = oq * stride - pad + i;
             const bool row_ok = y >= 0 && y < h;
             for (int j = 0; j < k; ++j) {
                 Pack out;
 #pragma unroll
                 for (int u = 0; u < VEC; ++u) {
-                    const int x = x0 + j + u;
+                    const int x = x0 + j + u * stride;
                     out.v[u] = (row_ok && x >= 0 && x < w) ? src[(size_t)y * w + x] : T(0);
                 }
                 *reinterpret_cast<Pack *>(dst + (size_t)(i * k + j) * qp) = out;
@@ -112,12 +114,12 @@ __global__ void im2col_build_kernel(const T *__restrict__ I, T *__restrict__ col
 
 // ---------------------------------------------------------------------------------------------
 // im2row (section II-B, last paragraph): patches unrolled into ROWS, from a channels-last input:
-//   rows[n][q*P+p][(i*k+j)*C + c] = I[n][q-pad+i][p-pad+j][c]  (zero outside the image).
+//   rows[n][q*P+p][(i*k+j)*C + c] = I[n][stride*q-pad+i][stride*p-pad+j][c]  (zero outside the image).
 // One thread copies one VEC-wide channel vector (VEC elements = 16 bytes; C % VEC == 0), so both the
 // read and the write are contiguous runs of C elements.
 template <typename T, int VEC>
 __global__ void im2row_build_kernel(const T *__restrict__ I, T *__restrict__ rows,
-                                    int n, int c, int h, int w, int k, int pad, int q, int p)
+                                    int n, int c, int h, int w, int k, int pad, int stride, int q, int p)
 {
     struct alignas(sizeof(T) * VEC) Pack { T v[VEC]; };
     const int cv = c / VEC;
@@ -131,7 +133,7 @@ __global__ void im2row_build_kernel(const T *__restrict__ I, T *__restrict__ row
         const int op = (int)(rest % p); rest /= p;
         const int oq = (int)(rest % q);
         const size_t in = rest / q;
-        const int y = oq - pad + i, x = op - pad + j;
+        const int y = oq * stride - pad + i, x = op * stride - pad + j;
         Pack out;
 #pragma unroll
         for (int u = 0; u < VEC; ++u) out.v[u] = T(0);
@@ -142,12 +144,12 @@ __global__ void im2row_build_kernel(const T *__restrict__ I, T *__restrict__ row
 }
 
 // ---------------------------------------------------------------------------------------------
-// Shift-add post pass of section III-A: O[n][m][q][p] = sum over taps of T[n][t*M+m][q+di][p+dj],
-// offsets taken in the 2-D plane; positions outside the H x W plane are discarded.
+// Shift-add post pass of section III-A: O[n][m][q][p] = sum over taps of T[n][t*M+m][s*q+di][s*p+dj]
+// (s = stride, 1 in the paper), offsets taken in the 2-D plane; positions outside the H x W plane are discarded.
 // One thread owns VEC consecutive columns of one output row (VEC > 1 needs P % VEC == 0).
 template <int VEC>
 __global__ void shift_add_f32_kernel(const float *__restrict__ T, float *__restrict__ O,
-                                     int n, int m, int h, int w, int k, int pad, int q, int p)
+                                     int n, int m, int h, int w, int k, int pad, int stride, int q, int p)
 {
     struct alignas(sizeof(float) * VEC) Pack { float v[VEC]; };
     const int pv = p / VEC;
@@ -166,14 +168,14 @@ __global__ void shift_add_f32_kernel(const float *__restrict__ T, float *__restr
 #pragma unroll
         for (int u = 0; u < VEC; ++u) acc.v[u] = 0.0f;
         for (int i = 0; i < k; ++i) {
-            const int y = oq - pad + i;
+            const int y = oq * stride - pad + i;
             if (y < 0 || y >= h) continue;
             for (int j = 0; j < k; ++j) {
                 const float *row = Tn + ((size_t)(i * k + j) * m + im) * hw + (size_t)y * w;
-                const int x0 = xg * VEC - pad + j;
+                const int x0 = xg * VEC * stride - pad + j;
 #pragma unroll
                 for (int u = 0; u < VEC; ++u) {
-                    const int x = x0 + u;
+                    const int x = x0 + u * stride;
                     if (x >= 0 && x < w) acc.v[u] += row[x];
                 }
             }
@@ -186,7 +188,7 @@ __global__ void shift_add_f32_kernel(const float *__restrict__ T, float *__restr
 // Direct loop nest (Eq. 1-3): one output element per thread, plain fp32 FMA.
 __global__ void direct_f32_kernel(const float *__restrict__ I, const float *__restrict__ K,
                                   float *__restrict__ O, int n, int c, int h, int w, int m, int k,
-                                  int pad, int q, int p)
+                                  int pad, int stride, int q, int p)
 {
     const size_t qp = (size_t)q * p;
     const size_t total = (size_t)n * m * qp;
@@ -202,10 +204,10 @@ __global__ void direct_f32_kernel(const float *__restrict__ I, const float *__re
         float acc = 0.0f;
         for (int ch = 0; ch < c; ++ch)
             for (int i = 0; i < k; ++i) {
-                const int y = oq - pad + i;
+                const int y = oq * stride - pad + i;
                 if (y < 0 || y >= h) continue;
                 for (int j = 0; j < k; ++j) {
-                    const int x = ox - pad + j;
+                    const int x = ox * stride - pad + j;
                     if (x < 0 || x >= w) continue;
                     acc = fmaf(img[((size_t)ch * h + y) * w + x], ker[(ch * k + i) * k + j], acc);
                 }

@@ -24,11 +24,11 @@ struct Dims {
 int validate(const conv_mcmk_desc *d, int variant, Dims *out)
 {
     if (!d) return CONV_MCMK_ERR_NULL;
-    if (d->n < 1 || d->c < 1 || d->h < 1 || d->w < 1 || d->m < 1 || d->k < 1 || d->pad < 0)
+    if (d->n < 1 || d->c < 1 || d->h < 1 || d->w < 1 || d->m < 1 || d->k < 1 || d->pad < 0 || d->stride < 1)
         return CONV_MCMK_ERR_SHAPE;
-    const long long q = (long long)d->h + 2LL * d->pad - d->k + 1;
-    const long long p = (long long)d->w + 2LL * d->pad - d->k + 1;
-    if (q < 1 || p < 1) return CONV_MCMK_ERR_SHAPE;
+    if ((long long)d->h + 2LL * d->pad < d->k || (long long)d->w + 2LL * d->pad < d->k) return CONV_MCMK_ERR_SHAPE;
+    const long long q = ((long long)d->h + 2LL * d->pad - d->k) / d->stride + 1;
+    const long long p = ((long long)d->w + 2LL * d->pad - d->k) / d->stride + 1;
     // the tile kernel addresses one image through a 32-bit byte offset with 2 GiB kept free
     if (((long long)d->c + 32) * d->h * d->w >= (1LL << 29)) return CONV_MCMK_ERR_SHAPE;
     const long long lim = 1LL << 31;
@@ -37,12 +37,11 @@ int validate(const conv_mcmk_desc *d, int variant, Dims *out)
         (long long)d->m * d->c * kk >= lim || (long long)d->c * kk * q * p >= lim * 4 ||
         kk * d->m * d->h * d->w >= lim * 4 || q >= 65536 * 16 || p >= 65536 * 16)
         return CONV_MCMK_ERR_SHAPE;
-    if (d->stride != 1) return CONV_MCMK_ERR_UNSUPPORTED;
     if (d->dtype != CONV_MCMK_F32 && d->dtype != CONV_MCMK_BF16) return CONV_MCMK_ERR_UNSUPPORTED;
     switch (variant) {
     case CONV_MCMK_KN2ROW:
     case CONV_MCMK_KN2COL:
-        if (d->k != 1 && d->k != 3 && d->k != 5 && d->k != 7) return CONV_MCMK_ERR_UNSUPPORTED;
+        if (d->k > kMaxKernelSide || d->stride > 2) return CONV_MCMK_ERR_UNSUPPORTED;
         if (d->pad > 65535) return CONV_MCMK_ERR_SHAPE;
         // channels-last input is read in aligned 16-byte channel vectors: 4 floats or 8 bfloat16
         if (variant == CONV_MCMK_KN2COL && d->c % (d->dtype == CONV_MCMK_BF16 ? 8 : 4) != 0) return CONV_MCMK_ERR_UNSUPPORTED;
@@ -96,26 +95,40 @@ int run_tile(int dtype, int ks, const TileRequest &rq)
     if (dtype == CONV_MCMK_F32) {
         switch (ks) {
         case 1: rc = run_tile_f32_k1(rq); break;
+        case 2: rc = run_tile_f32_k2(rq); break;
         case 3: rc = run_tile_f32_k3(rq); break;
+        case 4: rc = run_tile_f32_k4(rq); break;
         case 5: rc = run_tile_f32_k5(rq); break;
+        case 6: rc = run_tile_f32_k6(rq); break;
         case 7: rc = run_tile_f32_k7(rq); break;
         }
     } else {
         switch (ks) {
         case 1: rc = run_tile_bf16_k1(rq); break;
+        case 2: rc = run_tile_bf16_k2(rq); break;
         case 3: rc = run_tile_bf16_k3(rq); break;
+        case 4: rc = run_tile_bf16_k4(rq); break;
         case 5: rc = run_tile_bf16_k5(rq); break;
+        case 6: rc = run_tile_bf16_k6(rq); break;
         case 7: rc = run_tile_bf16_k7(rq); break;
         }
     }
     return rc == 0 ? CONV_MCMK_OK : rc == 1 ? CONV_MCMK_ERR_DEVICE : rc == 3 ? CONV_MCMK_ERR_SHAPE : CONV_MCMK_ERR_UNSUPPORTED;
 }
 
+// What a fused call may apply to the finished sums before storing them.
+struct Epilogue {
+    const float *bias = nullptr;   // [M], device
+    int relu = 0;
+    bool any() const { return bias != nullptr || relu != 0; }
+};
+
 // One launch of the tile kernel: a convolution (ks x ks taps, row_groups = 1) or a plain GEMM
 // (ks = 1 over a 1 x cols image, row_groups row planes of m rows each).
 int launch_tile(const conv_mcmk_desc *d, const Dims &dm, int ks, int shape, int csplit, const void *in,
                 const void *apk, float *out, int in_c, int in_h, int in_w, int out_q, int out_p, int pad,
-                int row_groups, hipStream_t st, bool channels_last = false)
+                int row_groups, hipStream_t st, bool channels_last = false, int stride = 1,
+                const Epilogue &ep = Epilogue())
 {
     TileRequest rq;
     TileArgs &a = rq.args;
@@ -128,8 +141,12 @@ int launch_tile(const conv_mcmk_desc *d, const Dims &dm, int ks, int shape, int 
     a.cg = ceil_div(in_c, d->dtype == CONV_MCMK_BF16 ? 32 : 16);
     a.tiles_x = a.tiles_y = a.row_tiles = 0;
     a.csplit = csplit;
+    a.bias = ep.bias;
+    a.relu = ep.relu;
+    if (csplit > 1 && ep.any()) return CONV_MCMK_ERR_UNSUPPORTED;   // partial sums cannot be rectified
     rq.shape = shape;
     rq.channels_last = channels_last;
+    rq.stride = stride;
     rq.stream = st;
     if (csplit > 1) {
         // partial sums are added into the output, so it starts from zero (a fill kernel, not a
@@ -184,7 +201,7 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
 
 // The candidate the cost estimate prefers for the fused kernel (or the one CONV_MCMK_TILE forces:
 // tuning aid, menu index = shape + 7 * (csplit - 1)).
-Candidate choose_fused(const conv_mcmk_desc *d, const Dims &dm)
+Candidate choose_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, bool epilogue = false)
 {
     Candidate best{};
     double best_cost = -1.0;
@@ -199,6 +216,11 @@ Candidate choose_fused(const conv_mcmk_desc *d, const Dims &dm)
             // 5x5 halo tiles would not fit the 160 KB of LDS) and are an alternative to, not a partner
             // of, the two-way split
             if (c.kg > 1 && (d->dtype == CONV_MCMK_BF16 || cs > 1 || d->k > 3)) continue;
+            if (d->stride > 1 && sh >= kStridedShapes) continue;       // strided input tiles: 14 x 14 outputs only
+            if (epilogue && cs > 1) continue;                          // partial sums cannot take the epilogue
+            // strided bf16 tiles gathered from [C][H][W] with a kernel side of 5 or more exist for the
+            // 2 x 4 wave layout only (register budget of the staging gather)
+            if (d->stride > 1 && d->dtype == CONV_MCMK_BF16 && !channels_last && d->k >= 5 && sh != 1) continue;
             const double cost = (force && atoi(force) == index) ? 0.0 : tile_cost(d, dm, c, d->k);
             if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = c; }
         }
@@ -206,11 +228,11 @@ Candidate choose_fused(const conv_mcmk_desc *d, const Dims &dm)
 }
 
 int launch_fused(const conv_mcmk_desc *d, const Dims &dm, const void *in, const void *apk, float *out,
-                 hipStream_t st, bool channels_last)
+                 hipStream_t st, bool channels_last, const Epilogue &ep = Epilogue())
 {
-    const Candidate best = choose_fused(d, dm);
+    const Candidate best = choose_fused(d, dm, channels_last, ep.any());
     return launch_tile(d, dm, d->k, best.shape, best.csplit, in, apk, out, d->c, d->h, d->w, dm.q, dm.p, d->pad, 1, st,
-                       channels_last);
+                       channels_last, d->stride, ep);
 }
 
 // Plain GEMM [rows x kc] . [kc x cols] per image on the same tile kernel: a 1x1 "convolution" over a
@@ -239,6 +261,18 @@ int workspace_check(const conv_mcmk_desc *d, int variant, const void *ws, size_t
     return CONV_MCMK_OK;
 }
 
+int fused_entry(const conv_mcmk_desc *d, int variant, const void *I_dev, const void *Kp_dev, void *O_dev, void *stream,
+                const Epilogue &ep = Epilogue())
+{
+    Dims dm;
+    int rc = validate(d, variant, &dm);
+    if (rc) return rc;
+    if ((rc = common_ptr_checks(I_dev, Kp_dev, O_dev))) return rc;
+    if (ep.bias && (reinterpret_cast<uintptr_t>(ep.bias) & 3u) != 0) return CONV_MCMK_ERR_ALIGN;
+    return launch_fused(d, dm, I_dev, Kp_dev, static_cast<float *>(O_dev), static_cast<hipStream_t>(stream),
+                        variant == CONV_MCMK_KN2COL, ep);
+}
+
 }  // namespace
 
 extern "C" {
@@ -249,7 +283,7 @@ const char *conv_mcmk_strerror(int code)
     case CONV_MCMK_OK: return "ok";
     case CONV_MCMK_ERR_NULL: return "a required pointer is NULL";
     case CONV_MCMK_ERR_SHAPE: return "invalid shape (dimension < 1, negative pad, empty output or tensor too large)";
-    case CONV_MCMK_ERR_UNSUPPORTED: return "unsupported stride, dtype, variant or kernel size for this variant";
+    case CONV_MCMK_ERR_UNSUPPORTED: return "unsupported stride, dtype, variant, kernel size or channel count for this variant";
     case CONV_MCMK_ERR_WORKSPACE: return "workspace missing or too small";
     case CONV_MCMK_ERR_DEVICE: return "the HIP runtime refused a launch";
     case CONV_MCMK_ERR_ALIGN: return "a pointer is not 16-byte aligned";
@@ -270,7 +304,7 @@ int conv_mcmk_describe_plan(const conv_mcmk_desc *d, int variant, char *buf, siz
     switch (variant) {
     case CONV_MCMK_KN2ROW:
     case CONV_MCMK_KN2COL: {
-        const Candidate c = choose_fused(d, dm);
+        const Candidate c = choose_fused(d, dm, variant == CONV_MCMK_KN2COL);
         const long long wgs = (long long)d->n * ceil_div(dm.p, c.tw) * ceil_div(dm.q, c.th) * ceil_div(dm.mb, c.wm) * c.csplit;
         snprintf(buf, n, "%s fused %s: tile %dx%d, waves %dx%d, channel groups %d, channel split %d, %lld workgroups, est %.1f us",
                  variant == CONV_MCMK_KN2COL ? "kn2col" : "kn2row", type, c.th, c.tw, c.wm, c.wp, c.kg, c.csplit, wgs,
@@ -357,22 +391,47 @@ int conv_mcmk_kn2row(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_
                      void *ws, size_t ws_bytes, void *stream)
 {
     (void)ws; (void)ws_bytes;
-    Dims dm;
-    int rc = validate(d, CONV_MCMK_KN2ROW, &dm);
-    if (rc) return rc;
-    if ((rc = common_ptr_checks(I_dev, Kp_dev, O_dev))) return rc;
-    return launch_fused(d, dm, I_dev, Kp_dev, static_cast<float *>(O_dev), static_cast<hipStream_t>(stream), false);
+    return fused_entry(d, CONV_MCMK_KN2ROW, I_dev, Kp_dev, O_dev, stream);
 }
 
 int conv_mcmk_kn2col(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_dev, void *O_dev,
                      void *ws, size_t ws_bytes, void *stream)
 {
     (void)ws; (void)ws_bytes;
+    return fused_entry(d, CONV_MCMK_KN2COL, I_dev, Kp_dev, O_dev, stream);
+}
+
+int conv_mcmk_kn2row_bias_relu(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_dev, const float *bias_dev,
+                               int relu, void *O_dev, void *stream)
+{
+    Epilogue ep;
+    ep.bias = bias_dev;
+    ep.relu = relu != 0;
+    return fused_entry(d, CONV_MCMK_KN2ROW, I_dev, Kp_dev, O_dev, stream, ep);
+}
+
+int conv_mcmk_kn2col_bias_relu(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_dev, const float *bias_dev,
+                               int relu, void *O_dev, void *stream)
+{
+    Epilogue ep;
+    ep.bias = bias_dev;
+    ep.relu = relu != 0;
+    return fused_entry(d, CONV_MCMK_KN2COL, I_dev, Kp_dev, O_dev, stream, ep);
+}
+
+int conv_mcmk_1x1(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_dev, void *O_dev, void *stream)
+{
     Dims dm;
-    int rc = validate(d, CONV_MCMK_KN2COL, &dm);
+    int rc = validate(d, CONV_MCMK_KN2ROW, &dm);
     if (rc) return rc;
+    if (d->k != 1) return CONV_MCMK_ERR_UNSUPPORTED;
     if ((rc = common_ptr_checks(I_dev, Kp_dev, O_dev))) return rc;
-    return launch_fused(d, dm, I_dev, Kp_dev, static_cast<float *>(O_dev), static_cast<hipStream_t>(stream), true);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // without padding or stride the image is just H*W columns of the matrix [C x HW] (section III-A):
+    // a plain GEMM with no tile edges inside the image
+    if (d->pad == 0 && d->stride == 1)
+        return launch_gemm(d, dm, I_dev, Kp_dev, static_cast<float *>(O_dev), d->c, (long long)d->h * d->w, 1, st);
+    return launch_fused(d, dm, I_dev, Kp_dev, static_cast<float *>(O_dev), st, false);
 }
 
 int conv_mcmk_kn2row_2pass(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_dev, void *O_dev,
@@ -393,10 +452,10 @@ int conv_mcmk_kn2row_2pass(const conv_mcmk_desc *d, const void *I_dev, const voi
     const size_t total = (size_t)d->n * d->m * dm.q * (dm.p / vec);
     if (vec == 4)
         hipLaunchKernelGGL(shift_add_f32_kernel<4>, dim3(grid_for(total, 256)), dim3(256), 0, st, T,
-                           static_cast<float *>(O_dev), d->n, d->m, d->h, d->w, d->k, d->pad, dm.q, dm.p);
+                           static_cast<float *>(O_dev), d->n, d->m, d->h, d->w, d->k, d->pad, d->stride, dm.q, dm.p);
     else
         hipLaunchKernelGGL(shift_add_f32_kernel<1>, dim3(grid_for(total, 256)), dim3(256), 0, st, T,
-                           static_cast<float *>(O_dev), d->n, d->m, d->h, d->w, d->k, d->pad, dm.q, dm.p);
+                           static_cast<float *>(O_dev), d->n, d->m, d->h, d->w, d->k, d->pad, d->stride, dm.q, dm.p);
     return launch_status();
 }
 
@@ -416,7 +475,7 @@ int conv_mcmk_im2col(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_
     const dim3 grid(grid_for(total, 256)), block(256);
 #define MCMK_IM2COL(T, V)                                                                             \
     hipLaunchKernelGGL((im2col_build_kernel<T, V>), grid, block, 0, st, static_cast<const T *>(I_dev), \
-                       static_cast<T *>(ws), d->n, d->c, d->h, d->w, d->k, d->pad, dm.q, dm.p)
+                       static_cast<T *>(ws), d->n, d->c, d->h, d->w, d->k, d->pad, d->stride, dm.q, dm.p)
     if (bf16) { if (vec == 8) MCMK_IM2COL(uint16_t, 8); else MCMK_IM2COL(uint16_t, 1); }
     else      { if (vec == 4) MCMK_IM2COL(float, 4);    else MCMK_IM2COL(float, 1); }
 #undef MCMK_IM2COL
@@ -439,10 +498,10 @@ int conv_mcmk_im2row(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_
     const dim3 grid(grid_for(total, 256)), block(256);
     if (bf16)
         hipLaunchKernelGGL((im2row_build_kernel<uint16_t, 8>), grid, block, 0, st, static_cast<const uint16_t *>(I_dev),
-                           static_cast<uint16_t *>(ws), d->n, d->c, d->h, d->w, d->k, d->pad, dm.q, dm.p);
+                           static_cast<uint16_t *>(ws), d->n, d->c, d->h, d->w, d->k, d->pad, d->stride, dm.q, dm.p);
     else
         hipLaunchKernelGGL((im2row_build_kernel<float, 4>), grid, block, 0, st, static_cast<const float *>(I_dev),
-                           static_cast<float *>(ws), d->n, d->c, d->h, d->w, d->k, d->pad, dm.q, dm.p);
+                           static_cast<float *>(ws), d->n, d->c, d->h, d->w, d->k, d->pad, d->stride, dm.q, dm.p);
     if ((rc = launch_status())) return rc;
     // O[n][q*P+p][m] = rows[n][q*P+p][:] . Khat[:][m]: the channels-last GEMM
     return launch_gemm(d, dm, ws, Kp_dev, static_cast<float *>(O_dev), d->c * dm.taps, (long long)dm.q * dm.p, 1, st, true);
@@ -460,7 +519,7 @@ int conv_mcmk_direct(const conv_mcmk_desc *d, const void *I_dev, const void *K_d
     const size_t total = (size_t)d->n * d->m * dm.q * dm.p;
     hipLaunchKernelGGL(direct_f32_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st,
                        static_cast<const float *>(I_dev), static_cast<const float *>(K_dev),
-                       static_cast<float *>(O_dev), d->n, d->c, d->h, d->w, d->m, d->k, d->pad, dm.q, dm.p);
+                       static_cast<float *>(O_dev), d->n, d->c, d->h, d->w, d->m, d->k, d->pad, d->stride, dm.q, dm.p);
     return launch_status();
 }
 

@@ -44,19 +44,22 @@ struct TileArgs {
     int row_tiles;        // ceil(row_groups*mb_per_group / WM)
     int csplit;           // 1, or 2: two workgroups share a tile, each takes half the chunks and
                           // adds its partial sums into a zeroed output (a + b is order-independent)
+    const float *bias;    // [row_groups * m] added to every output of its row, or nullptr (csplit == 1 only)
+    int relu;             // nonzero: negative results are stored as zero (csplit == 1 only)
 };
 
-template <int KS, int TH, int TW, int WM, int WP, int CCH = 16, int KG = 1>
+template <int KS, int TH, int TW, int WM, int WP, int CCH = 16, int KG = 1, int ST = 1>
 struct TileShape {
     static constexpr int kCC = CCH;                      // channels per chunk, a multiple of 16
     static constexpr int kGroupThreads = 64 * WM * WP;   // one channel group: WM x WP waves
     static constexpr int kThreads = kGroupThreads * KG;
-    static constexpr int kHT = TH + KS - 1;
-    static constexpr int kWT = TW + KS - 1;
+    static constexpr int kHT = (TH - 1) * ST + KS;       // input rows under a tile of TH output rows
+    static constexpr int kWT = (TW - 1) * ST + KS;
     static constexpr int kPos = kHT * kWT;               // halo-tile positions per channel
-    // channel stride in LDS words: >= kPos and == 16 mod 32, so the four channels one B fragment
-    // touches start 16 banks apart
-    static constexpr int kCHS = ((kPos + 15) / 32) * 32 + 16;
+    // channel stride in LDS words, >= kPos.  Unit stride: == 16 mod 32, so the four channels one B
+    // fragment touches start 16 banks apart.  Stride 2: the 16 positions of a fragment sit on every
+    // second bank, and an odd channel stride puts the next channel on the banks between them.
+    static constexpr int kCHS = ST == 1 ? ((kPos + 15) / 32) * 32 + 16 : (kPos | 1);
     static constexpr int kBuf = kCC * kCHS;              // words per LDS buffer
     static constexpr int kNPB = (TH * TW + 15) / 16;     // 16-position blocks per tile
     static constexpr int kPBW = (kNPB + WP - 1) / WP;    // blocks per wave
@@ -68,16 +71,19 @@ struct TileShape {
 // CL = true : channels last (c a multiple of 4), input [n][h][w][c], output [n][q][p][rows] -- the layout of the paper's
 //             kn2col variant (section III-A, last paragraph); the packed kernel and the whole
 //             accumulation are the same, only the staging gather and the final store differ.
+// ST: stride of the convolution (1 or 2).  Output position (y, x) reads the input tile at
+//     (ST*y + tap row, ST*x + tap column); the paper treats unit stride only (section II-A), the
+//     kn2row sum itself does not change.
 // KG > 1: the workgroup holds KG channel groups of WM x WP waves each.  Group g takes the chunks
 //         g, g+KG, g+2KG, ... of the tile (its own LDS buffers, its own staging), and the groups'
 //         partial sums are added through LDS at the end in a fixed order.  This is the split of the
 //         contraction for layers with too few tiles to fill the chip (small images, deep channels):
 //         no atomics, no zero fill, and -- because group g's waves are rotated by g along the position
 //         axis -- every SIMD ends up with the same number of position blocks.
-template <int KS, int TH, int TW, int WM, int WP, int CCH = 16, bool CL = false, int KG = 1>
+template <int KS, int TH, int TW, int WM, int WP, int CCH = 16, bool CL = false, int KG = 1, int ST = 1>
 __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileArgs a)
 {
-    using S = TileShape<KS, TH, TW, WM, WP, CCH, KG>;
+    using S = TileShape<KS, TH, TW, WM, WP, CCH, KG, ST>;
     static_assert(CCH % 16 == 0, "a chunk is a whole number of packed 16-channel groups");
     constexpr int NQ = CCH / 16;                   // packed A vectors per tap and chunk
     constexpr int CC = S::kCC, NT = S::kGroupThreads, WT = S::kWT, POS = S::kPos, CHS = S::kCHS;
@@ -115,7 +121,8 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
     const int tx = bid % a.tiles_x;    bid /= a.tiles_x;
     const int ty = bid % a.tiles_y;    bid /= a.tiles_y;
     const int img = bid;
-    const int x0 = tx * TW, y0 = ty * TH;
+    const int x0 = tx * TW, y0 = ty * TH;                         // first output position of the tile
+    const int ix0 = x0 * ST - a.pad, iy0 = y0 * ST - a.pad;       // input position under halo-tile element (0, 0)
 
     const int total_rb = a.row_groups * a.mb_per_group;
     int rb = rt * WM + wm;                       // this wave's 16-row block
@@ -147,7 +154,7 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
         const int e = tid + s * NT;
         const int cl = e / POS, pos = e % POS;
         const int r = pos / WT, col = pos % WT;
-        const int gy = y0 - a.pad + r, gx = x0 - a.pad + col;
+        const int gy = iy0 + r, gx = ix0 + col;
         const bool used = e < CC * POS;
         const bool inside = used && gy >= 0 && gy < a.h && gx >= 0 && gx < a.w;
         g_off[s] = inside ? (uint32_t)((cl * plane + (size_t)gy * a.w + gx) * sizeof(float)) : 0x80000000u;
@@ -172,7 +179,7 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
                 const int e = t + s * NT;
                 const int quad = e % QPC, pos = e / QPC;
                 const int r = pos / WT, col = pos % WT;
-                const int gy = y0 - a.pad + r, gx = x0 - a.pad + col;
+                const int gy = iy0 + r, gx = ix0 + col;
                 const int ch = chunk * CC + quad * 4;
                 const bool ok = e < QPC * POS && gy >= 0 && gy < a.h && gx >= 0 && gx < a.w;
                 const uint32_t base = (uint32_t)((((size_t)gy * a.w + gx) * a.c + ch) * sizeof(float));
@@ -224,7 +231,7 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
     for (int b = 0; b < PBW; ++b) {
         int pp = (first_pb + b) * 16 + (lane & 15);
         if (pp >= TH * TW) pp = 0;
-        b_off[b] = (lane >> 4) * CHS + (pp / TW) * WT + (pp % TW);
+        b_off[b] = (lane >> 4) * CHS + (pp / TW) * ST * WT + (pp % TW) * ST;
     }
 
     // ---- A fragments: one f32x4 per lane per tap covers a 16-channel chunk.  They are fetched
@@ -346,6 +353,23 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
     const size_t oplane = (size_t)a.q * a.p;
     const int out_rows = a.row_groups * a.m;
     float *out_img = a.out + (size_t)img * out_rows * oplane;
+    if (a.bias != nullptr || a.relu) {
+        // layer epilogue on the finished sums: per-row offset, then the rectifier
+        const int mrow0 = mbi * 16 + 4 * (lane >> 4);
+        f32x4 bv = {0.f, 0.f, 0.f, 0.f};
+        if (a.bias != nullptr) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if (mrow0 + v < a.m) bv[v] = a.bias[(size_t)grp * a.m + mrow0 + v];
+        }
+#pragma unroll
+        for (int b = 0; b < PBW; ++b)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float r = acc[b][v] + bv[v];
+                acc[b][v] = (a.relu && r < 0.0f) ? 0.0f : r;      // a NaN stays a NaN
+            }
+    }
 #pragma unroll
     for (int b = 0; b < PBW; ++b) {
         if (b >= nb_wave) continue;

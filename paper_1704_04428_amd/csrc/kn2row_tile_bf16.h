@@ -28,16 +28,19 @@ namespace mcmk {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef short i16x2 __attribute__((ext_vector_type(2)));
 
-template <int KS, int TH, int TW, int WM, int WP>
+template <int KS, int TH, int TW, int WM, int WP, int ST = 1>
 struct TileShapeBf16 {
     static constexpr int kCC = 32;                       // channels per chunk
     static constexpr int kThreads = 64 * WM * WP;
-    static constexpr int kHT = TH + KS - 1;
-    static constexpr int kWT = TW + KS - 1;
+    static constexpr int kHT = (TH - 1) * ST + KS;
+    static constexpr int kWT = (TW - 1) * ST + KS;
     static constexpr int kPos = kHT * kWT;
-    // bytes between tile rows: >= 16 per column, == 16*TW (mod 256)
-    static constexpr int kRowBytes = ((kWT * 16 - (TW * 16) % 256 + 255) / 256) * 256 + (TW * 16) % 256;
+    // bytes between tile rows: >= 16 per column; for unit stride == 16*TW (mod 256), see above; the
+    // strided tile is four times the size and is packed tight to stay inside the LDS
+    static constexpr int kRowBytes =
+        ST == 1 ? ((kWT * 16 - (TW * 16) % 256 + 255) / 256) * 256 + (TW * 16) % 256 : kWT * 16;
     static constexpr int kPlaneBytes = ((kHT * kRowBytes + 255) / 256) * 256;   // one channel octet
     static constexpr int kBufBytes = 4 * kPlaneBytes;
     static constexpr int kNPB = (TH * TW + 15) / 16;
@@ -51,12 +54,13 @@ struct TileShapeBf16 {
 // CL = true: channels last (input [n][h][w][c], output [n][q][p][rows], the kn2col layout); needs
 // c % 8 == 0 so that a channel octet of one position is one aligned 16-byte load -- the staging
 // transpose disappears.
-template <int KS, int TH, int TW, int WM, int WP, bool CL = false>
+// ST: stride of the convolution (1 or 2), as in kn2row_tile_f32.
+template <int KS, int TH, int TW, int WM, int WP, bool CL = false, int ST = 1>
 __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs a)
 {
-    using S = TileShapeBf16<KS, TH, TW, WM, WP>;
+    using S = TileShapeBf16<KS, TH, TW, WM, WP, ST>;
     constexpr int CC = S::kCC, NT = S::kThreads, WT = S::kWT, POS = S::kPos, RSB = S::kRowBytes, PLB = S::kPlaneBytes;
-    static_assert(RSB >= WT * 16 && (RSB - TW * 16) % 256 == 0, "row stride rule");
+    static_assert(RSB >= WT * 16 && (ST != 1 || (RSB - TW * 16) % 256 == 0), "row stride rule");
     constexpr int PBW = S::kPBW, NPB = S::kNPB, SLOTS = S::kSlots, BUF = S::kBufBytes;
     constexpr int REM = NPB % WP;
     constexpr bool kRagged = REM != 0;
@@ -81,7 +85,8 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs 
     const int tx = bid % a.tiles_x;    bid /= a.tiles_x;
     const int ty = bid % a.tiles_y;    bid /= a.tiles_y;
     const int img = bid;
-    const int x0 = tx * TW, y0 = ty * TH;
+    const int x0 = tx * TW, y0 = ty * TH;                         // first output position of the tile
+    const int ix0 = x0 * ST - a.pad, iy0 = y0 * ST - a.pad;       // input position under halo-tile element (0, 0)
 
     const int total_rb = a.row_groups * a.mb_per_group;
     int rb = rt * WM + wm;
@@ -106,14 +111,14 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs 
         const int e = tid + s * NT;
         const int oct = e / POS, pos = e % POS;
         const int r = pos / WT, col = pos % WT;
-        const int gy = y0 - a.pad + r, gx = x0 - a.pad + col;
+        const int gy = iy0 + r, gx = ix0 + col;
         const bool used = e < S::kItems;
         const bool inside = used && gy >= 0 && gy < a.h && gx >= 0 && gx < a.w;
         g_off[s] = inside ? (uint32_t)(oct * 8) * plane_bytes + (uint32_t)((size_t)gy * a.w + gx) * 2u : 0x80000000u;
         l_off[s] = used ? oct * PLB + r * RSB + col * 16 : -1;
     }
 
-    uint16_t stage[SLOTS][8];      // channels first: eight 2-byte gathers per item
+    i16x2 stage[SLOTS][4];         // channels first: eight 2-byte gathers per item, two to a register
     u32x4 stage_cl[SLOTS];         // channels last: one 16-byte load per item
     auto load_chunk = [&](int chunk) {
         if constexpr (CL) {
@@ -125,7 +130,7 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs 
                 const int e = t + s * NT;
                 const int oct = e % 4, pos = e / 4;
                 const int r = pos / WT, col = pos % WT;
-                const int gy = y0 - a.pad + r, gx = x0 - a.pad + col;
+                const int gy = iy0 + r, gx = ix0 + col;
                 const int ch = chunk * CC + oct * 8;
                 const bool ok = e < S::kItems && gy >= 0 && gy < a.h && gx >= 0 && gx < a.w && ch < a.c;
                 const uint32_t off = ok ? (uint32_t)((((size_t)gy * a.w + gx) * a.c + ch) * sizeof(uint16_t)) : 0x80000000u;
@@ -136,7 +141,7 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs 
             for (int s = 0; s < SLOTS; ++s)
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
-                    stage[s][e] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(
+                    stage[s][e / 2][e % 2] = (short)__builtin_amdgcn_raw_buffer_load_b16(
                         in_rsrc, (int)(g_off[s] + (uint32_t)e * plane_bytes + (uint32_t)min(chunk, a.cg) * chunk_bytes), 0, 0);
         }
     };
@@ -156,7 +161,7 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs 
             for (int s = 0; s < SLOTS; ++s) {
                 u32x4 v;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = (uint32_t)stage[s][2 * e] | ((uint32_t)stage[s][2 * e + 1] << 16);
+                for (int e = 0; e < 4; ++e) v[e] = __builtin_bit_cast(uint32_t, stage[s][e]);
                 if (l_off[s] >= 0) *reinterpret_cast<u32x4 *>(buf + l_off[s]) = v;
             }
         }
@@ -170,7 +175,7 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs 
     for (int b = 0; b < PBW; ++b) {
         int pp = (first_pb + b) * 16 + (lane & 15);
         if (pp >= TH * TW) pp = 0;
-        b_off[b] = (lane >> 4) * PLB + (pp / TW) * RSB + (pp % TW) * 16;
+        b_off[b] = (lane >> 4) * PLB + (pp / TW) * ST * RSB + (pp % TW) * ST * 16;
     }
 
     // ---- A fragments, fetched one tap row ahead: a ring of D = KS registers whose slot for tap t is
@@ -244,6 +249,23 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs 
     const size_t oplane = (size_t)a.q * a.p;
     const int out_rows = a.row_groups * a.m;
     float *out_img = a.out + (size_t)img * out_rows * oplane;
+    if (a.bias != nullptr || a.relu) {
+        // layer epilogue on the finished sums: per-row offset, then the rectifier
+        const int mrow0 = mbi * 16 + 4 * (lane >> 4);
+        f32x4 bv = {0.f, 0.f, 0.f, 0.f};
+        if (a.bias != nullptr) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if (mrow0 + v < a.m) bv[v] = a.bias[(size_t)grp * a.m + mrow0 + v];
+        }
+#pragma unroll
+        for (int b = 0; b < PBW; ++b)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float r = acc[b][v] + bv[v];
+                acc[b][v] = (a.relu && r < 0.0f) ? 0.0f : r;      // a NaN stays a NaN
+            }
+    }
 #pragma unroll
     for (int b = 0; b < PBW; ++b) {
         if (b >= nb_wave) continue;

@@ -11,7 +11,8 @@ namespace mcmk {
 // Tile shapes every instantiation file provides: tile rows x columns, waves along the rows and along
 // the positions, and the number of channel groups (in-workgroup split of the contraction; fp32 only).
 // Index kGemmShape is the plain-GEMM shape (1 x 224 positions, 32-channel chunks) and exists for
-// kernel side 1 only.
+// kernel side 1 only.  Stride 2 is instantiated for the first kStridedShapes entries (the 14 x 14
+// tiles without channel groups: the strided input tile of a larger output tile would not fit the LDS).
 struct TileShapeDesc {
     int th, tw, wm, wp, kg;
 };
@@ -21,22 +22,31 @@ constexpr TileShapeDesc kTileShapes[] = {
 };
 constexpr int kConvShapes = 7;
 constexpr int kGemmShape = 7;
+constexpr int kStridedShapes = 3;
+constexpr int kMaxKernelSide = 7;      // kernel sides 1..7 are instantiated
 
 struct TileRequest {
     TileArgs args;       // tiles_x, tiles_y and row_tiles are filled in by the launcher
     int shape;           // index into kTileShapes
     bool channels_last;  // input [n][h][w][c], output [n][q][p][rows] (kn2col); convolution shapes only
+    int stride;          // 1, or 2 with a shape index below kStridedShapes
     hipStream_t stream;
 };
 
 // Return hipSuccess-or-not as 0 / 1; 2 when the shape index is not instantiated, 3 when the grid is too large.
 int run_tile_f32_k1(const TileRequest &);
+int run_tile_f32_k2(const TileRequest &);
 int run_tile_f32_k3(const TileRequest &);
+int run_tile_f32_k4(const TileRequest &);
 int run_tile_f32_k5(const TileRequest &);
+int run_tile_f32_k6(const TileRequest &);
 int run_tile_f32_k7(const TileRequest &);
 int run_tile_bf16_k1(const TileRequest &);
+int run_tile_bf16_k2(const TileRequest &);
 int run_tile_bf16_k3(const TileRequest &);
+int run_tile_bf16_k4(const TileRequest &);
 int run_tile_bf16_k5(const TileRequest &);
+int run_tile_bf16_k6(const TileRequest &);
 int run_tile_bf16_k7(const TileRequest &);
 
 }  // namespace mcmk

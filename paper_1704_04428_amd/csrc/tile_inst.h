@@ -1,5 +1,5 @@
 // Body of one tile-kernel translation unit.  The including file defines
-//   MCMK_KS    kernel side (1, 3, 5 or 7)
+//   MCMK_KS    kernel side (1 to 7)
 //   MCMK_BF16  0: fp32 operands, 1: bf16 operands
 // and gets run_tile_<type>_k<KS>() with every tile shape of kTileShapes instantiated.
 #include "tile_dispatch.h"
@@ -7,10 +7,15 @@
 #include "kn2row_tile_bf16.h"
 #endif
 
+// bf16 operands in [C][H][W] order with stride 2 and a kernel side of 5 or more: the staging gather
+// of the large strided tile needs more registers than the two layouts with 7 position blocks per
+// wave leave free, so only the 2 x 4 wave layout is built (the host never picks the others).
+#define MCMK_STRIDED_BF16_NCHW_WIDE_ONLY (MCMK_BF16 && MCMK_KS >= 5)
+
 namespace mcmk {
 namespace {
 
-template <int TH, int TW, int WM, int WP, int CCH = 16, bool CL = false, int KG = 1>
+template <int TH, int TW, int WM, int WP, int CCH = 16, bool CL = false, int KG = 1, int ST = 1>
 int launch_shape(const TileRequest &rq)
 {
     TileArgs a = rq.args;
@@ -20,36 +25,36 @@ int launch_shape(const TileRequest &rq)
     const long long blocks = (long long)a.n * a.tiles_x * a.tiles_y * a.row_tiles * a.csplit;
     if (blocks < 1 || blocks >= (1LL << 31)) return 3;
 #if MCMK_BF16
-    using S = TileShapeBf16<MCMK_KS, TH, TW, WM, WP>;
+    using S = TileShapeBf16<MCMK_KS, TH, TW, WM, WP, ST>;
     if (S::kLdsBytes > 65536) {
         // more than 64 KiB of dynamic LDS has to be allowed per kernel, once per device
         static bool allowed[64] = {};
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 1;
         if (!allowed[dev]) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&kn2row_tile_bf16<MCMK_KS, TH, TW, WM, WP, CL>),
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&kn2row_tile_bf16<MCMK_KS, TH, TW, WM, WP, CL, ST>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::kLdsBytes) != hipSuccess)
                 return 1;
             allowed[dev] = true;
         }
     }
-    hipLaunchKernelGGL((kn2row_tile_bf16<MCMK_KS, TH, TW, WM, WP, CL>), dim3((unsigned)blocks), dim3(S::kThreads),
+    hipLaunchKernelGGL((kn2row_tile_bf16<MCMK_KS, TH, TW, WM, WP, CL, ST>), dim3((unsigned)blocks), dim3(S::kThreads),
                        S::kLdsBytes, rq.stream, a);
 #else
-    using S = TileShape<MCMK_KS, TH, TW, WM, WP, CCH, KG>;
+    using S = TileShape<MCMK_KS, TH, TW, WM, WP, CCH, KG, ST>;
     if (S::kLdsBytes > 65536) {
         // more than 64 KiB of dynamic LDS has to be allowed per kernel, once per device
         static bool allowed[64] = {};
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 1;
         if (!allowed[dev]) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&kn2row_tile_f32<MCMK_KS, TH, TW, WM, WP, CCH, CL, KG>),
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&kn2row_tile_f32<MCMK_KS, TH, TW, WM, WP, CCH, CL, KG, ST>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::kLdsBytes) != hipSuccess)
                 return 1;
             allowed[dev] = true;
         }
     }
-    hipLaunchKernelGGL((kn2row_tile_f32<MCMK_KS, TH, TW, WM, WP, CCH, CL, KG>), dim3((unsigned)blocks), dim3(S::kThreads),
+    hipLaunchKernelGGL((kn2row_tile_f32<MCMK_KS, TH, TW, WM, WP, CCH, CL, KG, ST>), dim3((unsigned)blocks), dim3(S::kThreads),
                        S::kLdsBytes, rq.stream, a);
 #endif
     return hipGetLastError() == hipSuccess ? 0 : 1;
@@ -67,6 +72,21 @@ int launch_shape(const TileRequest &rq)
 
 int MCMK_FN(const TileRequest &rq)
 {
+    if (rq.stride == 2) {
+        if (rq.shape < 0 || rq.shape >= kStridedShapes) return 2;
+        switch (rq.shape + (rq.channels_last ? kStridedShapes : 0)) {
+#if !MCMK_STRIDED_BF16_NCHW_WIDE_ONLY
+        case 0: return launch_shape<14, 14, 4, 2, 16, false, 1, 2>(rq);
+        case 2: return launch_shape<14, 14, 1, 4, 16, false, 1, 2>(rq);
+#endif
+        case 1: return launch_shape<14, 14, 2, 4, 16, false, 1, 2>(rq);
+        case 3: return launch_shape<14, 14, 4, 2, 16, true, 1, 2>(rq);
+        case 4: return launch_shape<14, 14, 2, 4, 16, true, 1, 2>(rq);
+        case 5: return launch_shape<14, 14, 1, 4, 16, true, 1, 2>(rq);
+        default: return 2;
+        }
+    }
+    if (rq.stride != 1) return 2;
     if (rq.channels_last) {
         switch (rq.shape) {
         case 0: return launch_shape<14, 14, 4, 2, 16, true>(rq);

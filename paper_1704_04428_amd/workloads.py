@@ -69,7 +69,7 @@ def small_integers(seed: int, count: int, lo: int, hi: int) -> np.ndarray:
 
 @dataclasses.dataclass(frozen=True)
 class Layer:
-    """One multi-channel multi-kernel convolution problem (stride 1, zero padding)."""
+    """One multi-channel multi-kernel convolution problem (zero padding; stride 1 unless stated)."""
     name: str
     n: int
     c: int
@@ -81,14 +81,15 @@ class Layer:
     input_dist: str = "u01"      # "u01": uniform[0,1) (post-ReLU-like); "u11": uniform[-1,1)
     kernel_dist: str = "he"      # "he": N(0, sqrt(2/(C k^2))); "u11": uniform[-1,1)
     seed: int = 0
+    stride: int = 1
 
     @property
     def q(self) -> int:          # output height
-        return self.h + 2 * self.pad - self.k + 1
+        return (self.h + 2 * self.pad - self.k) // self.stride + 1
 
     @property
     def p(self) -> int:          # output width
-        return self.w + 2 * self.pad - self.k + 1
+        return (self.w + 2 * self.pad - self.k) // self.stride + 1
 
     @property
     def flops(self) -> int:
@@ -115,6 +116,14 @@ LAYERS = {
     "cfg5a_vgg_deep56": Layer("cfg5a_vgg_deep56", 8, 256, 56, 56, 256, 3, 1, "u01", "he", _SEED_BASE + 16 * 5),
     "cfg5b_vgg_deep28": Layer("cfg5b_vgg_deep28", 8, 512, 28, 28, 512, 3, 1, "u01", "he", _SEED_BASE + 16 * 6),
     "cfg5c_vgg_deep14": Layer("cfg5c_vgg_deep14", 8, 512, 14, 14, 512, 3, 1, "u01", "he", _SEED_BASE + 16 * 7),
+}
+
+# The deep VGG-like shape varied along the axes the paper leaves out (stride, even kernel side) and
+# reduced to the 1 x 1 building block of section III-A; measured beside the benchmark layers.
+GENERALISED_LAYERS = {
+    "gen_vgg56_stride2": Layer("gen_vgg56_stride2", 8, 256, 56, 56, 256, 3, 1, "u01", "he", _SEED_BASE + 16 * 8, 2),
+    "gen_vgg56_k4": Layer("gen_vgg56_k4", 8, 256, 56, 56, 256, 4, 2, "u01", "he", _SEED_BASE + 16 * 9),
+    "gen_vgg56_1x1": Layer("gen_vgg56_1x1", 8, 256, 56, 56, 256, 1, 0, "u01", "he", _SEED_BASE + 16 * 10),
 }
 
 

@@ -32,16 +32,18 @@ class Guarded:
         return bool((head == CANARY).all().item()) and bool((tail == CANARY).all().item())
 
 
-def run_variant(variant, I, K, pad, dtype=B.F32, return_ws=False):
-    """I [N][C][H][W] float32 numpy, K [M][C][k][k] float32 numpy -> O float32 numpy via the C ABI."""
+def run_variant(variant, I, K, pad, dtype=B.F32, return_ws=False, stride=1, epilogue=None, one_by_one=False):
+    """I [N][C][H][W] float32 numpy, K [M][C][k][k] float32 numpy -> O float32 numpy via the C ABI.
+    epilogue = (bias [M] float32 numpy or None, relu) routes the call through the *_bias_relu entry
+    point of the variant (kn2row / kn2col); one_by_one = True through conv_mcmk_1x1."""
     import torch
     n, c, h, w = I.shape
     m, _, k, _ = K.shape
-    d = B.desc(n, c, h, w, m, k, pad, 1, dtype)
+    d = B.desc(n, c, h, w, m, k, pad, stride, dtype)
     rc = B.conv_mcmk_check(d, variant)
     if rc != B.OK:
         raise B.ConvMcmkError(rc, B.strerror(rc))
-    q, p = h + 2 * pad - k + 1, w + 2 * pad - k + 1
+    q, p = (h + 2 * pad - k) // stride + 1, (w + 2 * pad - k) // stride + 1
     dev = torch.device("cuda:0")
     channels_last = variant in B.CHANNELS_LAST
     if channels_last:
@@ -61,7 +63,16 @@ def run_variant(variant, I, K, pad, dtype=B.F32, return_ws=False):
     out = Guarded(n * m * q * p * 4)
     ws_bytes = B.conv_mcmk_workspace_bytes(d, variant)
     ws = Guarded(ws_bytes) if ws_bytes else None
-    B.RUNNERS[variant](d, I_dev, kern, out.payload, ws.payload if ws else None)
+    if epilogue is not None:
+        bias, relu = epilogue
+        bias_dev = torch.from_numpy(np.ascontiguousarray(bias, dtype=np.float32)).to(dev) if bias is not None else None
+        fn = {B.KN2ROW: B.conv_mcmk_kn2row_bias_relu, B.KN2COL: B.conv_mcmk_kn2col_bias_relu}[variant]
+        fn(d, I_dev, kern, bias_dev, relu, out.payload)
+    elif one_by_one:
+        assert variant == B.KN2ROW
+        B.conv_mcmk_1x1(d, I_dev, kern, out.payload)
+    else:
+        B.RUNNERS[variant](d, I_dev, kern, out.payload, ws.payload if ws else None)
     torch.cuda.synchronize()
     assert out.intact(), "output guard band overwritten"
     if ws is not None:

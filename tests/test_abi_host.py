@@ -53,12 +53,21 @@ def test_check_rejects_bad_descriptors(lib):
         assert B.conv_mcmk_check(B.desc(**bad), B.KN2ROW_2PASS) == B.ERR_SHAPE, field
     assert B.conv_mcmk_check(B.desc(**dict(ok, pad=-1)), B.KN2ROW) == B.ERR_SHAPE
     assert B.conv_mcmk_check(B.desc(**dict(ok, h=2, w=2, k=5, pad=0)), B.IM2COL) == B.ERR_SHAPE   # empty output
-    assert B.conv_mcmk_check(B.desc(**ok, stride=2), B.KN2ROW) == B.ERR_UNSUPPORTED              # section II-A
+    # strides are a generalisation (section II-A treats unit stride): fused kernels take 1 and 2, the rest any
+    assert B.conv_mcmk_check(B.desc(**ok, stride=0), B.IM2COL) == B.ERR_SHAPE
+    assert B.conv_mcmk_check(B.desc(**ok, stride=2), B.KN2ROW) == B.OK
+    assert B.conv_mcmk_check(B.desc(**ok, stride=3), B.KN2ROW) == B.ERR_UNSUPPORTED
+    assert B.conv_mcmk_check(B.desc(**ok, stride=3), B.KN2COL) == B.ERR_UNSUPPORTED
+    for v in (B.KN2ROW_2PASS, B.IM2COL, B.IM2ROW, B.DIRECT):
+        assert B.conv_mcmk_check(B.desc(**ok, stride=3), v) == B.OK
     assert B.conv_mcmk_check(B.desc(**ok, dtype=7), B.KN2ROW) == B.ERR_UNSUPPORTED
     assert B.conv_mcmk_check(B.desc(**ok), 9) == B.ERR_UNSUPPORTED
-    assert B.conv_mcmk_check(B.desc(**dict(ok, k=4)), B.KN2ROW) == B.ERR_UNSUPPORTED             # fused: k in 1,3,5,7
-    assert B.conv_mcmk_check(B.desc(**dict(ok, k=4)), B.KN2ROW_2PASS) == B.OK
-    assert B.conv_mcmk_check(B.desc(**dict(ok, k=4)), B.KN2COL) == B.ERR_UNSUPPORTED
+    for k in range(1, 8):                                                                         # fused: k = 1 .. 7
+        assert B.conv_mcmk_check(B.desc(**dict(ok, k=k, pad=3)), B.KN2ROW) == B.OK
+        assert B.conv_mcmk_check(B.desc(**dict(ok, k=k, pad=3)), B.KN2COL) == B.OK
+    assert B.conv_mcmk_check(B.desc(**dict(ok, k=8, pad=4)), B.KN2ROW) == B.ERR_UNSUPPORTED
+    assert B.conv_mcmk_check(B.desc(**dict(ok, k=8, pad=4)), B.KN2COL) == B.ERR_UNSUPPORTED
+    assert B.conv_mcmk_check(B.desc(**dict(ok, k=8, pad=4)), B.KN2ROW_2PASS) == B.OK
     assert B.conv_mcmk_check(B.desc(**dict(ok, c=12), dtype=B.BF16), B.KN2COL) == B.ERR_UNSUPPORTED   # octets
     assert B.conv_mcmk_check(B.desc(**dict(ok, c=16), dtype=B.BF16), B.KN2COL) == B.OK
     assert B.conv_mcmk_check(B.desc(**dict(ok, c=12)), B.KN2COL) == B.OK
@@ -74,6 +83,13 @@ def test_sizes(lib):
     assert B.conv_mcmk_workspace_bytes(d, B.DIRECT) == 0
     assert B.conv_mcmk_workspace_bytes(d, B.KN2ROW_2PASS) == 2 * 9 * 35 * 9 * 11 * 4     # k^2 x the output
     assert B.conv_mcmk_workspace_bytes(d, B.IM2COL) == 2 * 20 * 9 * q * p * 4             # k^2 x the input
+    # stride 2: Q = floor((9 + 2 - 3) / 2) + 1 = 5, P = floor((11 + 2 - 3) / 2) + 1 = 6; the patch matrix shrinks,
+    # the two-pass product (all H x W positions of every tap) does not
+    ds = B.desc(2, 20, 9, 11, 35, 3, 1, 2)
+    assert B.conv_mcmk_workspace_bytes(ds, B.IM2COL) == 2 * 20 * 9 * 5 * 6 * 4
+    assert B.conv_mcmk_workspace_bytes(ds, B.IM2ROW) == 2 * 20 * 9 * 5 * 6 * 4
+    assert B.conv_mcmk_workspace_bytes(ds, B.KN2ROW_2PASS) == 2 * 9 * 35 * 9 * 11 * 4
+    assert B.conv_mcmk_packed_kernel_bytes(ds, B.KN2ROW) == B.conv_mcmk_packed_kernel_bytes(d, B.KN2ROW)
     mb, cg = 3, 2      # ceil(35/16), ceil(20/16)
     assert B.conv_mcmk_packed_kernel_bytes(d, B.KN2ROW) == 9 * mb * cg * 256 * 4
     assert B.conv_mcmk_packed_kernel_bytes(d, B.KN2ROW_2PASS) == 9 * mb * cg * 256 * 4
@@ -103,8 +119,10 @@ def test_compute_calls_validate_before_launch(lib):
                  "conv_mcmk_kn2col", "conv_mcmk_im2row"):
         fn = getattr(lib, name)
         assert fn(ctypes.byref(d), null, null, null, null, 0, null) == B.ERR_NULL
-        bad = B.desc(1, 4, 8, 8, 4, 3, 1, stride=2)
+        bad = B.desc(1, 4, 8, 8, 4, 3, 1, dtype=5)
         assert fn(ctypes.byref(bad), null, null, null, null, 0, null) == B.ERR_UNSUPPORTED
+        bad = B.desc(1, 4, 8, 8, 4, 3, 1, stride=0)
+        assert fn(ctypes.byref(bad), null, null, null, null, 0, null) == B.ERR_SHAPE
     fake = ctypes.c_void_p(0x1000)
     odd = ctypes.c_void_p(0x1004)
     assert lib.conv_mcmk_kn2row(ctypes.byref(d), odd, fake, fake, null, 0, null) == B.ERR_ALIGN
@@ -113,6 +131,16 @@ def test_compute_calls_validate_before_launch(lib):
     assert lib.conv_mcmk_prepack(ctypes.byref(d), B.KN2ROW, null, null, null) == B.ERR_NULL
     assert lib.conv_mcmk_prepack(ctypes.byref(d), B.DIRECT, fake, fake, null) == B.ERR_UNSUPPORTED
     assert lib.conv_mcmk_cvt_f32_bf16(null, null, 4, null) == B.ERR_NULL
+    # the epilogue and 1 x 1 entry points validate the same way
+    for name in ("conv_mcmk_kn2row_bias_relu", "conv_mcmk_kn2col_bias_relu"):
+        fn = getattr(lib, name)
+        assert fn(ctypes.byref(d), null, null, null, 1, null, null) == B.ERR_NULL
+        assert fn(ctypes.byref(d), fake, fake, ctypes.c_void_p(0x1002), 1, fake, null) == B.ERR_ALIGN      # bias: 4-byte aligned
+        assert fn(ctypes.byref(B.desc(1, 4, 8, 8, 4, 3, 1, stride=3)), fake, fake, null, 0, fake, null) == B.ERR_UNSUPPORTED
+    assert lib.conv_mcmk_1x1(ctypes.byref(d), fake, fake, fake, null) == B.ERR_UNSUPPORTED               # k = 3
+    d1 = B.desc(1, 4, 8, 8, 4, 1, 0)
+    assert lib.conv_mcmk_1x1(ctypes.byref(d1), null, fake, fake, null) == B.ERR_NULL
+    assert lib.conv_mcmk_1x1(ctypes.byref(d1), fake, odd, fake, null) == B.ERR_ALIGN
 
 
 def test_plan_selection_for_benchmark_layers(lib, monkeypatch):
@@ -138,9 +166,12 @@ def test_plan_selection_for_benchmark_layers(lib, monkeypatch):
     assert "patch matrix [100 x 72]" in B.conv_mcmk_describe_plan(d, B.IM2ROW)
     assert B.conv_mcmk_describe_plan(d, B.KN2COL).startswith("kn2col fused f32")
     with pytest.raises(B.ConvMcmkError):
-        B.conv_mcmk_describe_plan(B.desc(1, 8, 10, 10, 8, 3, 1, stride=2), B.KN2ROW)
+        B.conv_mcmk_describe_plan(B.desc(1, 8, 10, 10, 8, 3, 1, stride=3), B.KN2ROW)
+    # stride 2: 14 x 14 output tiles only, Q = P = 5 here
+    assert "tile 14x14" in B.conv_mcmk_describe_plan(B.desc(1, 8, 10, 10, 8, 3, 1, stride=2), B.KN2ROW)
     monkeypatch.setenv("CONV_MCMK_TILE", "5")
     assert "tile 16x16, waves 1x4, channel groups 1, channel split 1" in B.conv_mcmk_describe_plan(d, B.KN2ROW)
+    assert "tile 14x14" in B.conv_mcmk_describe_plan(B.desc(1, 8, 10, 10, 8, 3, 1, stride=2), B.KN2ROW)   # 16 x 16: not with a stride
     monkeypatch.setenv("CONV_MCMK_TILE", "6")
     assert "channel groups 4" in B.conv_mcmk_describe_plan(d, B.KN2ROW)
     # an entry the operand type does not have is ignored: the selector's own choice stands
@@ -156,6 +187,6 @@ def test_kernel_register_budget():
         pytest.skip("no compiler resource report beside the objects (library built elsewhere)")
     spilling = {k: v for k, v in usage.items() if v.get("VGPRsSpill", 0) or v.get("ScratchSize", 0)}
     assert not spilling, spilling
-    wide = [v for k, v in usage.items() if "kn2row_tile_f32ILi3ELi14ELi14ELi4ELi2ELi16E" in k]
-    assert len(wide) == 2                                   # NCHW and channels-last
+    wide = [v for k, v in usage.items() if "kn2row_tile_f32ILi3ELi14ELi14ELi4ELi2ELi16E" in k and k.endswith("Li1ELi1EEEvNS_8TileArgsE")]
+    assert len(wide) == 2                                   # unit stride, one channel group: NCHW and channels-last
     assert all(v["VGPRs"] + v.get("AGPRs", 0) <= 128 for v in wide), wide

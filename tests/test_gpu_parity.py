@@ -80,8 +80,8 @@ def test_channels_last_shapes_match_oracle(name, variant, case):
     assert_within_bound(got, ref, absref, TOL_F32, f"{name} {case}")
 
 
-@pytest.mark.parametrize("name,variant", [a for a in ALL if a[1] not in (B.KN2ROW, B.KN2COL)])
-@pytest.mark.parametrize("case", EVEN_K + [(1, 8, 12, 13, 10, 2, 1), (2, 4, 11, 10, 20, 4, 1)])
+@pytest.mark.parametrize("name,variant", ALL)
+@pytest.mark.parametrize("case", EVEN_K + [(1, 8, 12, 13, 10, 2, 1), (2, 4, 11, 10, 20, 4, 1), (2, 24, 31, 33, 40, 6, 3)])
 def test_even_kernel_sizes(name, variant, case):
     _skip_unless_supported(variant, case)
     announce("even-k", name, case)
@@ -252,7 +252,7 @@ def test_runtime_errors_through_binding():
         B.conv_mcmk_im2col(d, I, K, O, None)
     assert e.value.code == B.ERR_WORKSPACE
     with pytest.raises(B.ConvMcmkError) as e:
-        B.conv_mcmk_kn2row(B.desc(1, 4, 8, 8, 4, 3, 1, stride=2), I, K, O)
+        B.conv_mcmk_kn2row(B.desc(1, 4, 8, 8, 4, 3, 1, stride=3), I, K, O)
     assert e.value.code == B.ERR_UNSUPPORTED
     with pytest.raises(B.ConvMcmkError) as e:
         B.conv_mcmk_kn2row(d, I[1:], K, O)
@@ -260,7 +260,7 @@ def test_runtime_errors_through_binding():
 
 
 @pytest.mark.parametrize("dtype", [B.F32, B.BF16])
-@pytest.mark.parametrize("k,pad", [(1, 0), (3, 1), (5, 2), (7, 3)])
+@pytest.mark.parametrize("k,pad", [(1, 0), (2, 1), (3, 1), (4, 1), (5, 2), (6, 3), (7, 3)])
 def test_every_tile_shape_of_the_menu(k, pad, dtype, monkeypatch):
     """The selector only ever launches the shape it prefers; force each of the 12 menu entries
     (7 tile/wave shapes x channel split 1 and 2; entries the operand type does not have fall back to the selector) so every instantiation is checked."""
