@@ -125,6 +125,22 @@ size_t conv_mcmk_packed_kernel_bytes(const conv_mcmk_desc *desc, int variant);
 int conv_mcmk_prepack(const conv_mcmk_desc *desc, int variant, const void *K_dev, void *Kp_dev, void *stream);
 
 /*
+ * Per-layer choice of the algorithm (the paper's conclusion: no single method wins on every layer, so
+ * a network should pick per layer).  Estimates the run time of every variant that can run `desc` in
+ * the given layout (channels_last = 0: KN2ROW, KN2ROW_2PASS, IM2COL, DIRECT on I[N][C][H][W];
+ * channels_last = 1: KN2COL, IM2ROW on I[N][H][W][C]) and whose workspace does not exceed
+ * ws_limit_bytes, and returns the cheapest in *variant (and its estimate in microseconds in *est_us,
+ * which may be NULL).  Host only.  Errors: CONV_MCMK_ERR_WORKSPACE when only the limit stands in the
+ * way, otherwise the error conv_mcmk_check gives (e.g. bf16 with k > 7 and no workspace: the fused
+ * kernel does not take the k, DIRECT does not take the type).
+ */
+int conv_mcmk_select(const conv_mcmk_desc *desc, int channels_last, size_t ws_limit_bytes, int *variant, double *est_us);
+
+/* conv_mcmk_<variant>() chosen by number: the call to follow conv_mcmk_select + conv_mcmk_prepack. */
+int conv_mcmk_run(const conv_mcmk_desc *desc, int variant, const void *I_dev, const void *K_dev, void *O_dev,
+                  void *ws, size_t ws_bytes, void *stream);
+
+/*
  * The convolution itself, one entry point per variant, same signature.
  *   I_dev   input, float or bfloat16 per desc->dtype
  *   Kp_dev  kernel: the packed form from conv_mcmk_prepack(desc, <this variant>) --

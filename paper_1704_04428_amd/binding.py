@@ -25,7 +25,7 @@ EXPORTS = (
     "conv_mcmk_strerror", "conv_mcmk_check", "conv_mcmk_describe_plan", "conv_mcmk_workspace_bytes", "conv_mcmk_packed_kernel_bytes",
     "conv_mcmk_prepack", "conv_mcmk_kn2row", "conv_mcmk_kn2row_2pass", "conv_mcmk_im2col",
     "conv_mcmk_direct", "conv_mcmk_kn2col", "conv_mcmk_im2row", "conv_mcmk_cvt_f32_bf16",
-    "conv_mcmk_kn2row_bias_relu", "conv_mcmk_kn2col_bias_relu", "conv_mcmk_1x1",
+    "conv_mcmk_kn2row_bias_relu", "conv_mcmk_kn2col_bias_relu", "conv_mcmk_1x1", "conv_mcmk_select", "conv_mcmk_run",
 )
 
 
@@ -78,6 +78,10 @@ def lib():
             fn = getattr(L, name)
             fn.argtypes = [dp, vp, vp, vp, i, vp, vp]
             fn.restype = i
+        L.conv_mcmk_select.argtypes = [dp, i, sz, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_double)]
+        L.conv_mcmk_select.restype = i
+        L.conv_mcmk_run.argtypes = [dp, i, vp, vp, vp, vp, sz, vp]
+        L.conv_mcmk_run.restype = i
         L.conv_mcmk_1x1.argtypes = [dp, vp, vp, vp, vp]
         L.conv_mcmk_1x1.restype = i
         L.conv_mcmk_cvt_f32_bf16.argtypes = [vp, vp, sz, vp]
@@ -173,6 +177,18 @@ def conv_mcmk_1x1(d, I, Kp, O, stream=None):
     _raise(lib().conv_mcmk_1x1(ctypes.byref(d), _ptr(I), _ptr(Kp), _ptr(O), _stream(stream)))
 
 
+def conv_mcmk_select(d, channels_last=False, ws_limit_bytes=2 ** 62):
+    """(variant, estimated microseconds) of the cheapest variant for this layer."""
+    variant, est = ctypes.c_int(-1), ctypes.c_double(0.0)
+    _raise(lib().conv_mcmk_select(ctypes.byref(d), int(channels_last), ws_limit_bytes, ctypes.byref(variant), ctypes.byref(est)))
+    return variant.value, est.value
+
+
+def conv_mcmk_run(d, variant, I, K, O, ws=None, stream=None):
+    ws_bytes = ws.numel() * ws.element_size() if ws is not None else 0
+    _raise(lib().conv_mcmk_run(ctypes.byref(d), variant, _ptr(I), _ptr(K), _ptr(O), _ptr(ws), ws_bytes, _stream(stream)))
+
+
 def conv_mcmk_cvt_f32_bf16(src, dst, count=None, stream=None):
     n = src.numel() if count is None else count
     _raise(lib().conv_mcmk_cvt_f32_bf16(_ptr(src), _ptr(dst), n, _stream(stream)))
@@ -203,6 +219,12 @@ class Plan:
         shape = (d.n, q, p, d.m) if variant in CHANNELS_LAST else (d.n, d.m, q, p)
         self.out = torch.empty(shape, dtype=torch.float32, device=dev)
 
+    @classmethod
+    def auto(cls, d: Desc, K_dev, channels_last=False, ws_limit_bytes=2 ** 62):
+        """The plan for the variant conv_mcmk_select prefers."""
+        variant, _ = conv_mcmk_select(d, channels_last, ws_limit_bytes)
+        return cls(d, variant, K_dev)
+
     def run(self, I_dev, stream=None):
-        RUNNERS[self.variant](self.d, I_dev, self.kernel, self.out, self.ws, stream)
+        conv_mcmk_run(self.d, self.variant, I_dev, self.kernel, self.out, self.ws, stream)
         return self.out

@@ -193,7 +193,12 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
     const long long held = per_cu < can_hold ? per_cu : can_hold;
     const double waves_per_simd = (double)held * waves / 4.0;
     const double pipe_use = waves_per_simd >= 2.0 ? 0.9 : 0.7;
-    double us = (double)per_cu * simd_load * steps * 0.0139 / pipe_use + 6.0;
+    double us = (double)per_cu * simd_load * steps * 0.0139 / pipe_use;
+    // staging-heavy cases: a 1 x 1 kernel uses every staged value once instead of k*k times, a
+    // strided tile stages four input values per output position (both measured)
+    if (ks == 1 && c.shape != kGemmShape) us *= 1.35;
+    if (d->stride == 2) us *= 1.25;
+    us += 6.0;
     if (c.csplit > 1) us += 3.0 + 2.0 * (double)d->n * d->m * dm.q * dm.p * 6.25e-6;
     if (c.kg > 1) us += 1.5;                                            // the closing exchange through LDS
     return us;
@@ -225,6 +230,53 @@ Candidate choose_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_la
             if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = c; }
         }
     return best;
+}
+
+// ------------------------------------------------------------------------------------------
+// Estimated run time in microseconds of a whole variant (the per-layer choice among algorithms the
+// paper's conclusion calls for).  Pieces: the tile-kernel estimate above for the matrix work; the
+// memory-bound passes at the 3.5 TB/s they were measured to sustain plus a launch; the direct loop
+// nest at its measured 3 TFLOP/s.
+double gemm_cost(const conv_mcmk_desc *d, long long kc, long long cols, int row_groups)
+{
+    conv_mcmk_desc g = *d;
+    g.c = (int)kc;  g.h = 1;  g.w = (int)cols;  g.k = 1;  g.pad = 0;  g.stride = 1;
+    Dims dm{1, (int)cols, ceil_div(d->m, 16) * row_groups, 1};
+    const TileShapeDesc &sh = kTileShapes[kGemmShape];
+    const Candidate c{kGemmShape, 1, sh.th, sh.tw, sh.wm, sh.wp, sh.kg};
+    // a staged tile serves one tap, not k*k: about 1.2 x the fused kernel's time per MFMA
+    return 1.2 * tile_cost(&g, dm, c, 1);
+}
+
+// a memory-bound pass before or after the matrix kernel: its bytes, its launch, and the drain / fill
+// between two dependent kernels
+double stream_cost(double bytes) { return bytes / 3.5e6 + 12.0; }
+
+double variant_cost(const conv_mcmk_desc *d, const Dims &dm, int variant)
+{
+    const double elt = d->dtype == CONV_MCMK_BF16 ? 2.0 : 4.0;
+    const double in_elems = (double)d->n * d->c * d->h * d->w;
+    const double patch_elems = (double)d->n * d->c * dm.taps * dm.q * dm.p;
+    switch (variant) {
+    case CONV_MCMK_KN2ROW:
+    case CONV_MCMK_KN2COL:
+        return tile_cost(d, dm, choose_fused(d, dm, variant == CONV_MCMK_KN2COL), d->k);
+    case CONV_MCMK_KN2ROW_2PASS: {
+        const double planes = (double)d->n * d->m * d->h * d->w;
+        return gemm_cost(d, d->c, (long long)d->h * d->w, dm.taps) +
+               stream_cost(4.0 * (dm.taps * planes + (double)d->n * d->m * dm.q * dm.p));
+    }
+    case CONV_MCMK_IM2COL:
+    case CONV_MCMK_IM2ROW:
+        return stream_cost(elt * (in_elems + patch_elems)) + gemm_cost(d, (long long)d->c * dm.taps, (long long)dm.q * dm.p, 1);
+    default: {
+        // one thread per output walks its C*k*k terms one after the other (0.12 us each when the chip
+        // is not full); a full chip sustains 3 TFLOP/s
+        const double serial = 0.12 * d->c * dm.taps;
+        const double bulk = 2.0 * d->n * d->m * (double)d->c * dm.taps * dm.q * dm.p / 3.0e6;
+        return (serial > bulk ? serial : bulk) + 5.0;
+    }
+    }
 }
 
 int launch_fused(const conv_mcmk_desc *d, const Dims &dm, const void *in, const void *apk, float *out,
@@ -312,19 +364,22 @@ int conv_mcmk_describe_plan(const conv_mcmk_desc *d, int variant, char *buf, siz
         break;
     }
     case CONV_MCMK_KN2ROW_2PASS:
-        snprintf(buf, n, "kn2row two-pass %s: GEMM [%d x %d].[%d x %d] per image (tile 1x%d, waves %dx%d), then shift-add",
-                 type, dm.taps * d->m, d->c, d->c, d->h * d->w, g.tw, g.wm, g.wp);
+        snprintf(buf, n, "kn2row two-pass %s: GEMM [%d x %d].[%d x %d] per image (tile 1x%d, waves %dx%d), then shift-add, est %.1f us",
+                 type, dm.taps * d->m, d->c, d->c, d->h * d->w, g.tw, g.wm, g.wp, variant_cost(d, dm, variant));
         break;
     case CONV_MCMK_IM2COL:
-        snprintf(buf, n, "im2col %s: patch matrix [%d x %d] per image, GEMM [%d x %d].[%d x %d] (tile 1x%d, waves %dx%d)",
-                 type, d->c * dm.taps, dm.q * dm.p, d->m, d->c * dm.taps, d->c * dm.taps, dm.q * dm.p, g.tw, g.wm, g.wp);
+        snprintf(buf, n, "im2col %s: patch matrix [%d x %d] per image, GEMM [%d x %d].[%d x %d] (tile 1x%d, waves %dx%d), est %.1f us",
+                 type, d->c * dm.taps, dm.q * dm.p, d->m, d->c * dm.taps, d->c * dm.taps, dm.q * dm.p, g.tw, g.wm, g.wp,
+                 variant_cost(d, dm, variant));
         break;
     case CONV_MCMK_IM2ROW:
-        snprintf(buf, n, "im2row %s: patch matrix [%d x %d] per image (channels last), GEMM [%d x %d].[%d x %d] (tile 1x%d, waves %dx%d)",
-                 type, dm.q * dm.p, d->c * dm.taps, dm.q * dm.p, d->c * dm.taps, d->c * dm.taps, d->m, g.tw, g.wm, g.wp);
+        snprintf(buf, n, "im2row %s: patch matrix [%d x %d] per image (channels last), GEMM [%d x %d].[%d x %d] (tile 1x%d, waves %dx%d), est %.1f us",
+                 type, dm.q * dm.p, d->c * dm.taps, dm.q * dm.p, d->c * dm.taps, d->c * dm.taps, d->m, g.tw, g.wm, g.wp,
+                 variant_cost(d, dm, variant));
         break;
     default:
-        snprintf(buf, n, "direct f32: one thread per output element, %lld outputs", (long long)d->n * d->m * dm.q * dm.p);
+        snprintf(buf, n, "direct f32: one thread per output element, %lld outputs, est %.1f us",
+                 (long long)d->n * d->m * dm.q * dm.p, variant_cost(d, dm, variant));
         break;
     }
     return CONV_MCMK_OK;
@@ -521,6 +576,48 @@ int conv_mcmk_direct(const conv_mcmk_desc *d, const void *I_dev, const void *K_d
                        static_cast<const float *>(I_dev), static_cast<const float *>(K_dev),
                        static_cast<float *>(O_dev), d->n, d->c, d->h, d->w, d->m, d->k, d->pad, d->stride, dm.q, dm.p);
     return launch_status();
+}
+
+int conv_mcmk_select(const conv_mcmk_desc *d, int channels_last, size_t ws_limit_bytes, int *variant, double *est_us)
+{
+    if (!d || !variant) return CONV_MCMK_ERR_NULL;
+    static const int kFirst[] = {CONV_MCMK_KN2ROW, CONV_MCMK_KN2ROW_2PASS, CONV_MCMK_IM2COL, CONV_MCMK_DIRECT};
+    static const int kLast[] = {CONV_MCMK_KN2COL, CONV_MCMK_IM2ROW};
+    const int *menu = channels_last ? kLast : kFirst;
+    const int count = channels_last ? 2 : 4;
+    int best = -1, worst_rc = CONV_MCMK_OK;
+    double best_cost = 0.0;
+    bool over_limit = false;
+    for (int i = 0; i < count; ++i) {
+        Dims dm;
+        const int rc = validate(d, menu[i], &dm);
+        if (rc) {
+            // a malformed descriptor fails every variant the same way; remember the reason
+            if (worst_rc == CONV_MCMK_OK || rc == CONV_MCMK_ERR_SHAPE) worst_rc = rc;
+            continue;
+        }
+        if (conv_mcmk_workspace_bytes(d, menu[i]) > ws_limit_bytes) { over_limit = true; continue; }
+        const double cost = variant_cost(d, dm, menu[i]);
+        if (best < 0 || cost < best_cost) { best = menu[i]; best_cost = cost; }
+    }
+    if (best < 0) return over_limit ? CONV_MCMK_ERR_WORKSPACE : worst_rc ? worst_rc : CONV_MCMK_ERR_UNSUPPORTED;
+    *variant = best;
+    if (est_us) *est_us = best_cost;
+    return CONV_MCMK_OK;
+}
+
+int conv_mcmk_run(const conv_mcmk_desc *d, int variant, const void *I_dev, const void *K_dev, void *O_dev,
+                  void *ws, size_t ws_bytes, void *stream)
+{
+    switch (variant) {
+    case CONV_MCMK_KN2ROW: return conv_mcmk_kn2row(d, I_dev, K_dev, O_dev, ws, ws_bytes, stream);
+    case CONV_MCMK_KN2ROW_2PASS: return conv_mcmk_kn2row_2pass(d, I_dev, K_dev, O_dev, ws, ws_bytes, stream);
+    case CONV_MCMK_IM2COL: return conv_mcmk_im2col(d, I_dev, K_dev, O_dev, ws, ws_bytes, stream);
+    case CONV_MCMK_DIRECT: return conv_mcmk_direct(d, I_dev, K_dev, O_dev, ws, ws_bytes, stream);
+    case CONV_MCMK_KN2COL: return conv_mcmk_kn2col(d, I_dev, K_dev, O_dev, ws, ws_bytes, stream);
+    case CONV_MCMK_IM2ROW: return conv_mcmk_im2row(d, I_dev, K_dev, O_dev, ws, ws_bytes, stream);
+    default: return d ? CONV_MCMK_ERR_UNSUPPORTED : CONV_MCMK_ERR_NULL;
+    }
 }
 
 int conv_mcmk_cvt_f32_bf16(const void *src_dev, void *dst_dev, size_t count, void *stream)

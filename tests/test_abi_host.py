@@ -190,3 +190,40 @@ def test_kernel_register_budget():
     wide = [v for k, v in usage.items() if "kn2row_tile_f32ILi3ELi14ELi14ELi4ELi2ELi16E" in k and k.endswith("Li1ELi1EEEvNS_8TileArgsE")]
     assert len(wide) == 2                                   # unit stride, one channel group: NCHW and channels-last
     assert all(v["VGPRs"] + v.get("AGPRs", 0) <= 128 for v in wide), wide
+
+
+def test_variant_selection(lib, monkeypatch):
+    """The per-layer choice among algorithms (host logic): the fused kernel wherever it applies, a
+    staged variant where it does not, the workspace limit honoured."""
+    import ctypes
+    from paper_1704_04428_amd import workloads as wl
+    monkeypatch.delenv("CONV_MCMK_TILE", raising=False)
+    for L in list(wl.LAYERS.values()) + list(wl.GENERALISED_LAYERS.values()):
+        d = B.desc(L.n, L.c, L.h, L.w, L.m, L.k, L.pad, L.stride)
+        variant, est = B.conv_mcmk_select(d)
+        assert variant == B.KN2ROW and est > 0, L.name
+        assert B.conv_mcmk_select(d, ws_limit_bytes=0)[0] == B.KN2ROW                # needs no workspace
+        if L.c % 4 == 0:
+            assert B.conv_mcmk_select(d, channels_last=True)[0] == B.KN2COL
+    # a first-layer-like 11 x 11 kernel with stride 4: outside the fused kernels, so a staged variant;
+    # the patch matrix is small (stride 4), the two-pass product is not
+    big = B.desc(1, 3, 227, 227, 96, 11, 0, 4)
+    assert B.conv_mcmk_select(big)[0] == B.IM2COL
+    assert B.conv_mcmk_select(big, ws_limit_bytes=B.conv_mcmk_workspace_bytes(big, B.IM2COL) - 1)[0] == B.DIRECT
+    assert B.conv_mcmk_select(B.desc(1, 4, 227, 227, 96, 11, 0, 4), channels_last=True)[0] == B.IM2ROW
+    # bf16 operands, k = 9, no workspace allowed: nothing can run it
+    with pytest.raises(B.ConvMcmkError) as e:
+        B.conv_mcmk_select(B.desc(1, 8, 30, 30, 8, 9, 4, 1, B.BF16), ws_limit_bytes=0)
+    assert e.value.code == B.ERR_WORKSPACE
+    with pytest.raises(B.ConvMcmkError) as e:
+        B.conv_mcmk_select(B.desc(1, 8, 0, 30, 8, 3, 1))
+    assert e.value.code == B.ERR_SHAPE
+    with pytest.raises(B.ConvMcmkError) as e:
+        B.conv_mcmk_select(B.desc(1, 6, 30, 30, 8, 3, 1), channels_last=True)            # channel vectors of 4
+    assert e.value.code == B.ERR_UNSUPPORTED
+    out = ctypes.c_int(0)
+    assert lib.conv_mcmk_select(None, 0, 0, ctypes.byref(out), None) == B.ERR_NULL
+    assert lib.conv_mcmk_select(ctypes.byref(big), 0, 0, None, None) == B.ERR_NULL
+    null = ctypes.c_void_p(0)
+    assert lib.conv_mcmk_run(ctypes.byref(big), 17, null, null, null, null, 0, null) == B.ERR_UNSUPPORTED
+    assert lib.conv_mcmk_run(ctypes.byref(big), B.IM2COL, null, null, null, null, 0, null) == B.ERR_NULL

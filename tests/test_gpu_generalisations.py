@@ -175,3 +175,49 @@ def test_one_by_one_entry_point_refuses_larger_kernels():
     with pytest.raises(B.ConvMcmkError) as e:
         B.conv_mcmk_1x1(d, buf, buf, buf)
     assert e.value.code == B.ERR_UNSUPPORTED
+
+
+# ------------------------------------------------------------------ per-layer choice among the algorithms
+
+@pytest.mark.parametrize("case", [
+    (1, 3, 227, 227, 96, 11, 0, 4),      # first-layer-like: outside the fused kernels
+    (1, 64, 30, 30, 64, 9, 4, 1),
+    (1, 32, 28, 28, 96, 5, 2, 1),
+    (2, 128, 28, 28, 128, 3, 1, 1),
+    (1, 16, 32, 32, 16, 3, 1, 1),
+    (1, 8, 64, 64, 8, 8, 4, 3),
+])
+def test_selected_variant_is_correct_and_near_the_fastest(case):
+    """conv_mcmk_select + Plan.auto: the chosen variant gives the oracle's result, and none of the
+    other variants in the same layout is more than 1.5 x faster when timed here."""
+    import torch
+    announce("select", case)
+    n, c, h, w, m, k, pad, stride = case
+    I, K = _inputs(case, 3600 + sum(case))
+    ref, absref = oracle.mcmk(I, K, pad, stride)
+    d = B.desc(n, c, h, w, m, k, pad, stride)
+    I_dev, K_dev = torch.from_numpy(I).cuda(), torch.from_numpy(K).cuda()
+    chosen, _ = B.conv_mcmk_select(d)
+    plan = B.Plan.auto(d, K_dev)
+    assert plan.variant == chosen
+    got = plan.run(I_dev).cpu().numpy()
+    assert_within_bound(got, ref, absref, TOL_F32, f"selected variant {chosen} {case}")
+
+    def timed(p):
+        for _ in range(20):
+            p.run(I_dev)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(50):
+            p.run(I_dev)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / 50
+
+    times = {}
+    for variant in (B.KN2ROW, B.KN2ROW_2PASS, B.IM2COL, B.DIRECT):
+        if B.conv_mcmk_check(d, variant) == B.OK:
+            times[variant] = timed(B.Plan(d, variant, K_dev))
+    announce("select times (ms)", {v: round(t, 4) for v, t in times.items()}, "chosen", chosen)
+    assert times[chosen] <= 1.5 * min(times.values()), (times, chosen)
