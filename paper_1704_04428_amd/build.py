@@ -16,6 +16,10 @@ FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument",
     "-Rpass-analysis=kernel-resource-usage",       # per-kernel register / LDS / spill report, kept beside the objects
+    # the tile kernels are written as fully unrolled loops over (tap, position block); for 7 x 7 kernels the
+    # body passes the default size limit for '#pragma unroll', and a loop left rolled turns the register
+    # rings into scratch memory
+    "-mllvm", "-pragma-unroll-threshold=200000",
 ]
 JOBS = 8
 TIMEOUT_S = 900      # per translation unit; a compile that takes longer is a bug, not patience

@@ -86,8 +86,14 @@ int grid_for(size_t total, int block)
 struct Candidate {
     int shape;     // index into kTileShapes
     int csplit;    // 1 or 2
-    int th, tw, wm, wp, kg;
+    int th, tw, wm, wp, kg, rb;
 };
+
+Candidate candidate(int shape, int csplit)
+{
+    const TileShapeDesc &t = kTileShapes[shape];
+    return Candidate{shape, csplit, t.th, t.tw, t.wm, t.wp, t.kg, t.rb};
+}
 
 int run_tile(int dtype, int ks, const TileRequest &rq)
 {
@@ -169,7 +175,7 @@ int launch_tile(const conv_mcmk_desc *d, const Dims &dm, int ks, int shape, int 
 //     device-scope atomic adds per output element.
 double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, int ks)
 {
-    const long long tiles = (long long)d->n * ceil_div(dm.p, c.tw) * ceil_div(dm.q, c.th) * ceil_div(dm.mb, c.wm);
+    const long long tiles = (long long)d->n * ceil_div(dm.p, c.tw) * ceil_div(dm.q, c.th) * ceil_div(dm.mb, c.wm * c.rb);
     const long long wgs = tiles * c.csplit;
     const int npb = ceil_div(c.th * c.tw, 16);
     const int group_waves = c.wm * c.wp;
@@ -179,7 +185,7 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
         const int g = w / group_waves;                                  // channel group, rotated by g
         const int wp = ((w % group_waves + g * c.wm) % group_waves) / c.wm;
         const int rem = npb % c.wp, pbw = ceil_div(npb, c.wp);
-        simd_blocks[w % 4] += (rem == 0 || wp < rem) ? pbw : pbw - 1;
+        simd_blocks[w % 4] += c.rb * ((rem == 0 || wp < rem) ? pbw : pbw - 1);
     }
     int simd_load = 0;
     for (int i = 0; i < 4; ++i) simd_load = simd_blocks[i] > simd_load ? simd_blocks[i] : simd_load;
@@ -189,34 +195,52 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
     // fp32: 4 MFMAs of 32 cycles per tap and 16-channel chunk; bf16: 1 MFMA of 16 cycles per tap and 32-channel chunk
     const double steps = (double)chunks * ks * ks * (bf16 ? 0.5 : 4.0);
     const long long per_cu = (wgs + kNumCU - 1) / kNumCU;
-    const int can_hold = c.kg > 1 ? 1 : 16 / waves;                    // workgroups a CU can hold (LDS, VGPRs)
+    // workgroups a CU can hold (LDS, VGPRs): the bf16 kernels need more than 128 registers, so 8 waves per CU
+    const int can_hold = c.kg > 1 ? 1 : (bf16 ? 8 : 16) / waves;
     const long long held = per_cu < can_hold ? per_cu : can_hold;
     const double waves_per_simd = (double)held * waves / 4.0;
-    const double pipe_use = waves_per_simd >= 2.0 ? 0.9 : 0.7;
+    double pipe_use = waves_per_simd >= 2.0 ? 0.9 : 0.7;
+    // bf16: the product is four times shorter than the fp32 one while a B fragment is four times
+    // larger, so LDS reads, operand loads and the per-chunk hand-over weigh more; measured slopes over
+    // the channel count give 48 % of the pipe with one row block per wave and 59 % with two
+    if (bf16) {
+        pipe_use *= c.rb > 1 ? 0.65 : 0.53;
+        // an A fragment (1 KB from L1/L2 per wave) is reused for the wave's position blocks, the staged
+        // tile for the workgroup's rows: few blocks per wave or few rows per workgroup leave the
+        // load path, not the matrix pipe, as the limit (fitted to the sweep of all shapes)
+        const double reuse_a = 0.25 + 0.107 * ceil_div(npb, c.wp);
+        const double rows = 16.0 * c.wm * c.rb;
+        const double reuse_b = rows / (rows + 16.0) / 0.8;
+        pipe_use *= (reuse_a < 1.1 ? reuse_a : 1.1) * (reuse_b < 1.0 ? reuse_b : 1.0);
+    }
     double us = (double)per_cu * simd_load * steps * 0.0139 / pipe_use;
     // staging-heavy cases: a 1 x 1 kernel uses every staged value once instead of k*k times, a
     // strided tile stages four input values per output position (both measured)
     if (ks == 1 && c.shape != kGemmShape) us *= 1.35;
     if (d->stride == 2) us *= 1.25;
-    us += 6.0;
+    us += bf16 ? 9.0 : 6.0;          // launch, first loads, output write (bf16 workgroups: twice the rows to write)
     if (c.csplit > 1) us += 3.0 + 2.0 * (double)d->n * d->m * dm.q * dm.p * 6.25e-6;
     if (c.kg > 1) us += 1.5;                                            // the closing exchange through LDS
     return us;
 }
 
 // The candidate the cost estimate prefers for the fused kernel (or the one CONV_MCMK_TILE forces:
-// tuning aid, menu index = shape + 7 * (csplit - 1)).
+// tuning aid, menu index = shape + 7 * (csplit - 1) for the seven common shapes, then
+// 14 + wide shape + 3 * (csplit - 1) for the bf16 shapes with two row blocks per wave).
 Candidate choose_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, bool epilogue = false)
 {
     Candidate best{};
     double best_cost = -1.0;
-    int index = 0;
     const char *force = getenv("CONV_MCMK_TILE");
     if (force && (force[0] < '0' || force[0] > '9')) force = nullptr;
+    const int menu_len = kConvShapes + kWideConvShapes;
+    for (int pass = 0, index = 0; pass < 2; ++pass)                    // common shapes, then the wide ones
     for (int cs = 1; cs <= 2; ++cs)
-        for (int sh = 0; sh < kConvShapes; ++sh, ++index) {
-            const Candidate c{sh, cs, kTileShapes[sh].th, kTileShapes[sh].tw, kTileShapes[sh].wm, kTileShapes[sh].wp,
-                              kTileShapes[sh].kg};
+        for (int pos = pass == 0 ? 0 : kConvShapes; pos < (pass == 0 ? kConvShapes : menu_len); ++pos, ++index) {
+            const int sh = pos < kConvShapes ? pos : kWideConvShape[pos - kConvShapes];
+            const Candidate c = candidate(sh, cs);
+            // two row blocks per wave: bf16 operands, unit stride
+            if (c.rb > 1 && (d->dtype != CONV_MCMK_BF16 || d->stride > 1 || d->k > 3)) continue;
             // channel groups exist for fp32 and kernel sides up to 3 only (four groups of double-buffered
             // 5x5 halo tiles would not fit the 160 KB of LDS) and are an alternative to, not a partner
             // of, the two-way split
@@ -242,8 +266,7 @@ double gemm_cost(const conv_mcmk_desc *d, long long kc, long long cols, int row_
     conv_mcmk_desc g = *d;
     g.c = (int)kc;  g.h = 1;  g.w = (int)cols;  g.k = 1;  g.pad = 0;  g.stride = 1;
     Dims dm{1, (int)cols, ceil_div(d->m, 16) * row_groups, 1};
-    const TileShapeDesc &sh = kTileShapes[kGemmShape];
-    const Candidate c{kGemmShape, 1, sh.th, sh.tw, sh.wm, sh.wp, sh.kg};
+    const Candidate c = candidate(kGemmShape, 1);
     // a staged tile serves one tap, not k*k: about 1.2 x the fused kernel's time per MFMA
     return 1.2 * tile_cost(&g, dm, c, 1);
 }
@@ -287,14 +310,27 @@ int launch_fused(const conv_mcmk_desc *d, const Dims &dm, const void *in, const 
                        channels_last, d->stride, ep);
 }
 
+// bf16 GEMMs take the shape with two row blocks per wave (128 rows per workgroup) when that still
+// leaves a workgroup for every compute unit (CONV_MCMK_GEMM_TILE = 7 or 11 overrides: tuning aid).
+int gemm_shape(const conv_mcmk_desc *d, const Dims &dm, long long cols, int row_groups)
+{
+    if (d->dtype != CONV_MCMK_BF16) return kGemmShape;
+    const char *force = getenv("CONV_MCMK_GEMM_TILE");
+    if (force && atoi(force) == kWideGemmShape) return kWideGemmShape;
+    if (force && atoi(force) == kGemmShape) return kGemmShape;
+    const TileShapeDesc &w = kTileShapes[kWideGemmShape];
+    const long long wide_wgs = (long long)d->n * ceil_div(cols, w.tw) * ceil_div((long long)dm.mb * row_groups, w.wm * w.rb);
+    return wide_wgs >= kNumCU ? kWideGemmShape : kGemmShape;
+}
+
 // Plain GEMM [rows x kc] . [kc x cols] per image on the same tile kernel: a 1x1 "convolution" over a
 // 1 x cols image.
 int launch_gemm(const conv_mcmk_desc *d, const Dims &dm, const void *bmat, const void *apk, float *cmat,
                 int kc, long long cols, int row_groups, hipStream_t st, bool channels_last = false)
 {
     if (cols >= (1LL << 31)) return CONV_MCMK_ERR_SHAPE;
-    return launch_tile(d, dm, 1, kGemmShape, 1, bmat, apk, cmat, kc, 1, (int)cols, 1, (int)cols, 0, row_groups, st,
-                       channels_last);
+    return launch_tile(d, dm, 1, gemm_shape(d, dm, cols, row_groups), 1, bmat, apk, cmat, kc, 1, (int)cols, 1, (int)cols, 0,
+                       row_groups, st, channels_last);
 }
 
 int common_ptr_checks(const void *I, const void *K, const void *O)
@@ -357,9 +393,9 @@ int conv_mcmk_describe_plan(const conv_mcmk_desc *d, int variant, char *buf, siz
     case CONV_MCMK_KN2ROW:
     case CONV_MCMK_KN2COL: {
         const Candidate c = choose_fused(d, dm, variant == CONV_MCMK_KN2COL);
-        const long long wgs = (long long)d->n * ceil_div(dm.p, c.tw) * ceil_div(dm.q, c.th) * ceil_div(dm.mb, c.wm) * c.csplit;
-        snprintf(buf, n, "%s fused %s: tile %dx%d, waves %dx%d, channel groups %d, channel split %d, %lld workgroups, est %.1f us",
-                 variant == CONV_MCMK_KN2COL ? "kn2col" : "kn2row", type, c.th, c.tw, c.wm, c.wp, c.kg, c.csplit, wgs,
+        const long long wgs = (long long)d->n * ceil_div(dm.p, c.tw) * ceil_div(dm.q, c.th) * ceil_div(dm.mb, c.wm * c.rb) * c.csplit;
+        snprintf(buf, n, "%s fused %s: tile %dx%d, waves %dx%d, row blocks %d, channel groups %d, channel split %d, %lld workgroups, est %.1f us",
+                 variant == CONV_MCMK_KN2COL ? "kn2col" : "kn2row", type, c.th, c.tw, c.wm, c.wp, c.rb, c.kg, c.csplit, wgs,
                  tile_cost(d, dm, c, d->k));
         break;
     }

@@ -55,7 +55,11 @@ struct TileShapeBf16 {
 // c % 8 == 0 so that a channel octet of one position is one aligned 16-byte load -- the staging
 // transpose disappears.
 // ST: stride of the convolution (1 or 2), as in kn2row_tile_f32.
-template <int KS, int TH, int TW, int WM, int WP, bool CL = false, int ST = 1>
+// RB: 16-row blocks per wave.  A B fragment read from LDS (1 KB per wave) feeds RB products, and the
+//     bf16 product is so short (16 cycles) that one read per product would keep the LDS, not the matrix
+//     pipe, busy: four SIMDs x one 1 KB read per 16 cycles is the whole LDS bandwidth of a compute unit.
+//     The workgroup covers 16*WM*RB rows.
+template <int KS, int TH, int TW, int WM, int WP, bool CL = false, int ST = 1, int RB = 1>
 __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs a)
 {
     using S = TileShapeBf16<KS, TH, TW, WM, WP, ST>;
@@ -89,11 +93,16 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs 
     const int ix0 = x0 * ST - a.pad, iy0 = y0 * ST - a.pad;       // input position under halo-tile element (0, 0)
 
     const int total_rb = a.row_groups * a.mb_per_group;
-    int rb = rt * WM + wm;
-    const bool rb_valid = rb < total_rb;
-    if (!rb_valid) rb = total_rb - 1;
-    const int grp = rb / a.mb_per_group;
-    const int mbi = rb % a.mb_per_group;
+    bool rb_valid[RB];
+    int grp[RB], mbi[RB];                        // row group (tap plane of a row-group GEMM) and block inside it
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+        int rb = (rt * WM + wm) * RB + r;
+        rb_valid[r] = rb < total_rb;
+        if (!rb_valid[r]) rb = total_rb - 1;     // keep loads in bounds; nothing is stored
+        grp[r] = rb / a.mb_per_group;
+        mbi[r] = rb % a.mb_per_group;
+    }
 
     // ---- staging plan: item e = tid + s*NT is (channel octet e / POS, position e % POS).
     // 2-byte loads through a range-checked buffer descriptor: outside the image (offset 2 GiB) and
@@ -189,51 +198,65 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs 
     const int chunk_lo = (int)((long long)nchunks * part / a.csplit);
     const int chunk_hi = (int)((long long)nchunks * (part + 1) / a.csplit);
     const u32x4 *apk = reinterpret_cast<const u32x4 *>(a.apk);
+    struct AFrag { u32x4 r[RB]; };
     auto load_a = [&](int chunk, int t) {
-        const size_t tap = (size_t)t + grp;
-        return apk[((tap * a.mb_per_group + mbi) * a.cg + min(chunk, nchunks - 1)) * 64 + lane];
+        AFrag f;
+#pragma unroll
+        for (int r = 0; r < RB; ++r) {
+            const size_t tap = (size_t)t + grp[r];
+            f.r[r] = apk[((tap * a.mb_per_group + mbi[r]) * a.cg + min(chunk, nchunks - 1)) * 64 + lane];
+        }
+        return f;
     };
 
-    f32x4 acc[PBW];
+    f32x4 acc[RB][PBW];
 #pragma unroll
-    for (int b = 0; b < PBW; ++b) acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int r = 0; r < RB; ++r)
+#pragma unroll
+        for (int b = 0; b < PBW; ++b) acc[r][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    u32x4 a_ring[D];
+    AFrag a_ring[D];
     load_chunk(chunk_lo);
 #pragma unroll
     for (int d = 0; d < D; ++d) a_ring[d] = load_a(chunk_lo + d / T, d % T);
     store_chunk(lds_raw + (chunk_lo & 1) * BUF);
     __syncthreads();
 
+    // One chunk of matrix-core work.  The (tap, position block) pairs form one sequence of B
+    // fragments; each is read from LDS kAhead fragments before its RB products are issued and waits
+    // in a short register ring (a ring a whole tap deep costs 2 * NB * 4 registers and pushed the
+    // kernel over its budget once a wave held two row blocks).
     auto compute_chunk = [&](auto nb_tag, int chunk) {
         constexpr int NB = decltype(nb_tag)::value;
+        constexpr int NF = T * NB;                                 // fragments per chunk
+        constexpr int kWant = RB > 1 ? 3 : 4;                      // with two products per fragment three reads ahead cover the LDS latency
+        constexpr int kAhead = NF > kWant ? kWant : NF - 1;
+        constexpr int R = kAhead + 1;
         const unsigned char *bsrc = lds_raw + (chunk & 1) * BUF;
-        u32x4 bq[2][NB];
+        auto read_frag = [&](int s) {
+            const int t = s / NB, b = s % NB;
+            return *reinterpret_cast<const u32x4 *>(bsrc + b_off[b] + (t / KS) * RSB + (t % KS) * 16);
+        };
+        u32x4 ring[R];
 #pragma unroll
-        for (int b = 0; b < NB; ++b) bq[0][b] = *reinterpret_cast<const u32x4 *>(bsrc + b_off[b]);
+        for (int s = 0; s < kAhead; ++s) ring[s % R] = read_frag(s);
 #pragma unroll
         for (int t = 0; t < T; ++t) {
-            const u32x4 a_cur = a_ring[t % D];
+            const AFrag a_cur = a_ring[t % D];
             a_ring[t % D] = load_a(chunk + (t + D) / T, (t + D) % T);
-            if (t + 1 < T) {
 #pragma unroll
-                for (int b = 0; b < NB; ++b)
-                    bq[(t + 1) & 1][b] = *reinterpret_cast<const u32x4 *>(
-                        bsrc + b_off[b] + ((t + 1) / KS) * RSB + ((t + 1) % KS) * 16);
+            for (int b = 0; b < NB; ++b) {
+                const int s = t * NB + b;                                             // position in the fragment sequence
+                if (s + kAhead < NF) ring[(s + kAhead) % R] = read_frag(s + kAhead);
+#pragma unroll
+                for (int r = 0; r < RB; ++r)
+                    acc[r][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a_cur.r[r]),
+                                                                        __builtin_bit_cast(bf16x8, ring[s % R]),
+                                                                        acc[r][b], 0, 0, 0);
+                if (s + kAhead < NF) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read ...
+                __builtin_amdgcn_sched_group_barrier(0x008, RB, 0);                       // ... then the products of one fragment
             }
-#pragma unroll
-            for (int b = 0; b < NB; ++b)
-                acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a_cur),
-                                                                 __builtin_bit_cast(bf16x8, bq[t & 1][b]),
-                                                                 acc[b], 0, 0, 0);
-            if (t + 1 < T) {
-#pragma unroll
-                for (int b = 0; b < NB; ++b) {
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read ...
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // ... then one MFMA
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_sched_barrier(0);                                            // nothing drifts across taps
         }
     };
 
@@ -245,54 +268,56 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs 
         __syncthreads();
     }
 
-    if (!rb_valid) return;
     const size_t oplane = (size_t)a.q * a.p;
     const int out_rows = a.row_groups * a.m;
     float *out_img = a.out + (size_t)img * out_rows * oplane;
-    if (a.bias != nullptr || a.relu) {
-        // layer epilogue on the finished sums: per-row offset, then the rectifier
-        const int mrow0 = mbi * 16 + 4 * (lane >> 4);
-        f32x4 bv = {0.f, 0.f, 0.f, 0.f};
-        if (a.bias != nullptr) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-                if (mrow0 + v < a.m) bv[v] = a.bias[(size_t)grp * a.m + mrow0 + v];
+    for (int r = 0; r < RB; ++r) {
+        if (!rb_valid[r]) continue;
+        const int mrow0 = mbi[r] * 16 + 4 * (lane >> 4);
+        if (a.bias != nullptr || a.relu) {
+            // layer epilogue on the finished sums: per-row offset, then the rectifier
+            f32x4 bv = {0.f, 0.f, 0.f, 0.f};
+            if (a.bias != nullptr) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (mrow0 + v < a.m) bv[v] = a.bias[(size_t)grp[r] * a.m + mrow0 + v];
+            }
+#pragma unroll
+            for (int b = 0; b < PBW; ++b)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float x = acc[r][b][v] + bv[v];
+                    acc[r][b][v] = (a.relu && x < 0.0f) ? 0.0f : x;      // a NaN stays a NaN
+                }
         }
 #pragma unroll
-        for (int b = 0; b < PBW; ++b)
+        for (int b = 0; b < PBW; ++b) {
+            if (b >= nb_wave) continue;
+            const int pp = (first_pb + b) * 16 + (lane & 15);
+            const int y = y0 + pp / TW, x = x0 + pp % TW;
+            if (pp >= TH * TW || y >= a.q || x >= a.p) continue;
+            if constexpr (CL) {
+                float *dst = out_img + ((size_t)y * a.p + x) * out_rows + (size_t)grp[r] * a.m + mrow0;
+                if (a.csplit == 1 && (out_rows & 3) == 0 && mrow0 + 3 < a.m) {
+                    *reinterpret_cast<f32x4 *>(dst) = acc[r][b];
+                } else {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const float r = acc[b][v] + bv[v];
-                acc[b][v] = (a.relu && r < 0.0f) ? 0.0f : r;      // a NaN stays a NaN
-            }
-    }
-#pragma unroll
-    for (int b = 0; b < PBW; ++b) {
-        if (b >= nb_wave) continue;
-        const int pp = (first_pb + b) * 16 + (lane & 15);
-        const int y = y0 + pp / TW, x = x0 + pp % TW;
-        if (pp >= TH * TW || y >= a.q || x >= a.p) continue;
-        const int mrow0 = mbi * 16 + 4 * (lane >> 4);
-        if constexpr (CL) {
-            float *dst = out_img + ((size_t)y * a.p + x) * out_rows + (size_t)grp * a.m + mrow0;
-            if (a.csplit == 1 && (out_rows & 3) == 0 && mrow0 + 3 < a.m) {
-                *reinterpret_cast<f32x4 *>(dst) = acc[b];
+                    for (int v = 0; v < 4; ++v) {
+                        if (mrow0 + v >= a.m) continue;
+                        if (a.csplit == 1) dst[v] = acc[r][b][v];
+                        else unsafeAtomicAdd(dst + v, acc[r][b][v]);
+                    }
+                }
             } else {
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    if (mrow0 + v >= a.m) continue;
-                    if (a.csplit == 1) dst[v] = acc[b][v];
-                    else unsafeAtomicAdd(dst + v, acc[b][v]);
+                    const int mrow = mrow0 + v;
+                    if (mrow >= a.m) continue;
+                    float *dst = out_img + (size_t)(grp[r] * a.m + mrow) * oplane + (size_t)y * a.p + x;
+                    if (a.csplit == 1) *dst = acc[r][b][v];
+                    else unsafeAtomicAdd(dst, acc[r][b][v]);
                 }
-            }
-        } else {
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int mrow = mrow0 + v;
-                if (mrow >= a.m) continue;
-                float *dst = out_img + (size_t)(grp * a.m + mrow) * oplane + (size_t)y * a.p + x;
-                if (a.csplit == 1) *dst = acc[b][v];
-                else unsafeAtomicAdd(dst, acc[b][v]);
             }
         }
     }

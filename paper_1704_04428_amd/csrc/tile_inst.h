@@ -15,13 +15,13 @@
 namespace mcmk {
 namespace {
 
-template <int TH, int TW, int WM, int WP, int CCH = 16, bool CL = false, int KG = 1, int ST = 1>
+template <int TH, int TW, int WM, int WP, int CCH = 16, bool CL = false, int KG = 1, int ST = 1, int RB = 1>
 int launch_shape(const TileRequest &rq)
 {
     TileArgs a = rq.args;
     a.tiles_x = (a.p + TW - 1) / TW;
     a.tiles_y = (a.q + TH - 1) / TH;
-    a.row_tiles = (a.row_groups * a.mb_per_group + WM - 1) / WM;
+    a.row_tiles = (a.row_groups * a.mb_per_group + WM * RB - 1) / (WM * RB);
     const long long blocks = (long long)a.n * a.tiles_x * a.tiles_y * a.row_tiles * a.csplit;
     if (blocks < 1 || blocks >= (1LL << 31)) return 3;
 #if MCMK_BF16
@@ -32,13 +32,13 @@ int launch_shape(const TileRequest &rq)
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 1;
         if (!allowed[dev]) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&kn2row_tile_bf16<MCMK_KS, TH, TW, WM, WP, CL, ST>),
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&kn2row_tile_bf16<MCMK_KS, TH, TW, WM, WP, CL, ST, RB>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::kLdsBytes) != hipSuccess)
                 return 1;
             allowed[dev] = true;
         }
     }
-    hipLaunchKernelGGL((kn2row_tile_bf16<MCMK_KS, TH, TW, WM, WP, CL, ST>), dim3((unsigned)blocks), dim3(S::kThreads),
+    hipLaunchKernelGGL((kn2row_tile_bf16<MCMK_KS, TH, TW, WM, WP, CL, ST, RB>), dim3((unsigned)blocks), dim3(S::kThreads),
                        S::kLdsBytes, rq.stream, a);
 #else
     using S = TileShape<MCMK_KS, TH, TW, WM, WP, CCH, KG, ST>;
@@ -101,6 +101,14 @@ int MCMK_FN(const TileRequest &rq)
 #if MCMK_KS == 1
         case 7: return launch_shape<1, 224, 4, 2, 32, true>(rq);
 #endif
+#if MCMK_BF16 && MCMK_KS <= 3
+        case 8: return launch_shape<14, 14, 4, 2, 16, true, 1, 1, 2>(rq);
+        case 9: return launch_shape<14, 14, 2, 4, 16, true, 1, 1, 2>(rq);
+        case 10: return launch_shape<14, 14, 4, 1, 16, true, 1, 1, 2>(rq);
+#if MCMK_KS == 1
+        case 11: return launch_shape<1, 224, 4, 2, 32, true, 1, 1, 2>(rq);
+#endif
+#endif
         default: return 2;
         }
     }
@@ -116,6 +124,14 @@ int MCMK_FN(const TileRequest &rq)
 #endif
 #if MCMK_KS == 1
     case 7: return launch_shape<1, 224, 4, 2, 32>(rq);     // plain GEMM: deeper chunks, fewer barriers
+#endif
+#if MCMK_BF16 && MCMK_KS <= 3
+    case 8: return launch_shape<14, 14, 4, 2, 16, false, 1, 1, 2>(rq);      // two row blocks per wave
+    case 9: return launch_shape<14, 14, 2, 4, 16, false, 1, 1, 2>(rq);
+    case 10: return launch_shape<14, 14, 4, 1, 16, false, 1, 1, 2>(rq);     // a wave owns every position block
+#if MCMK_KS == 1
+    case 11: return launch_shape<1, 224, 4, 2, 32, false, 1, 1, 2>(rq);
+#endif
 #endif
     default: return 2;
     }
