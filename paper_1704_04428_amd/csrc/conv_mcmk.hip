@@ -173,7 +173,7 @@ int launch_tile(const conv_mcmk_desc *d, const Dims &dm, int ks, int shape, int 
 //     against 90 % with two or more);
 //   - each launch pays a fixed prologue / epilogue; the channel split pays a zero fill plus two
 //     device-scope atomic adds per output element.
-double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, int ks)
+double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, int ks, bool channels_last = true)
 {
     const long long tiles = (long long)d->n * ceil_div(dm.p, c.tw) * ceil_div(dm.q, c.th) * ceil_div(dm.mb, c.wm * c.rb);
     const long long wgs = tiles * c.csplit;
@@ -219,6 +219,12 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
     if (ks == 1 && c.shape != kGemmShape) us *= 1.35;
     if (d->stride == 2) us *= 1.25;
     us += bf16 ? 9.0 : 6.0;          // launch, first loads, output write (bf16 workgroups: twice the rows to write)
+    // [M][Q][P] output of a bf16 call: every workgroup writes at the same time at the end, and rows of 14
+    // floats make partial cache lines of that burst (measured 17 k cycles against 8 k with whole image rows)
+    if (bf16 && !channels_last && c.tw < 28) {
+        const double burst = (double)d->n * d->m * dm.q * dm.p * 4.0 / 25.7e6;     // relative to the layer it was measured on
+        us += 2.5 * (burst < 1.0 ? burst : 1.0);
+    }
     if (c.csplit > 1) us += 3.0 + 2.0 * (double)d->n * d->m * dm.q * dm.p * 6.25e-6;
     if (c.kg > 1) us += 1.5;                                            // the closing exchange through LDS
     return us;
@@ -226,7 +232,7 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
 
 // The candidate the cost estimate prefers for the fused kernel (or the one CONV_MCMK_TILE forces:
 // tuning aid, menu index = shape + 7 * (csplit - 1) for the seven common shapes, then
-// 14 + wide shape + 3 * (csplit - 1) for the bf16 shapes with two row blocks per wave).
+// 14 + wide shape + 4 * (csplit - 1) for the bf16 shapes with two row blocks per wave or 32-wide blocks).
 Candidate choose_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, bool epilogue = false)
 {
     Candidate best{};
@@ -250,7 +256,7 @@ Candidate choose_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_la
             // strided bf16 tiles gathered from [C][H][W] with a kernel side of 5 or more exist for the
             // 2 x 4 wave layout only (register budget of the staging gather)
             if (d->stride > 1 && d->dtype == CONV_MCMK_BF16 && !channels_last && d->k >= 5 && sh != 1) continue;
-            const double cost = (force && atoi(force) == index) ? 0.0 : tile_cost(d, dm, c, d->k);
+            const double cost = (force && atoi(force) == index) ? 0.0 : tile_cost(d, dm, c, d->k, channels_last);
             if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = c; }
         }
     return best;
@@ -283,7 +289,7 @@ double variant_cost(const conv_mcmk_desc *d, const Dims &dm, int variant)
     switch (variant) {
     case CONV_MCMK_KN2ROW:
     case CONV_MCMK_KN2COL:
-        return tile_cost(d, dm, choose_fused(d, dm, variant == CONV_MCMK_KN2COL), d->k);
+        return tile_cost(d, dm, choose_fused(d, dm, variant == CONV_MCMK_KN2COL), d->k, variant == CONV_MCMK_KN2COL);
     case CONV_MCMK_KN2ROW_2PASS: {
         const double planes = (double)d->n * d->m * d->h * d->w;
         return gemm_cost(d, d->c, (long long)d->h * d->w, dm.taps) +
@@ -396,7 +402,7 @@ int conv_mcmk_describe_plan(const conv_mcmk_desc *d, int variant, char *buf, siz
         const long long wgs = (long long)d->n * ceil_div(dm.p, c.tw) * ceil_div(dm.q, c.th) * ceil_div(dm.mb, c.wm * c.rb) * c.csplit;
         snprintf(buf, n, "%s fused %s: tile %dx%d, waves %dx%d, row blocks %d, channel groups %d, channel split %d, %lld workgroups, est %.1f us",
                  variant == CONV_MCMK_KN2COL ? "kn2col" : "kn2row", type, c.th, c.tw, c.wm, c.wp, c.rb, c.kg, c.csplit, wgs,
-                 tile_cost(d, dm, c, d->k));
+                 tile_cost(d, dm, c, d->k, variant == CONV_MCMK_KN2COL));
         break;
     }
     case CONV_MCMK_KN2ROW_2PASS:

@@ -9,11 +9,12 @@
 namespace mcmk {
 
 // Tile shapes every instantiation file provides: tile rows x columns, waves along the rows and along
-// the positions, and the number of channel groups (in-workgroup split of the contraction; fp32 only).
-// Index kGemmShape is the plain-GEMM shape (1 x 224 positions, 32-channel chunks) and exists for
-// kernel side 1 only.  Stride 2 is instantiated for the first kStridedShapes entries (the 14 x 14
-// tiles without channel groups: the strided input tile of a larger output tile would not fit the LDS).
-// rb: 16-row blocks per wave (the shapes with rb = 2 exist for bf16 operands, unit stride, kernel sides up to 3).
+// the positions, the number of channel groups (in-workgroup split of the contraction; fp32 only) and
+// the 16-row blocks per wave (2: bf16 operands, unit stride, kernel sides up to 3).
+// Index kGemmShape / kWideGemmShape are the plain-GEMM shapes (1 x 224 positions, 32-channel chunks)
+// and exist for kernel side 1 only.  Stride 2 is instantiated for the first kStridedShapes entries
+// (the 14 x 14 tiles without channel groups: the strided input tile of a larger output tile would not
+// fit the LDS).
 struct TileShapeDesc {
     int th, tw, wm, wp, kg, rb;
 };
@@ -21,15 +22,19 @@ constexpr TileShapeDesc kTileShapes[] = {
     {14, 14, 4, 2, 1, 1}, {14, 14, 2, 4, 1, 1}, {14, 14, 1, 4, 1, 1}, {16, 16, 4, 2, 1, 1}, {16, 16, 2, 4, 1, 1}, {16, 16, 1, 4, 1, 1},
     {14, 14, 1, 4, 4, 1}, {1, 224, 4, 2, 1, 1},
     {14, 14, 4, 2, 1, 2}, {14, 14, 2, 4, 1, 2}, {14, 14, 4, 1, 1, 2}, {1, 224, 4, 2, 1, 2},
+    // whole image rows of a 56-wide image: 224 positions = 14 blocks exactly, and a row of outputs is
+    // one contiguous run in memory (what the [M][Q][P] output of the bf16 kernel, whose closing
+    // write is a quarter of its time, gains from)
+    {4, 56, 4, 2, 1, 2},
 };
 constexpr int kConvShapes = 7;
 constexpr int kGemmShape = 7;
-// bf16 shapes with two row blocks per wave: convolution shapes ...
-constexpr int kWideConvShapes = 3;
-constexpr int kWideConvShape[kWideConvShapes] = {8, 9, 10};
-constexpr int kWideGemmShape = 11;     // ... and the plain-GEMM shape
 constexpr int kStridedShapes = 3;
 constexpr int kMaxKernelSide = 7;      // kernel sides 1..7 are instantiated
+// bf16 shapes with two row blocks per wave: convolution shapes ...
+constexpr int kWideConvShapes = 4;
+constexpr int kWideConvShape[kWideConvShapes] = {8, 9, 10, 12};
+constexpr int kWideGemmShape = 11;     // ... and the plain-GEMM shape
 
 struct TileRequest {
     TileArgs args;       // tiles_x, tiles_y and row_tiles are filled in by the launcher

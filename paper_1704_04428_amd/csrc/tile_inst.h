@@ -105,6 +105,7 @@ int MCMK_FN(const TileRequest &rq)
         case 8: return launch_shape<14, 14, 4, 2, 16, true, 1, 1, 2>(rq);
         case 9: return launch_shape<14, 14, 2, 4, 16, true, 1, 1, 2>(rq);
         case 10: return launch_shape<14, 14, 4, 1, 16, true, 1, 1, 2>(rq);
+        case 12: return launch_shape<4, 56, 4, 2, 16, true, 1, 1, 2>(rq);
 #if MCMK_KS == 1
         case 11: return launch_shape<1, 224, 4, 2, 32, true, 1, 1, 2>(rq);
 #endif
@@ -129,6 +130,7 @@ int MCMK_FN(const TileRequest &rq)
     case 8: return launch_shape<14, 14, 4, 2, 16, false, 1, 1, 2>(rq);      // two row blocks per wave
     case 9: return launch_shape<14, 14, 2, 4, 16, false, 1, 1, 2>(rq);
     case 10: return launch_shape<14, 14, 4, 1, 16, false, 1, 1, 2>(rq);     // a wave owns every position block
+    case 12: return launch_shape<4, 56, 4, 2, 16, false, 1, 1, 2>(rq);      // whole image rows
 #if MCMK_KS == 1
     case 11: return launch_shape<1, 224, 4, 2, 32, false, 1, 1, 2>(rq);
 #endif
