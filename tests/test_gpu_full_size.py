@@ -46,3 +46,25 @@ def test_sampled_outputs(layer, name, variant):
         fused = run_variant(B.KN2ROW, I, K, L.pad)
         scale = np.abs(fused).max()
         assert np.abs(got - fused).max() <= 2e-4 * max(scale, 1.0) * 4
+
+
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+@pytest.mark.parametrize("name,variant", [("kn2row", B.KN2ROW), ("kn2col", B.KN2COL), ("im2col", B.IM2COL)])
+@pytest.mark.parametrize("layer", list(wl.GENERALISED_LAYERS))
+def test_generalised_layers_sampled(layer, name, variant, dtype):
+    """The deep VGG-like shape with stride 2, with an even kernel side and as a 1 x 1 layer, at the
+    size bench.py times them: sampled outputs against the oracle."""
+    from gpu_util import TOL_BF16
+    L = wl.GENERALISED_LAYERS[layer]
+    announce("generalised", layer, name, dtype)
+    I, K = wl.make_input(L), wl.make_kernel(L)
+    pts = wl.sample_points(L, 2000)
+    ref, absref = oracle.mcmk_at(I, K, L.pad, pts, L.stride)
+    got = run_variant(variant, I, K, L.pad, dtype=dtype, stride=L.stride)
+    assert got.shape == (L.n, L.m, L.q, L.p)
+    sampled = got[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]]
+    assert_within_bound(sampled, ref, absref, TOL_BF16 if dtype == B.BF16 else TOL_F32, f"{name} {layer}")
+    if layer == "gen_vgg56_1x1" and variant == B.KN2ROW:
+        one = run_variant(B.KN2ROW, I, K, L.pad, dtype=dtype, one_by_one=True)
+        sampled = one[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]]
+        assert_within_bound(sampled, ref, absref, TOL_BF16 if dtype == B.BF16 else TOL_F32, f"1x1 entry {layer}")
