@@ -26,14 +26,17 @@ constexpr TileShapeDesc kTileShapes[] = {
     // one contiguous run in memory (what the [M][Q][P] output of the bf16 kernel, whose closing
     // write is a quarter of its time, gains from)
     {4, 56, 4, 2, 1, 2},
+    // small images (a single 27 x 27 or 28 x 28 image has four 14 x 14 tiles): quarter tiles, one position
+    // block per wave, so that a layer with few tiles still spreads over the chip
+    {7, 7, 1, 4, 1, 1},
 };
 constexpr int kConvShapes = 7;
 constexpr int kGemmShape = 7;
 constexpr int kStridedShapes = 3;
 constexpr int kMaxKernelSide = 7;      // kernel sides 1..7 are instantiated
-// bf16 shapes with two row blocks per wave: convolution shapes ...
-constexpr int kWideConvShapes = 4;
-constexpr int kWideConvShape[kWideConvShapes] = {8, 9, 10, 12};
+// shapes beyond the first seven (bf16 shapes with two row blocks per wave, quarter tiles): convolution shapes ...
+constexpr int kWideConvShapes = 5;
+constexpr int kWideConvShape[kWideConvShapes] = {8, 9, 10, 12, 13};
 constexpr int kWideGemmShape = 11;     // ... and the plain-GEMM shape
 
 struct TileRequest {
