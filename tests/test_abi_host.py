@@ -149,6 +149,9 @@ def test_plan_selection_for_benchmark_layers(lib, monkeypatch):
     from paper_1704_04428_amd import workloads as wl
     monkeypatch.delenv("CONV_MCMK_TILE", raising=False)
     want = {
+        # single small images: quarter tiles, so that 4 x 16 (tiles x row blocks) becomes 256 workgroups
+        "cfg3_alexnet_conv2": "tile 7x7, waves 1x4, row blocks 1, channel groups 1, channel split 1, 256 workgroups",
+        "cfg2_googlenet5x5": "tile 7x7, waves 1x4, row blocks 1, channel groups 1, channel split 1, 96 workgroups",
         "cfg4_vgg_early": "tile 14x14, waves 4x2, row blocks 1, channel groups 1, channel split 1, 256 workgroups",
         "cfg5a_vgg_deep56": "tile 14x14, waves 4x2, row blocks 1, channel groups 1, channel split 1, 512 workgroups",
         "cfg5b_vgg_deep28": "tile 14x14, waves 4x2, row blocks 1, channel groups 1, channel split 1, 256 workgroups",
@@ -174,6 +177,13 @@ def test_plan_selection_for_benchmark_layers(lib, monkeypatch):
     assert "tile 14x14" in B.conv_mcmk_describe_plan(B.desc(1, 8, 10, 10, 8, 3, 1, stride=2), B.KN2ROW)   # 16 x 16: not with a stride
     monkeypatch.setenv("CONV_MCMK_TILE", "6")
     assert "channel groups 4" in B.conv_mcmk_describe_plan(d, B.KN2ROW)
+    # bf16 operands on the deep 56 x 56 layer: two row blocks per wave; whole image rows for the [M][Q][P] output
+    L = wl.LAYERS["cfg5a_vgg_deep56"]
+    monkeypatch.delenv("CONV_MCMK_TILE")
+    db = B.desc(L.n, L.c, L.h, L.w, L.m, L.k, L.pad, 1, B.BF16)
+    assert "tile 4x56, waves 4x2, row blocks 2" in B.conv_mcmk_describe_plan(db, B.KN2ROW)
+    assert "tile 14x14, waves 4x2, row blocks 2" in B.conv_mcmk_describe_plan(db, B.KN2COL)
+    monkeypatch.setenv("CONV_MCMK_TILE", "6")
     # an entry the operand type does not have is ignored: the selector's own choice stands
     assert "channel groups 1" in B.conv_mcmk_describe_plan(B.desc(1, 8, 10, 10, 8, 3, 1, 1, B.BF16), B.KN2ROW)
 
