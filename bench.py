@@ -60,6 +60,32 @@ def auto_counts(fn, warm_ms=60.0, timed_ms=120.0):
     return max(20, int(timed_ms / ms)), max(10, int(warm_ms / ms))
 
 
+def time_in_graph(fn, launches=50, replays=40):
+    """Average time per call when `launches` calls are captured into one HIP graph and the graph is
+    replayed: what a launch-bound layer costs once the host is out of the loop."""
+    import torch
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fn()                                   # anything lazy happens outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for _ in range(launches):
+            fn()
+    for _ in range(5):
+        graph.replay()
+    torch.cuda.synchronize()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(replays):
+        graph.replay()
+    stop.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(stop) / (replays * launches)
+
+
 def bench_layer(L, variants, steps, warmup, I_dev=None, K_dev=None, dtype=0):
     import torch
     from paper_1704_04428_amd import binding as B
@@ -105,6 +131,10 @@ def bench_layer(L, variants, steps, warmup, I_dev=None, K_dev=None, dtype=0):
             "gflops": round(L.flops / (dev_ms * 1e-3) / 1e9, 1),
             "workspace_bytes": B.conv_mcmk_workspace_bytes(d, variant),
         }
+        if name == "kn2row" and dev_ms < 0.02:
+            # a launch-bound layer: the interval between launches issued from Python is part of "ms";
+            # the same calls replayed from a HIP graph show the device's share
+            out[name]["ms_in_graph"] = round(time_in_graph(run), 5)
         del plan
     return out
 

@@ -5,6 +5,8 @@
 
 #include <cstdio>
 #include <cstdlib>
+#include <cstring>
+#include <mutex>
 
 #include "aux_kernels.h"
 #include "tile_dispatch.h"
@@ -233,12 +235,48 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
 // The candidate the cost estimate prefers for the fused kernel (or the one CONV_MCMK_TILE forces:
 // tuning aid, menu index = shape + 7 * (csplit - 1) for the seven common shapes, then
 // 14 + further shape + 5 * (csplit - 1) for the bf16 shapes with two row blocks per wave or 32-wide blocks).
+Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, bool epilogue, const char *force);
+
+// The search walks the whole menu, a few microseconds of host time -- as long as the smallest layers
+// run on the GPU -- so the last few answers are remembered (per layer, layout, epilogue and override).
 Candidate choose_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, bool epilogue = false)
+{
+    const char *force = getenv("CONV_MCMK_TILE");
+    if (force && (force[0] < '0' || force[0] > '9')) force = nullptr;
+    struct Key {
+        conv_mcmk_desc d;
+        int flags, forced;
+    };
+    Key key;
+    memset(&key, 0, sizeof(key));
+    key.d = *d;
+    key.flags = (channels_last ? 1 : 0) | (epilogue ? 2 : 0);
+    key.forced = force ? atoi(force) : -1;
+    constexpr int kSlots = 32;
+    static std::mutex mu;
+    static Key keys[kSlots];
+    static Candidate vals[kSlots];
+    static int used = 0, next = 0;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        for (int i = 0; i < used; ++i)
+            if (memcmp(&keys[i], &key, sizeof(Key)) == 0) return vals[i];
+    }
+    const Candidate best = search_fused(d, dm, channels_last, epilogue, force);
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        keys[next] = key;
+        vals[next] = best;
+        next = (next + 1) % kSlots;
+        if (used < kSlots) ++used;
+    }
+    return best;
+}
+
+Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, bool epilogue, const char *force)
 {
     Candidate best{};
     double best_cost = -1.0;
-    const char *force = getenv("CONV_MCMK_TILE");
-    if (force && (force[0] < '0' || force[0] > '9')) force = nullptr;
     const int menu_len = kConvShapes + kWideConvShapes;
     for (int pass = 0, index = 0; pass < 2; ++pass)                    // common shapes, then the wide ones
     for (int cs = 1; cs <= 2; ++cs)
