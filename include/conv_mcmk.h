@@ -68,7 +68,7 @@ enum {
 enum {
     CONV_MCMK_OK              = 0,
     CONV_MCMK_ERR_NULL        = 1, /* a required pointer is NULL */
-    CONV_MCMK_ERR_SHAPE       = 2, /* a dimension or the stride < 1, pad < 0, empty output, or a tensor too large (one image of 2^29 or more input elements, 2^31 or more output elements) */
+    CONV_MCMK_ERR_SHAPE       = 2, /* a dimension or the stride < 1, pad < 0, empty output, or a tensor too large (one image of 2^29 or more input elements -- for IM2COL / IM2ROW: patch-matrix elements --, 2^31 or more output elements) */
     CONV_MCMK_ERR_UNSUPPORTED = 3, /* unknown dtype or variant, or a k / stride / dtype / channel count the variant does not implement */
     CONV_MCMK_ERR_WORKSPACE   = 4, /* workspace missing or smaller than conv_mcmk_workspace_bytes() */
     CONV_MCMK_ERR_DEVICE      = 5, /* the HIP runtime refused a launch */

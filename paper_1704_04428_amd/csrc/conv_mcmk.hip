@@ -49,10 +49,12 @@ int validate(const conv_mcmk_desc *d, int variant, Dims *out)
         if (variant == CONV_MCMK_KN2COL && d->c % (d->dtype == CONV_MCMK_BF16 ? 8 : 4) != 0) return CONV_MCMK_ERR_UNSUPPORTED;
         break;
     case CONV_MCMK_KN2ROW_2PASS:
-    case CONV_MCMK_IM2COL:
         break;
+    case CONV_MCMK_IM2COL:
     case CONV_MCMK_IM2ROW:
-        if (d->c % (d->dtype == CONV_MCMK_BF16 ? 8 : 4) != 0) return CONV_MCMK_ERR_UNSUPPORTED;
+        // the GEMM reads the patch matrix of one image through the same 32-bit byte offsets
+        if (((long long)d->c * kk + 32) * q * p >= (1LL << 29)) return CONV_MCMK_ERR_SHAPE;
+        if (variant == CONV_MCMK_IM2ROW && d->c % (d->dtype == CONV_MCMK_BF16 ? 8 : 4) != 0) return CONV_MCMK_ERR_UNSUPPORTED;
         break;
     case CONV_MCMK_DIRECT:
         if (d->dtype != CONV_MCMK_F32) return CONV_MCMK_ERR_UNSUPPORTED;

@@ -74,6 +74,13 @@ def test_check_rejects_bad_descriptors(lib):
     assert B.conv_mcmk_check(B.desc(**dict(ok, c=6)), B.KN2COL) == B.ERR_UNSUPPORTED                   # quads
     assert B.conv_mcmk_check(B.desc(**dict(ok, h=70000, w=70000)), B.DIRECT) == B.ERR_SHAPE      # >= 2^31 per image
     assert lib.conv_mcmk_check(None, B.KN2ROW) == B.ERR_NULL
+    # the patch matrix of one image must stay addressable with 32-bit byte offsets: 512 x 25 x 224 x 224 elements does not
+    big = B.desc(1, 512, 224, 224, 64, 5, 2)
+    assert B.conv_mcmk_check(big, B.KN2ROW) == B.OK
+    assert B.conv_mcmk_check(big, B.KN2ROW_2PASS) == B.OK
+    assert B.conv_mcmk_check(big, B.IM2COL) == B.ERR_SHAPE
+    assert B.conv_mcmk_check(big, B.IM2ROW) == B.ERR_SHAPE
+    assert B.conv_mcmk_select(big)[0] == B.KN2ROW
 
 
 def test_sizes(lib):
