@@ -228,3 +228,38 @@ class Plan:
     def run(self, I_dev, stream=None):
         conv_mcmk_run(self.d, self.variant, I_dev, self.kernel, self.out, self.ws, stream)
         return self.out
+
+
+def conv_mcmk(I, K, pad=0, stride=1, variant=None, bias=None, relu=False, channels_last=False, bf16=False):
+    """One-call form for device tensors: I float32 [N][C][H][W] (or [N][H][W][C] with channels_last),
+    K float32 [M][C][k][k]; returns O float32 [N][M][Q][P] (or [N][Q][P][M]).  Picks the variant with
+    conv_mcmk_select unless one is named, re-orders the kernel (in a real network: once per layer, keep
+    the Plan instead), converts the input to bfloat16 when bf16 is set, and applies the bias / rectifier
+    epilogue of the fused variants when asked.  Every step runs in the library's kernels."""
+    import torch
+    if I.dim() != 4 or K.dim() != 4 or K.shape[2] != K.shape[3]:
+        raise ValueError("I must be 4-D and K [M][C][k][k]")
+    n = I.shape[0]
+    c, h, w = (I.shape[3], I.shape[1], I.shape[2]) if channels_last else (I.shape[1], I.shape[2], I.shape[3])
+    m, kc, k, _ = K.shape
+    if kc != c:
+        raise ValueError("input and kernel disagree on the number of channels")
+    d = desc(n, c, h, w, m, k, pad, stride, BF16 if bf16 else F32)
+    epilogue = bias is not None or relu
+    if variant is None:
+        variant = (KN2COL if channels_last else KN2ROW) if epilogue else conv_mcmk_select(d, channels_last)[0]
+    if (variant in CHANNELS_LAST) != bool(channels_last):
+        raise ValueError("the variant does not take this layout")
+    if epilogue and variant not in (KN2ROW, KN2COL):
+        raise ValueError("the bias / rectifier epilogue belongs to the fused variants")
+    I = I.contiguous()
+    plan = Plan(d, variant, K.contiguous())
+    if bf16:
+        I_bf = torch.empty(I.shape, dtype=torch.bfloat16, device=I.device)
+        conv_mcmk_cvt_f32_bf16(I, I_bf)
+        I = I_bf
+    if epilogue:
+        fn = conv_mcmk_kn2col_bias_relu if variant == KN2COL else conv_mcmk_kn2row_bias_relu
+        fn(d, I, plan.kernel, bias.contiguous() if bias is not None else None, relu, plan.out)
+        return plan.out
+    return plan.run(I)

@@ -221,3 +221,32 @@ def test_selected_variant_is_correct_and_near_the_fastest(case):
             times[variant] = timed(B.Plan(d, variant, K_dev))
     announce("select times (ms)", {v: round(t, 4) for v, t in times.items()}, "chosen", chosen)
     assert times[chosen] <= 1.5 * min(times.values()), (times, chosen)
+
+
+# ------------------------------------------------------------------ the one-call form of the binding
+
+def test_one_call_form():
+    import torch
+    case = (2, 24, 19, 21, 20, 3, 1, 1)
+    I, K = _inputs(case, 3700)
+    bias = wl.uniform(3701, case[4], -0.5, 0.5)
+    ref, absref = oracle.mcmk(I, K, 1)
+    ref2, absref2 = oracle.mcmk(I, K, 1, 2)
+    I_dev, K_dev = torch.from_numpy(I).cuda(), torch.from_numpy(K).cuda()
+    announce("one-call")
+    got = B.conv_mcmk(I_dev, K_dev, pad=1).cpu().numpy()
+    assert_within_bound(got, ref, absref, TOL_F32, "auto")
+    for name, variant in ALL:
+        cl = variant in B.CHANNELS_LAST
+        x = I_dev.permute(0, 2, 3, 1).contiguous() if cl else I_dev
+        got = B.conv_mcmk(x, K_dev, pad=1, stride=2, variant=variant, channels_last=cl)
+        got = (got.permute(0, 3, 1, 2) if cl else got).cpu().numpy()
+        assert_within_bound(got, ref2, absref2, TOL_F32, f"one-call {name} stride 2")
+    got = B.conv_mcmk(I_dev, K_dev, pad=1, bias=torch.from_numpy(bias).cuda(), relu=True).cpu().numpy()
+    assert_within_bound(got, oracle.bias_relu(ref, bias, True), absref + np.abs(bias).reshape(1, -1, 1, 1), TOL_F32, "epilogue")
+    got = B.conv_mcmk(I_dev, K_dev, pad=1, bf16=True).cpu().numpy()
+    assert_within_bound(got, ref, absref, TOL_BF16, "bf16")
+    with pytest.raises(ValueError):
+        B.conv_mcmk(I_dev, K_dev, pad=1, variant=B.KN2COL)                      # layout and variant disagree
+    with pytest.raises(ValueError):
+        B.conv_mcmk(I_dev, K_dev, pad=1, variant=B.IM2COL, relu=True)
