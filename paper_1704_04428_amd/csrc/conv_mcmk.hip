@@ -218,6 +218,9 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
         pipe_use *= (reuse_a < 1.1 ? reuse_a : 1.1) * (reuse_b < 1.0 ? reuse_b : 1.0);
     }
     double us = (double)per_cu * simd_load * steps * 0.0139 / pipe_use;
+    // bf16: a wave has one chunk of staging loads in flight, so a workgroup cannot finish a chunk faster than
+    // a round trip to memory (about 0.8 us when every CU asks at once), however little matrix work it holds
+    if (bf16 && us < per_cu * chunks * 0.8) us = per_cu * chunks * 0.8;
     // staging-heavy cases: a 1 x 1 kernel uses every staged value once instead of k*k times, a
     // strided tile stages four input values per output position (both measured)
     if (ks == 1 && c.shape != kGemmShape) us *= 1.35;
@@ -288,10 +291,10 @@ Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_la
             // two row blocks per wave: bf16 operands, unit stride
             if (c.rb > 1 && (d->dtype != CONV_MCMK_BF16 || d->stride > 1 || d->k > 3)) continue;
             if (c.th == 7 && (d->stride > 1 || d->k > 5)) continue;    // quarter tiles: unit stride, kernel sides up to 5
-            // channel groups exist for fp32 and kernel sides up to 3 only (four groups of double-buffered
-            // 5x5 halo tiles would not fit the 160 KB of LDS) and are an alternative to, not a partner
-            // of, the two-way split
-            if (c.kg > 1 && (d->dtype == CONV_MCMK_BF16 || cs > 1 || d->k > 3)) continue;
+            // channel groups exist for kernel sides up to 3 only (four groups of double-buffered 5x5 halo
+            // tiles would not fit the 160 KB of LDS), for bf16 with channels-last input only, and are an
+            // alternative to, not a partner of, the two-way split
+            if (c.kg > 1 && (cs > 1 || d->k > 3 || (d->dtype == CONV_MCMK_BF16 && !channels_last))) continue;
             if (d->stride > 1 && sh >= kStridedShapes) continue;       // strided input tiles: 14 x 14 outputs only
             if (epilogue && cs > 1) continue;                          // partial sums cannot take the epilogue
             // strided bf16 tiles gathered from [C][H][W] with a kernel side of 5 or more exist for the

@@ -30,7 +30,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef short i16x2 __attribute__((ext_vector_type(2)));
 
-template <int KS, int TH, int TW, int WM, int WP, int ST = 1>
+template <int KS, int TH, int TW, int WM, int WP, int ST = 1, int KG = 1>
 struct TileShapeBf16 {
     static constexpr int kCC = 32;                       // channels per chunk
     static constexpr int kThreads = 64 * WM * WP;
@@ -38,16 +38,17 @@ struct TileShapeBf16 {
     static constexpr int kWT = (TW - 1) * ST + KS;
     static constexpr int kPos = kHT * kWT;
     // bytes between tile rows: >= 16 per column; for unit stride == 16*TW (mod 256), see above; the
-    // strided tile is four times the size and is packed tight to stay inside the LDS
+    // strided tile is four times the size, and with channel groups there are KG pairs of buffers: both
+    // are packed tight to stay inside the LDS (bank conflicts matter little where they are used)
     static constexpr int kRowBytes =
-        ST == 1 ? ((kWT * 16 - (TW * 16) % 256 + 255) / 256) * 256 + (TW * 16) % 256 : kWT * 16;
+        (ST == 1 && KG == 1) ? ((kWT * 16 - (TW * 16) % 256 + 255) / 256) * 256 + (TW * 16) % 256 : kWT * 16;
     static constexpr int kPlaneBytes = ((kHT * kRowBytes + 255) / 256) * 256;   // one channel octet
     static constexpr int kBufBytes = 4 * kPlaneBytes;
     static constexpr int kNPB = (TH * TW + 15) / 16;
     static constexpr int kPBW = (kNPB + WP - 1) / WP;
     static constexpr int kItems = 4 * kPos;              // (position, channel octet) pairs per chunk
     static constexpr int kSlots = (kItems + kThreads - 1) / kThreads;
-    static constexpr size_t kLdsBytes = 2 * (size_t)kBufBytes;
+    static constexpr size_t kLdsBytes = 2 * (size_t)KG * kBufBytes;
 };
 
 // TileArgs is shared with the fp32 kernel; `in` and `apk` point at bf16 data, cg counts 32-channel groups.
@@ -59,24 +60,35 @@ struct TileShapeBf16 {
 //     bf16 product is so short (16 cycles) that one read per product would keep the LDS, not the matrix
 //     pipe, busy: four SIMDs x one 1 KB read per 16 cycles is the whole LDS bandwidth of a compute unit.
 //     The workgroup covers 16*WM*RB rows.
-template <int KS, int TH, int TW, int WM, int WP, bool CL = false, int ST = 1, int RB = 1>
-__global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs a)
+// KG: channel groups inside the workgroup, as in kn2row_tile_f32: group g (WM x WP waves, its own pair of LDS
+//     buffers) takes chunks g, g+KG, ...; the partial sums meet in LDS at the end in a fixed order.  For
+//     the short bf16 chunks the gain is not matrix work but latency: a wave can keep only one chunk of
+//     staging loads in flight (its loads complete in order, and it also has to wait for its A
+//     fragments), so a small-image layer with many channels is a chain of memory round trips, and KG
+//     groups walk KG such chains side by side.
+template <int KS, int TH, int TW, int WM, int WP, bool CL = false, int ST = 1, int RB = 1, int KG = 1>
+__global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_bf16(const TileArgs a)
 {
-    using S = TileShapeBf16<KS, TH, TW, WM, WP, ST>;
+    using S = TileShapeBf16<KS, TH, TW, WM, WP, ST, KG>;
     constexpr int CC = S::kCC, NT = S::kThreads, WT = S::kWT, POS = S::kPos, RSB = S::kRowBytes, PLB = S::kPlaneBytes;
-    static_assert(RSB >= WT * 16 && (ST != 1 || (RSB - TW * 16) % 256 == 0), "row stride rule");
+    static_assert(RSB >= WT * 16 && (ST != 1 || KG != 1 || (RSB - TW * 16) % 256 == 0), "row stride rule");
     constexpr int PBW = S::kPBW, NPB = S::kNPB, SLOTS = S::kSlots, BUF = S::kBufBytes;
     constexpr int REM = NPB % WP;
     constexpr bool kRagged = REM != 0;
     static_assert(NPB >= WP, "every wave needs at least one position block");
 
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_all[];
 
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = threadIdx.x & 63;
+    const int wave_all = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int kg = KG == 1 ? 0 : wave_all / (WM * WP);            // channel group of this wave
+    // waves go to SIMD (wave index % 4); rotating the group's waves by kg along the position axis
+    // gives each SIMD one wave of every position share
+    const int wave = (wave_all % (WM * WP) + kg * WM) % (WM * WP);
+    const int tid = wave * 64 + lane;                             // thread index inside the group
     const int wm = wave % WM;
     const int wp = wave / WM;
+    unsigned char *const lds_raw = lds_all + (size_t)kg * 2 * BUF;    // this group's two buffers
 
     // ---- which tile (XCD-aware order, see kn2row_tile_f32)
     int bid = blockIdx.x;
@@ -216,23 +228,26 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs 
         for (int b = 0; b < PBW; ++b) acc[r][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     AFrag a_ring[D];
-    load_chunk(chunk_lo);
+    const int chunk_first = chunk_lo + kg;                        // this group's chunks: first, +KG, +2KG, ...
+    load_chunk(chunk_first);
 #pragma unroll
-    for (int d = 0; d < D; ++d) a_ring[d] = load_a(chunk_lo + d / T, d % T);
-    store_chunk(lds_raw + (chunk_lo & 1) * BUF);
+    for (int d = 0; d < D; ++d) a_ring[d] = load_a(chunk_first + KG * (d / T), d % T);
+    store_chunk(lds_raw);
     __syncthreads();
 
     // One chunk of matrix-core work.  The (tap, position block) pairs form one sequence of B
     // fragments; each is read from LDS kAhead fragments before its RB products are issued and waits
     // in a short register ring (a ring a whole tap deep costs 2 * NB * 4 registers and pushed the
     // kernel over its budget once a wave held two row blocks).
-    auto compute_chunk = [&](auto nb_tag, int chunk) {
+    auto compute_chunk = [&](auto nb_tag, int chunk, int step) {
         constexpr int NB = decltype(nb_tag)::value;
         constexpr int NF = T * NB;                                 // fragments per chunk
-        constexpr int kWant = RB > 1 ? 3 : 4;                      // with two products per fragment three reads ahead cover the LDS latency
+        // with two products per fragment three reads ahead cover the LDS latency; sixteen-wave workgroups (channel
+        // groups) have 128 registers per lane and four waves per SIMD to cover it instead
+        constexpr int kWant = KG > 1 ? 2 : RB > 1 ? 3 : 4;
         constexpr int kAhead = NF > kWant ? kWant : NF - 1;
         constexpr int R = kAhead + 1;
-        const unsigned char *bsrc = lds_raw + (chunk & 1) * BUF;
+        const unsigned char *bsrc = lds_raw + (step & 1) * BUF;
         auto read_frag = [&](int s) {
             const int t = s / NB, b = s % NB;
             return *reinterpret_cast<const u32x4 *>(bsrc + b_off[b] + (t / KS) * RSB + (t % KS) * 16);
@@ -243,7 +258,7 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs 
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             const AFrag a_cur = a_ring[t % D];
-            a_ring[t % D] = load_a(chunk + (t + D) / T, (t + D) % T);
+            a_ring[t % D] = load_a(chunk + KG * ((t + D) / T), (t + D) % T);
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 const int s = t * NB + b;                                             // position in the fragment sequence
@@ -260,12 +275,40 @@ __global__ __launch_bounds__(64 * WM * WP) void kn2row_tile_bf16(const TileArgs 
         }
     };
 
-    for (int chunk = chunk_lo; chunk < chunk_hi; ++chunk) {
-        load_chunk(chunk + 1);
-        if (kRagged && nb_wave != PBW) compute_chunk(std::integral_constant<int, kRagged ? PBW - 1 : PBW>{}, chunk);
-        else compute_chunk(std::integral_constant<int, PBW>{}, chunk);
-        store_chunk(lds_raw + ((chunk + 1) & 1) * BUF);
+    const int nsteps = (chunk_hi - chunk_lo + KG - 1) / KG;       // the same for every group: barriers match
+    for (int step = 0; step < nsteps; ++step) {
+        const int chunk = chunk_first + step * KG;
+        load_chunk(chunk + KG);
+        if (KG == 1 || chunk < chunk_hi) {                        // wave-uniform
+            if (kRagged && nb_wave != PBW) compute_chunk(std::integral_constant<int, kRagged ? PBW - 1 : PBW>{}, chunk, step);
+            else compute_chunk(std::integral_constant<int, PBW>{}, chunk, step);
+        }
+        store_chunk(lds_raw + ((step + 1) & 1) * BUF);
         __syncthreads();
+    }
+
+    // ---- add the channel groups' partial sums: groups 1.. park theirs in LDS (the staging buffers
+    // are free now), group 0 adds them in group order and goes on to write the tile
+    if constexpr (KG > 1) {
+        static_assert((size_t)(KG - 1) * WM * WP * RB * PBW * 1024 <= 2 * (size_t)KG * BUF, "parked sums must fit the staging buffers");
+        f32x4 *park = reinterpret_cast<f32x4 *>(lds_all);
+        const int slot = (wm + WM * wp) * RB * PBW;               // same (wm, wp) in every group
+        if (kg > 0) {
+#pragma unroll
+            for (int r = 0; r < RB; ++r)
+#pragma unroll
+                for (int b = 0; b < PBW; ++b)
+                    park[(((kg - 1) * WM * WP * RB * PBW) + slot + r * PBW + b) * 64 + lane] = acc[r][b];
+        }
+        __syncthreads();
+        if (kg > 0) return;
+#pragma unroll
+        for (int g = 1; g < KG; ++g)
+#pragma unroll
+            for (int r = 0; r < RB; ++r)
+#pragma unroll
+                for (int b = 0; b < PBW; ++b)
+                    acc[r][b] += park[(((g - 1) * WM * WP * RB * PBW) + slot + r * PBW + b) * 64 + lane];
     }
 
     const size_t oplane = (size_t)a.q * a.p;

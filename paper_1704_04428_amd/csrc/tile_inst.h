@@ -25,21 +25,23 @@ int launch_shape(const TileRequest &rq)
     const long long blocks = (long long)a.n * a.tiles_x * a.tiles_y * a.row_tiles * a.csplit;
     if (blocks < 1 || blocks >= (1LL << 31)) return 3;
 #if MCMK_BF16
-    using S = TileShapeBf16<MCMK_KS, TH, TW, WM, WP, ST>;
-    if (S::kLdsBytes > 65536) {
+    using S = TileShapeBf16<MCMK_KS, TH, TW, WM, WP, ST, KG>;
+    constexpr size_t kLds = S::kLdsBytes;            // every channel group has its own pair of buffers
+    static_assert(kLds <= 160 * 1024, "the tile does not fit the LDS of a compute unit");
+    if (kLds > 65536) {
         // more than 64 KiB of dynamic LDS has to be allowed per kernel, once per device
         static bool allowed[64] = {};
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 1;
         if (!allowed[dev]) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&kn2row_tile_bf16<MCMK_KS, TH, TW, WM, WP, CL, ST, RB>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::kLdsBytes) != hipSuccess)
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&kn2row_tile_bf16<MCMK_KS, TH, TW, WM, WP, CL, ST, RB, KG>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds) != hipSuccess)
                 return 1;
             allowed[dev] = true;
         }
     }
-    hipLaunchKernelGGL((kn2row_tile_bf16<MCMK_KS, TH, TW, WM, WP, CL, ST, RB>), dim3((unsigned)blocks), dim3(S::kThreads),
-                       S::kLdsBytes, rq.stream, a);
+    hipLaunchKernelGGL((kn2row_tile_bf16<MCMK_KS, TH, TW, WM, WP, CL, ST, RB, KG>), dim3((unsigned)blocks), dim3(S::kThreads * KG),
+                       kLds, rq.stream, a);
 #else
     using S = TileShape<MCMK_KS, TH, TW, WM, WP, CCH, KG, ST>;
     if (S::kLdsBytes > 65536) {
@@ -95,7 +97,7 @@ int MCMK_FN(const TileRequest &rq)
         case 3: return launch_shape<16, 16, 4, 2, 16, true>(rq);
         case 4: return launch_shape<16, 16, 2, 4, 16, true>(rq);
         case 5: return launch_shape<16, 16, 1, 4, 16, true>(rq);
-#if !MCMK_BF16 && MCMK_KS <= 3
+#if MCMK_KS <= 3
         case 6: return launch_shape<14, 14, 1, 4, 16, true, 4>(rq);
 #endif
 #if MCMK_KS == 1
@@ -124,7 +126,9 @@ int MCMK_FN(const TileRequest &rq)
     case 4: return launch_shape<16, 16, 2, 4>(rq);
     case 5: return launch_shape<16, 16, 1, 4>(rq);
 #if !MCMK_BF16 && MCMK_KS <= 3
-    case 6: return launch_shape<14, 14, 1, 4, 16, false, 4>(rq);   // four channel groups in the workgroup
+    // four channel groups in the workgroup (bf16: channels last only -- with [C][H][W] input the 2-byte
+    // staging gathers, not the chain of round trips the groups shorten, are what such layers wait for)
+    case 6: return launch_shape<14, 14, 1, 4, 16, false, 4>(rq);
 #endif
 #if MCMK_KS == 1
     case 7: return launch_shape<1, 224, 4, 2, 32>(rq);     // plain GEMM: deeper chunks, fewer barriers
