@@ -27,6 +27,8 @@
  *   - dtype CONV_MCMK_F32: I, packed kernel and O are float.
  *     dtype CONV_MCMK_BF16: I and the packed kernel are bfloat16 (the upper 16
  *     bits of a float, rounded to nearest even), accumulation and O are float.
+ *     (The bf16 variants that read I[N][C][H][W] need H*W >= 2 -- IM2COL: Q*P >= 2 --
+ *     and refuse a single-element plane with CONV_MCMK_ERR_UNSUPPORTED.)
  */
 #ifndef CONV_MCMK_H
 #define CONV_MCMK_H

@@ -40,6 +40,12 @@ int validate(const conv_mcmk_desc *d, int variant, Dims *out)
         kk * d->m * d->h * d->w >= lim * 4 || q >= 65536 * 16 || p >= 65536 * 16)
         return CONV_MCMK_ERR_SHAPE;
     if (d->dtype != CONV_MCMK_F32 && d->dtype != CONV_MCMK_BF16) return CONV_MCMK_ERR_UNSUPPORTED;
+    // bf16 input in [C][H][W] order is staged two positions at a time: a plane of a single element
+    // (for im2col: a patch matrix with a single column) is not taken
+    if (d->dtype == CONV_MCMK_BF16 &&
+        (((variant == CONV_MCMK_KN2ROW || variant == CONV_MCMK_KN2ROW_2PASS) && (long long)d->h * d->w < 2) ||
+         (variant == CONV_MCMK_IM2COL && q * p < 2)))
+        return CONV_MCMK_ERR_UNSUPPORTED;
     switch (variant) {
     case CONV_MCMK_KN2ROW:
     case CONV_MCMK_KN2COL:
@@ -292,9 +298,9 @@ Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_la
             if (c.rb > 1 && (d->dtype != CONV_MCMK_BF16 || d->stride > 1 || d->k > 3)) continue;
             if (c.th == 7 && (d->stride > 1 || d->k > 5)) continue;    // quarter tiles: unit stride, kernel sides up to 5
             // channel groups exist for kernel sides up to 3 only (four groups of double-buffered 5x5 halo
-            // tiles would not fit the 160 KB of LDS), for bf16 with channels-last input only, and are an
-            // alternative to, not a partner of, the two-way split
-            if (c.kg > 1 && (cs > 1 || d->k > 3 || (d->dtype == CONV_MCMK_BF16 && !channels_last))) continue;
+            // tiles would not fit the 160 KB of LDS) and are an alternative to, not a partner of, the
+            // two-way split
+            if (c.kg > 1 && (cs > 1 || d->k > 3)) continue;
             if (d->stride > 1 && sh >= kStridedShapes) continue;       // strided input tiles: 14 x 14 outputs only
             if (epilogue && cs > 1) continue;                          // partial sums cannot take the epilogue
             // strided bf16 tiles gathered from [C][H][W] with a kernel side of 5 or more exist for the

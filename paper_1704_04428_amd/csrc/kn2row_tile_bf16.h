@@ -116,30 +116,64 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_bf16(const Tile
         mbi[r] = rb % a.mb_per_group;
     }
 
-    // ---- staging plan: item e = tid + s*NT is (channel octet e / POS, position e % POS).
-    // 2-byte loads through a range-checked buffer descriptor: outside the image (offset 2 GiB) and
-    // beyond channel C the hardware returns 0.
+    // ---- staging plan for [C][H][W] input.  The tile wants 8 channels of one position side by side,
+    // memory has the positions of one channel side by side: an item is (channel octet, tile row, PAIR
+    // of columns), fetched with eight 4-byte loads (one per channel, two positions each) and turned
+    // into the two 16-byte LDS entries by eight byte permutes.  Half the loads of a 2-byte gather per
+    // element, and the texture addresser, which takes a wave's gather a few lanes at a time, is
+    // what this path waits for.  The loads go through a range-checked buffer descriptor: an
+    // offset of 2 GiB (pair outside the image) and channels beyond C return 0.  A pair with only
+    // one element inside the image (left / right border) reads a dword that lies wholly inside the
+    // plane -- at the element, or one element earlier when it is the last of its plane -- and the
+    // permute selector of the slot picks the half that holds it (or zeros).  Needs H*W >= 2.
+    // With channels-last input (CL) an item is simply (channel octet, position): one 16-byte load.
+    constexpr int HT = S::kHT;
+    constexpr int PW = (WT + 1) / 2;                       // column pairs per tile row
+    constexpr int PITEMS = 4 * HT * PW;
+    constexpr int PSLOTS = (PITEMS + NT - 1) / NT;
+    constexpr uint32_t kSelLo = 0x05040100u, kSelHi = 0x07060302u, kSelZero = 0x0c0c0c0cu;
     const size_t plane = (size_t)a.h * a.w;
     const uint16_t *in_img = reinterpret_cast<const uint16_t *>(a.in) + (size_t)img * a.c * plane;
     const __amdgpu_buffer_rsrc_t in_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint16_t *>(in_img), 0, (int)((size_t)a.c * plane * sizeof(uint16_t)), 0x00020000);
     const uint32_t plane_bytes = (uint32_t)(plane * sizeof(uint16_t));
     const uint32_t chunk_bytes = (uint32_t)CC * plane_bytes;
-    uint32_t g_off[SLOTS];   // byte offset of (first channel of the octet, position) in chunk 0, or 2 GiB
-    int l_off[SLOTS];        // byte offset inside an LDS buffer, or -1 when the slot is unused
+    constexpr int NSEL = CL ? 1 : PSLOTS;
+    uint32_t g_off[NSEL];    // byte offset of the slot's dword in the first channel of its octet, chunk 0, or 2 GiB
+    uint32_t sel_a[NSEL];    // permute selector for the first column of the pair, ...
+    uint32_t sel_b[NSEL];    // ... and for the second
+    int l_off[NSEL];         // byte offset of the first column inside an LDS buffer, or -1 when the slot is unused
+    bool two_cols[NSEL];     // the tile row has the pair's second column
+    if constexpr (!CL) {
 #pragma unroll
-    for (int s = 0; s < SLOTS; ++s) {
-        const int e = tid + s * NT;
-        const int oct = e / POS, pos = e % POS;
-        const int r = pos / WT, col = pos % WT;
-        const int gy = iy0 + r, gx = ix0 + col;
-        const bool used = e < S::kItems;
-        const bool inside = used && gy >= 0 && gy < a.h && gx >= 0 && gx < a.w;
-        g_off[s] = inside ? (uint32_t)(oct * 8) * plane_bytes + (uint32_t)((size_t)gy * a.w + gx) * 2u : 0x80000000u;
-        l_off[s] = used ? oct * PLB + r * RSB + col * 16 : -1;
+        for (int s = 0; s < PSLOTS; ++s) {
+            const int e = tid + s * NT;
+            const int oct = e / (HT * PW), rem = e % (HT * PW);
+            const int r = rem / PW, col = 2 * (rem % PW);
+            const int gy = iy0 + r, gx = ix0 + col;
+            const bool used = e < PITEMS;
+            const bool in_row = used && gy >= 0 && gy < a.h;
+            const bool v0 = in_row && gx >= 0 && gx < a.w;
+            const bool v1 = in_row && col + 1 < WT && gx + 1 >= 0 && gx + 1 < a.w;
+            long long p = (long long)gy * a.w + gx;         // element index of the dword's lower half inside a plane
+            uint32_t sa = kSelZero, sb = kSelZero;
+            if (v0 && v1) {
+                sa = kSelLo;  sb = kSelHi;
+            } else if (v0) {
+                if (p + 1 < (long long)plane) sa = kSelLo; else { p -= 1;  sa = kSelHi; }
+            } else if (v1) {
+                p += 1;
+                if (p + 1 < (long long)plane) sb = kSelLo; else { p -= 1;  sb = kSelHi; }
+            }
+            g_off[s] = (v0 || v1) ? (uint32_t)(oct * 8) * plane_bytes + (uint32_t)p * 2u : 0x80000000u;
+            sel_a[s] = sa;
+            sel_b[s] = sb;
+            l_off[s] = used ? oct * PLB + r * RSB + col * 16 : -1;
+            two_cols[s] = col + 1 < WT;
+        }
     }
 
-    i16x2 stage[SLOTS][4];         // channels first: eight 2-byte gathers per item, two to a register
+    uint32_t stage[NSEL][8];       // channels first: eight 4-byte loads per item (two positions of one channel each)
     u32x4 stage_cl[SLOTS];         // channels last: one 16-byte load per item
     auto load_chunk = [&](int chunk) {
         if constexpr (CL) {
@@ -159,10 +193,10 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_bf16(const Tile
             }
         } else {
 #pragma unroll
-            for (int s = 0; s < SLOTS; ++s)
+            for (int s = 0; s < PSLOTS; ++s)
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
-                    stage[s][e / 2][e % 2] = (short)__builtin_amdgcn_raw_buffer_load_b16(
+                    stage[s][e] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(
                         in_rsrc, (int)(g_off[s] + (uint32_t)e * plane_bytes + (uint32_t)min(chunk, a.cg) * chunk_bytes), 0, 0);
         }
     };
@@ -179,11 +213,18 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_bf16(const Tile
             }
         } else {
 #pragma unroll
-            for (int s = 0; s < SLOTS; ++s) {
-                u32x4 v;
+            for (int s = 0; s < PSLOTS; ++s) {
+                u32x4 first, second;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = __builtin_bit_cast(uint32_t, stage[s][e]);
-                if (l_off[s] >= 0) *reinterpret_cast<u32x4 *>(buf + l_off[s]) = v;
+                for (int e = 0; e < 4; ++e) {
+                    // channels 2e and 2e+1 of the octet side by side, for the pair's first and second column
+                    first[e] = __builtin_amdgcn_perm(stage[s][2 * e + 1], stage[s][2 * e], sel_a[s]);
+                    second[e] = __builtin_amdgcn_perm(stage[s][2 * e + 1], stage[s][2 * e], sel_b[s]);
+                }
+                if (l_off[s] >= 0) {
+                    *reinterpret_cast<u32x4 *>(buf + l_off[s]) = first;
+                    if (two_cols[s]) *reinterpret_cast<u32x4 *>(buf + l_off[s] + 16) = second;
+                }
             }
         }
     };

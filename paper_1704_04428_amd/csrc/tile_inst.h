@@ -125,10 +125,8 @@ int MCMK_FN(const TileRequest &rq)
     case 3: return launch_shape<16, 16, 4, 2>(rq);
     case 4: return launch_shape<16, 16, 2, 4>(rq);
     case 5: return launch_shape<16, 16, 1, 4>(rq);
-#if !MCMK_BF16 && MCMK_KS <= 3
-    // four channel groups in the workgroup (bf16: channels last only -- with [C][H][W] input the 2-byte
-    // staging gathers, not the chain of round trips the groups shorten, are what such layers wait for)
-    case 6: return launch_shape<14, 14, 1, 4, 16, false, 4>(rq);
+#if MCMK_KS <= 3
+    case 6: return launch_shape<14, 14, 1, 4, 16, false, 4>(rq);   // four channel groups in the workgroup
 #endif
 #if MCMK_KS == 1
     case 7: return launch_shape<1, 224, 4, 2, 32>(rq);     // plain GEMM: deeper chunks, fewer barriers

@@ -74,6 +74,14 @@ def test_check_rejects_bad_descriptors(lib):
     assert B.conv_mcmk_check(B.desc(**dict(ok, c=6)), B.KN2COL) == B.ERR_UNSUPPORTED                   # quads
     assert B.conv_mcmk_check(B.desc(**dict(ok, h=70000, w=70000)), B.DIRECT) == B.ERR_SHAPE      # >= 2^31 per image
     assert lib.conv_mcmk_check(None, B.KN2ROW) == B.ERR_NULL
+    # bf16 [C][H][W] input is staged two positions at a time: a one-element plane is refused
+    one = dict(n=1, c=8, h=1, w=1, m=4, k=1, pad=0)
+    assert B.conv_mcmk_check(B.desc(**one), B.KN2ROW) == B.OK
+    assert B.conv_mcmk_check(B.desc(**one, dtype=B.BF16), B.KN2ROW) == B.ERR_UNSUPPORTED
+    assert B.conv_mcmk_check(B.desc(**one, dtype=B.BF16), B.KN2ROW_2PASS) == B.ERR_UNSUPPORTED
+    assert B.conv_mcmk_check(B.desc(**one, dtype=B.BF16), B.IM2COL) == B.ERR_UNSUPPORTED
+    assert B.conv_mcmk_check(B.desc(**one, dtype=B.BF16), B.KN2COL) == B.OK
+    assert B.conv_mcmk_check(B.desc(**dict(one, w=2), dtype=B.BF16), B.KN2ROW) == B.OK
     # the patch matrix of one image must stay addressable with 32-bit byte offsets: 512 x 25 x 224 x 224 elements does not
     big = B.desc(1, 512, 224, 224, 64, 5, 2)
     assert B.conv_mcmk_check(big, B.KN2ROW) == B.OK
@@ -191,8 +199,9 @@ def test_plan_selection_for_benchmark_layers(lib, monkeypatch):
     assert "tile 4x56, waves 4x2, row blocks 2" in B.conv_mcmk_describe_plan(db, B.KN2ROW)
     assert "tile 14x14, waves 4x2, row blocks 2" in B.conv_mcmk_describe_plan(db, B.KN2COL)
     monkeypatch.setenv("CONV_MCMK_TILE", "6")
-    # an entry the operand type does not have is ignored: the selector's own choice stands
-    assert "channel groups 1" in B.conv_mcmk_describe_plan(B.desc(1, 8, 10, 10, 8, 3, 1, 1, B.BF16), B.KN2ROW)
+    assert "channel groups 4" in B.conv_mcmk_describe_plan(B.desc(1, 8, 10, 10, 8, 3, 1, 1, B.BF16), B.KN2ROW)
+    # an entry the kernel side does not have is ignored: the selector's own choice stands
+    assert "channel groups 1" in B.conv_mcmk_describe_plan(B.desc(1, 8, 10, 10, 8, 5, 2), B.KN2ROW)
 
 
 def test_kernel_register_budget():

@@ -33,7 +33,10 @@ CASES = [
     (3, 70, 29, 43, 70, 3, 1),
     (1, 4, 9, 9, 5, 3, 0),
     (1, 4, 6, 7, 5, 3, 2),
-    (1, 1, 1, 1, 1, 1, 0),
+    (1, 1, 1, 2, 1, 1, 0),         # the smallest plane the [C][H][W] bf16 path takes: two elements
+    (1, 3, 2, 1, 2, 1, 0),         # one column: every pair of columns has a single valid element
+    (1, 5, 1, 7, 3, 3, 1),         # one row, odd width
+    (2, 9, 5, 3, 4, 2, 1),         # even kernel side: odd tile width, the last pair has one column
     (2, 64, 28, 28, 48, 5, 2),
 ]
 
@@ -57,6 +60,15 @@ def test_bf16_matches_oracle(name, variant, case):
     Ir, Kr = steps.round_to_bf16(I), steps.round_to_bf16(K)
     ref_r, abs_r = oracle.mcmk(Ir, Kr, pad)
     assert_within_bound(got, ref_r, abs_r, TOL_F32, f"bf16 {name} {case} vs rounded inputs")
+
+
+def test_bf16_single_element_plane_is_refused():
+    """[C][H][W] bf16 input is staged two positions at a time; H*W = 1 is left to fp32 or channels last."""
+    with pytest.raises(B.ConvMcmkError) as e:
+        run_variant(B.KN2ROW, np.ones((1, 8, 1, 1), np.float32), np.ones((4, 8, 1, 1), np.float32), 0, dtype=B.BF16)
+    assert e.value.code == B.ERR_UNSUPPORTED
+    got = run_variant(B.KN2COL, np.ones((1, 8, 1, 1), np.float32), np.ones((4, 8, 1, 1), np.float32), 0, dtype=B.BF16)
+    np.testing.assert_array_equal(got, np.full((1, 4, 1, 1), 8.0, np.float32))
 
 
 @pytest.mark.parametrize("variant", [B.KN2COL, B.IM2ROW])
