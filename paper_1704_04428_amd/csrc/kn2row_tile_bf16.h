@@ -1,5 +1,5 @@
 // Workgroup-tile kernel for bfloat16 operands with fp32 accumulation: the same decomposition as
-// kn2row_tile_f32 (one workgroup = 16*WM rows x a TH x TW output tile; all k*k taps of the kn2row
+// kn2row_tile_f32 (one workgroup = 16*WM*RB rows x a TH x TW output tile; all k*k taps of the kn2row
 // sum, paper section III-A, accumulate into the same registers; a tap is an address offset into the
 // input tile in LDS), re-shaped for v_mfma_f32_16x16x32_bf16:
 //
@@ -10,8 +10,9 @@
 //     probe of ds_read_b128 on gfx950 showed to run at full rate.  A 16-position block of a tile
 //     that is TW wide continues on the next tile row; the row stride is chosen congruent to
 //     16*TW modulo 256 bytes, so the continued part falls on exactly the banks the first part
-//     left free.  Global memory stays [C][H][W]; the staging pass transposes: a thread gathers 8
-//     channels of one position with eight 2-byte loads and writes them with one 16-byte LDS store;
+//     left free.  Global memory stays [C][H][W]; the staging pass transposes: a thread fetches 8
+//     channels of two neighbouring positions with eight 4-byte loads, separates the positions with
+//     byte permutes and writes two 16-byte LDS entries (see the staging plan in the kernel);
 //   - the A operand is again pre-ordered in global memory: one 16-byte load per lane gives the
 //     fragment of a (tap, 16-row block, 32-channel chunk).
 //
@@ -28,7 +29,6 @@ namespace mcmk {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef short i16x2 __attribute__((ext_vector_type(2)));
 
 template <int KS, int TH, int TW, int WM, int WP, int ST = 1, int KG = 1>
 struct TileShapeBf16 {
