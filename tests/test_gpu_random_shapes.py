@@ -59,6 +59,54 @@ def test_random_shape(case):
     assert ran >= 3          # the two staged variants and direct take every shape
 
 
+def _random_strided_cases(count, seed):
+    r = wl.splitmix64(seed, np.arange(count * 10)).reshape(count, 10)
+    cases = []
+    for row in r:
+        v = [int(x % 1000003) for x in row]
+        k = 1 + v[0] % 7
+        pad = v[1] % k
+        stride = 2 + v[8] % 2                 # 2 or 3 (the fused kernels refuse 3)
+        n = 1 + v[2] % 2
+        c = 1 + v[3] % 48
+        if v[7] % 2:
+            c = 8 * (1 + c // 8)              # eligible for the channels-last variants, bf16 included
+        h = max(1, k - 2 * pad) + v[4] % 45
+        w = max(1, k - 2 * pad) + v[5] % 45
+        m = 1 + v[6] % 70
+        cases.append((n, c, h, w, m, k, pad, stride, v[9] % 2 == 0))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_strided_cases(32, 20250314))
+def test_random_strided_shape_with_epilogue(case):
+    """Random shapes with a stride, every variant and operand type that takes them, and -- for the fused
+    variants -- the same call through the bias / rectifier entry point."""
+    n, c, h, w, m, k, pad, stride, relu = case
+    I = wl.uniform(sum(case[:8]), n * c * h * w, -1, 1).reshape(n, c, h, w)
+    K = wl.normal(sum(case[:8]) + 1, m * c * k * k, 0.5).reshape(m, c, k, k)
+    bias = wl.uniform(sum(case[:8]) + 2, m, -1, 1)
+    ref, absref = oracle.mcmk(I, K, pad, stride)
+    want = oracle.bias_relu(ref, bias, relu)
+    ran = 0
+    for dtype, tol in ((B.F32, TOL_F32), (B.BF16, TOL_BF16)):
+        for name, variant in VARIANTS:
+            d = B.desc(n, c, h, w, m, k, pad, stride, dtype)
+            rc = B.conv_mcmk_check(d, variant)
+            if rc == B.ERR_UNSUPPORTED:
+                continue
+            assert rc == B.OK, (case, name, dtype, rc)
+            announce("random strided", case, name, "bf16" if dtype else "f32")
+            got = run_variant(variant, I, K, pad, dtype=dtype, stride=stride)
+            assert got.shape == ref.shape
+            assert_within_bound(got, ref, absref, tol, f"{name} dtype={dtype} {case}")
+            ran += 1
+            if variant in (B.KN2ROW, B.KN2COL):
+                got = run_variant(variant, I, K, pad, dtype=dtype, stride=stride, epilogue=(bias, relu))
+                assert_within_bound(got, want, absref + np.abs(bias).reshape(1, -1, 1, 1), tol, f"{name} epilogue dtype={dtype} {case}")
+    assert ran >= 3
+
+
 def test_large_tensors_sampled():
     """Indices beyond 2^31 bytes: a 1 GiB output and a 0.5 GiB two-pass workspace; sampled outputs."""
     L = wl.Layer("big", 1, 4, 2048, 2048, 64, 3, 1, "u11", "u11", 4711)
