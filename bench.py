@@ -139,6 +139,19 @@ def bench_layer(L, variants, steps, warmup, I_dev=None, K_dev=None, dtype=0):
     return out
 
 
+def library_gemm_ms(L, bf16=False):
+    """Context for the im2col baseline, not part of the library: the GEMM [M x C k^2].[C k^2 x QP] per image
+    (the product im2col hands to a GEMM, section II-B) through torch.bmm, i.e. the vendor BLAS."""
+    import torch
+    dt = torch.bfloat16 if bf16 else torch.float32
+    a = torch.randn(L.m, L.c * L.k * L.k, device="cuda", dtype=dt)
+    b = torch.randn(L.n, L.c * L.k * L.k, L.q * L.p, device="cuda", dtype=dt)
+    out = torch.empty(L.n, L.m, L.q * L.p, device="cuda", dtype=dt)
+    run = lambda: torch.matmul(a, b, out=out)                    # noqa: E731
+    n_steps, n_warm = auto_counts(run)
+    return time_calls(run, n_steps, n_warm)[1]
+
+
 def cpu_baseline(L, I, K, budget_s=12.0, max_passes=40):
     """The oracle as it stands, timed on the host cores: whole passes over the workload until about
     `budget_s` seconds of CPU work have been spent."""
@@ -257,11 +270,15 @@ def main():
             table[name] = bench_layer(layer, variants, steps, None, I_dev if same else None, K_dev if same else None)
             r = table[name]
             r["kn2row_over_im2col_time"] = round(r["kn2row"]["ms"] / r["im2col"]["ms"], 4)
+            if layer.flops > 1e9:
+                # how the hand-written GEMM of the im2col baseline compares with the vendor BLAS on the same product
+                r["library_gemm_ms"] = {"f32": round(library_gemm_ms(layer), 5)}
             r["frac_f32_mfma_peak"] = round(r["kn2row"]["gflops"] / 1e3 / PEAK_F32_MFMA_TFLOPS, 4)
             if name.startswith("cfg5"):          # the deep-layer sweep is also quoted with bf16 operands
                 b = bench_layer(layer, ["kn2row", "kn2col", "im2col", "im2row", "kn2row_2pass"], steps, None,
                                 I_dev if same else None, K_dev if same else None, dtype=B.BF16)
                 b["frac_bf16_mfma_peak"] = round(b["kn2row"]["gflops"] / 1e3 / PEAK_BF16_MFMA_TFLOPS, 4)
+                r["library_gemm_ms"]["bf16"] = round(library_gemm_ms(layer, bf16=True), 5)
                 r["bf16"] = b
             log(name, json.dumps(r))
         result["table"] = table
