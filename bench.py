@@ -152,6 +152,22 @@ def library_gemm_ms(L, bf16=False):
     return time_calls(run, n_steps, n_warm)[1]
 
 
+def library_conv_ms(L, bf16=False):
+    """Context only: the same layer through torch.nn.functional.conv2d, i.e. the vendor's convolution library
+    as PyTorch calls it (whatever algorithm it picks; framework overhead included)."""
+    import torch
+    import torch.nn.functional as F
+    dt = torch.bfloat16 if bf16 else torch.float32
+    x = torch.rand(L.input_shape(), device="cuda", dtype=dt)
+    k = torch.randn(L.kernel_shape(), device="cuda", dtype=dt) * 0.05
+    run = lambda: F.conv2d(x, k, padding=L.pad, stride=L.stride)       # noqa: E731
+    for _ in range(3):
+        run()
+    torch.cuda.synchronize()
+    n_steps, n_warm = auto_counts(run)
+    return time_calls(run, n_steps, n_warm)[1]
+
+
 def cpu_baseline(L, I, K, budget_s=12.0, max_passes=40):
     """The oracle as it stands, timed on the host cores: whole passes over the workload until about
     `budget_s` seconds of CPU work have been spent."""
@@ -270,6 +286,7 @@ def main():
             table[name] = bench_layer(layer, variants, steps, None, I_dev if same else None, K_dev if same else None)
             r = table[name]
             r["kn2row_over_im2col_time"] = round(r["kn2row"]["ms"] / r["im2col"]["ms"], 4)
+            r["library_conv_ms"] = {"f32": round(library_conv_ms(layer), 5)}
             if layer.flops > 1e9:
                 # how the hand-written GEMM of the im2col baseline compares with the vendor BLAS on the same product
                 r["library_gemm_ms"] = {"f32": round(library_gemm_ms(layer), 5)}
@@ -279,6 +296,7 @@ def main():
                                 I_dev if same else None, K_dev if same else None, dtype=B.BF16)
                 b["frac_bf16_mfma_peak"] = round(b["kn2row"]["gflops"] / 1e3 / PEAK_BF16_MFMA_TFLOPS, 4)
                 r["library_gemm_ms"]["bf16"] = round(library_gemm_ms(layer, bf16=True), 5)
+                r["library_conv_ms"]["bf16"] = round(library_conv_ms(layer, bf16=True), 5)
                 r["bf16"] = b
             log(name, json.dumps(r))
         result["table"] = table
