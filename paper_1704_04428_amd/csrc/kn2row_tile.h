@@ -56,14 +56,23 @@ struct TileShape {
     static constexpr int kHT = (TH - 1) * ST + KS;       // input rows under a tile of TH output rows
     static constexpr int kWT = (TW - 1) * ST + KS;
     static constexpr int kPos = kHT * kWT;               // halo-tile positions per channel
+    // Staging deals the tile's elements to the group's threads channel by channel.  When the thread count is
+    // a multiple of the positions per channel, a thread keeps one position and walks the channels: one
+    // offset pair serves all its slots.  A tile that misses that by less than a tenth is staged as if it
+    // had kPosStage positions (the few threads beyond kPos load nothing and store zeros into the padding
+    // behind their channel), which frees the registers of the per-slot offsets.
+    static constexpr int kPerPass = kGroupThreads / kPos;                // whole channels per pass of the group
+    static constexpr bool kPadStage = kPerPass >= 1 && kGroupThreads % kPos != 0 && kGroupThreads % kPerPass == 0 &&
+                                      (kGroupThreads / kPerPass) * 10 <= kPos * 11;
+    static constexpr int kPosStage = kPadStage ? kGroupThreads / kPerPass : kPos;
     // channel stride in LDS words, >= kPos.  Unit stride: == 16 mod 32, so the four channels one B
     // fragment touches start 16 banks apart.  Stride 2: the 16 positions of a fragment sit on every
     // second bank, and an odd channel stride puts the next channel on the banks between them.
-    static constexpr int kCHS = ST == 1 ? ((kPos + 15) / 32) * 32 + 16 : (kPos | 1);
+    static constexpr int kCHS = ST == 1 ? ((kPosStage + 15) / 32) * 32 + 16 : (kPosStage | 1);
     static constexpr int kBuf = kCC * kCHS;              // words per LDS buffer
     static constexpr int kNPB = (TH * TW + 15) / 16;     // 16-position blocks per tile
     static constexpr int kPBW = (kNPB + WP - 1) / WP;    // blocks per wave
-    static constexpr int kSlots = (kCC * kPos + kGroupThreads - 1) / kGroupThreads;
+    static constexpr int kSlots = (kCC * kPosStage + kGroupThreads - 1) / kGroupThreads;
     static constexpr size_t kLdsBytes = 2 * (size_t)KG * kBuf * sizeof(float);
 };
 
@@ -86,7 +95,7 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
     using S = TileShape<KS, TH, TW, WM, WP, CCH, KG, ST>;
     static_assert(CCH % 16 == 0, "a chunk is a whole number of packed 16-channel groups");
     constexpr int NQ = CCH / 16;                   // packed A vectors per tap and chunk
-    constexpr int CC = S::kCC, NT = S::kGroupThreads, WT = S::kWT, POS = S::kPos, CHS = S::kCHS;
+    constexpr int CC = S::kCC, NT = S::kGroupThreads, WT = S::kWT, POS = S::kPos, POSS = S::kPosStage, CHS = S::kCHS;
     constexpr int PBW = S::kPBW, NPB = S::kNPB, SLOTS = S::kSlots, BUF = S::kBuf;
     // position blocks are dealt evenly to the WP waves: the first REM waves own PBW blocks, the
     // others PBW-1 (all own PBW when the split is exact)
@@ -142,23 +151,23 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
         const_cast<float *>(in_img), 0, (int)((size_t)a.c * plane * sizeof(float)), 0x00020000);
     const uint32_t chunk_bytes = (uint32_t)(CC * plane * sizeof(float));
     const int chunks_total = (a.cg + NQ - 1) / NQ;
-    // When the thread count is a multiple of the positions per channel every thread keeps one
-    // position and walks the channels in steps of NT/POS: one offset pair serves all its slots.
-    constexpr bool kRegular = (NT % POS) == 0;
+    // When the thread count is a multiple of the (staged) positions per channel every thread keeps one
+    // position and walks the channels in steps of NT/POSS: one offset pair serves all its slots.
+    constexpr bool kRegular = (NT % POSS) == 0;
     constexpr int NOFF = kRegular ? 1 : SLOTS;
-    constexpr int CSTEP = kRegular ? NT / POS : 0;
+    constexpr int CSTEP = kRegular ? NT / POSS : 0;
     uint32_t g_off[NOFF];  // byte offset of the element in chunk 0, or 2 GiB when outside the image
     int l_off[NOFF];       // word offset inside an LDS buffer, or -1 when the slot is unused
 #pragma unroll
     for (int s = 0; s < NOFF; ++s) {
         const int e = tid + s * NT;
-        const int cl = e / POS, pos = e % POS;
+        const int cl = e / POSS, pos = e % POSS;
         const int r = pos / WT, col = pos % WT;
         const int gy = iy0 + r, gx = ix0 + col;
-        const bool used = e < CC * POS;
-        const bool inside = used && gy >= 0 && gy < a.h && gx >= 0 && gx < a.w;
+        const bool used = e < CC * POSS;
+        const bool inside = used && pos < POS && gy >= 0 && gy < a.h && gx >= 0 && gx < a.w;
         g_off[s] = inside ? (uint32_t)((cl * plane + (size_t)gy * a.w + gx) * sizeof(float)) : 0x80000000u;
-        l_off[s] = used ? cl * CHS + r * WT + col : -1;
+        l_off[s] = used ? cl * CHS + pos : -1;          // pos == r * WT + col; beyond POS: the padding, CHS >= POSS
     }
     static_assert(!kRegular || SLOTS * CSTEP == CC, "regular staging must cover the chunk exactly");
 

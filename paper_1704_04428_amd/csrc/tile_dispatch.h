@@ -29,15 +29,20 @@ constexpr TileShapeDesc kTileShapes[] = {
     // small images (a single 27 x 27 or 28 x 28 image has four 14 x 14 tiles): quarter tiles, one position
     // block per wave, so that a layer with few tiles still spreads over the chip
     {7, 7, 1, 4, 1, 1},
+    // two 14 x 14 tiles side by side under sixteen waves (fp32 operands, kernel sides up to 3): 392 positions
+    // are 24.5 blocks, so 2 % of the matrix work is padding where a single 14 x 14 tile (12.25 blocks in 13)
+    // has 6 %; each SIMD gets one wave with 7 blocks and three with 6
+    {14, 28, 4, 4, 1, 1},
 };
 constexpr int kConvShapes = 7;
 constexpr int kGemmShape = 7;
 constexpr int kStridedShapes = 3;
 constexpr int kMaxKernelSide = 7;      // kernel sides 1..7 are instantiated
 // shapes beyond the first seven (bf16 shapes with two row blocks per wave, quarter tiles): convolution shapes ...
-constexpr int kWideConvShapes = 5;
-constexpr int kWideConvShape[kWideConvShapes] = {8, 9, 10, 12, 13};
+constexpr int kWideConvShapes = 6;
+constexpr int kWideConvShape[kWideConvShapes] = {8, 9, 10, 12, 13, 14};
 constexpr int kWideGemmShape = 11;     // ... and the plain-GEMM shape
+constexpr int kPairTileShape = 14;     // the 14 x 28 shape
 
 struct TileRequest {
     TileArgs args;       // tiles_x, tiles_y and row_tiles are filled in by the launcher

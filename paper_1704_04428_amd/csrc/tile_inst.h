@@ -106,6 +106,9 @@ int MCMK_FN(const TileRequest &rq)
 #if MCMK_KS <= 5
         case 13: return launch_shape<7, 7, 1, 4, 16, true>(rq);
 #endif
+#if !MCMK_BF16 && MCMK_KS <= 3
+        case 14: return launch_shape<14, 28, 4, 4, 16, true>(rq);
+#endif
 #if MCMK_BF16 && MCMK_KS <= 3
         case 8: return launch_shape<14, 14, 4, 2, 16, true, 1, 1, 2>(rq);
         case 9: return launch_shape<14, 14, 2, 4, 16, true, 1, 1, 2>(rq);
@@ -133,6 +136,9 @@ int MCMK_FN(const TileRequest &rq)
 #endif
 #if MCMK_KS <= 5
     case 13: return launch_shape<7, 7, 1, 4>(rq);                           // quarter tiles for small images
+#endif
+#if !MCMK_BF16 && MCMK_KS <= 3
+    case 14: return launch_shape<14, 28, 4, 4>(rq);                         // a pair of tiles under sixteen waves
 #endif
 #if MCMK_BF16 && MCMK_KS <= 3
     case 8: return launch_shape<14, 14, 4, 2, 16, false, 1, 1, 2>(rq);      // two row blocks per wave
