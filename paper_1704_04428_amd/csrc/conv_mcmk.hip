@@ -245,7 +245,7 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
 
 // The candidate the cost estimate prefers for the fused kernel (or the one CONV_MCMK_TILE forces:
 // tuning aid, menu index = shape + 7 * (csplit - 1) for the seven common shapes, then
-// 14 + further shape + 6 * (csplit - 1) for the further shapes: bf16 with two row blocks per wave, quarter tiles, tile pairs).
+// 14 + further shape + 7 * (csplit - 1) for the further shapes: bf16 with two row blocks per wave, quarter tiles, tile pairs).
 Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, bool epilogue, const char *force);
 
 // The search walks the whole menu, a few microseconds of host time -- as long as the smallest layers
@@ -297,8 +297,11 @@ Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_la
             // two row blocks per wave: bf16 operands, unit stride
             if (c.rb > 1 && (d->dtype != CONV_MCMK_BF16 || d->stride > 1 || d->k > 3)) continue;
             if (c.th == 7 && (d->stride > 1 || d->k > 5)) continue;
-            // the 14 x 28 pair under sixteen waves: fp32 operands, unit stride (excluded below), kernel sides up to 3
-            if (sh == kPairTileShape && (d->dtype == CONV_MCMK_BF16 || d->k > 3)) continue;    // quarter tiles: unit stride, kernel sides up to 5
+            // the 14 x 28 pairs under sixteen waves: fp32 operands, unit stride (excluded below), kernel sides up to 3
+            if (sh >= kPairTileShape && (d->dtype == CONV_MCMK_BF16 || d->k > 3)) continue;
+            // the two-group pair is not built for 2 x 2 kernels, nor for channels-last operands (measured slower there
+            // than single tiles: the 16-byte gathers of eight waves fill a 30-column tile less evenly)
+            if (sh > kPairTileShape && (d->k == 2 || channels_last)) continue;    // quarter tiles: unit stride, kernel sides up to 5
             // channel groups exist for kernel sides up to 3 only (four groups of double-buffered 5x5 halo
             // tiles would not fit the 160 KB of LDS) and are an alternative to, not a partner of, the
             // two-way split

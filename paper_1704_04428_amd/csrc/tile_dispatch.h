@@ -33,16 +33,19 @@ constexpr TileShapeDesc kTileShapes[] = {
     // are 24.5 blocks, so 2 % of the matrix work is padding where a single 14 x 14 tile (12.25 blocks in 13)
     // has 6 %; each SIMD gets one wave with 7 blocks and three with 6
     {14, 28, 4, 4, 1, 1},
+    // the same pair with two channel groups of eight waves, 32 rows per workgroup: twice the workgroups for layers
+    // that have too few pairs (28 x 28 images), and a SIMD carries 12.5 blocks per chunk where single tiles give it 13
+    {14, 28, 2, 4, 2, 1},
 };
 constexpr int kConvShapes = 7;
 constexpr int kGemmShape = 7;
 constexpr int kStridedShapes = 3;
 constexpr int kMaxKernelSide = 7;      // kernel sides 1..7 are instantiated
 // shapes beyond the first seven (bf16 shapes with two row blocks per wave, quarter tiles): convolution shapes ...
-constexpr int kWideConvShapes = 6;
-constexpr int kWideConvShape[kWideConvShapes] = {8, 9, 10, 12, 13, 14};
+constexpr int kWideConvShapes = 7;
+constexpr int kWideConvShape[kWideConvShapes] = {8, 9, 10, 12, 13, 14, 15};
 constexpr int kWideGemmShape = 11;     // ... and the plain-GEMM shape
-constexpr int kPairTileShape = 14;     // the 14 x 28 shape
+constexpr int kPairTileShape = 14;     // the 14 x 28 shapes: this one and the next (two channel groups)
 
 struct TileRequest {
     TileArgs args;       // tiles_x, tiles_y and row_tiles are filled in by the launcher

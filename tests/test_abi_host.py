@@ -170,7 +170,8 @@ def test_plan_selection_for_benchmark_layers(lib, monkeypatch):
         "cfg4_vgg_early": "tile 14x14, waves 4x2, row blocks 1, channel groups 1, channel split 1, 256 workgroups",
         # 56 x 56 images: pairs of tiles under sixteen waves, one workgroup per compute unit, 2 % padding instead of 6 %
         "cfg5a_vgg_deep56": "tile 14x28, waves 4x4, row blocks 1, channel groups 1, channel split 1, 256 workgroups",
-        "cfg5b_vgg_deep28": "tile 14x14, waves 4x2, row blocks 1, channel groups 1, channel split 1, 256 workgroups",
+        # 28 x 28 images: too few pairs for 64-row workgroups, so 32 rows and two channel groups of eight waves
+        "cfg5b_vgg_deep28": "tile 14x28, waves 2x4, row blocks 1, channel groups 2, channel split 1, 256 workgroups",
         # 14x14 images: 64 tiles of 64 kernels cannot fill 256 CUs, so the contraction is split four ways
         "cfg5c_vgg_deep14": "tile 14x14, waves 1x4, row blocks 1, channel groups 4, channel split 1, 256 workgroups",
     }

@@ -262,9 +262,9 @@ def test_runtime_errors_through_binding():
 @pytest.mark.parametrize("dtype", [B.F32, B.BF16])
 @pytest.mark.parametrize("k,pad", [(1, 0), (2, 1), (3, 1), (4, 1), (5, 2), (6, 3), (7, 3)])
 def test_every_tile_shape_of_the_menu(k, pad, dtype, monkeypatch):
-    """The selector only ever launches the shape it prefers; force each of the 26 menu entries
-    (7 common tile / wave shapes, then 4 bf16-only shapes with two row blocks per wave, the quarter tiles and the
-    fp32-only pair of tiles under sixteen waves, each with channel split 1 and 2; entries the operand type or kernel side does not have fall back to the selector) so every
+    """The selector only ever launches the shape it prefers; force each of the 28 menu entries
+    (7 common tile / wave shapes, then 4 bf16-only shapes with two row blocks per wave, the quarter tiles and the two
+    fp32-only pairs of tiles under sixteen waves, each with channel split 1 and 2; entries the operand type or kernel side does not have fall back to the selector) so every
     instantiation is checked."""
     from gpu_util import TOL_BF16
     case = (2, 72, 33, 30, 80, k, pad)        # 5 (fp32) / 3 (bf16) channel chunks: an uneven split
@@ -273,7 +273,7 @@ def test_every_tile_shape_of_the_menu(k, pad, dtype, monkeypatch):
     K = wl.normal(601 + k, m * c * k * k, 0.5).reshape(m, c, k, k)
     ref, absref = oracle.mcmk(I, K, pad)
     tol = TOL_BF16 if dtype == B.BF16 else TOL_F32
-    for index in range(26):
+    for index in range(28):
         for variant in (B.KN2ROW, B.KN2COL):
             announce("menu", "k", k, "dtype", dtype, "tile", index, "variant", variant)
             monkeypatch.setenv("CONV_MCMK_TILE", str(index))
