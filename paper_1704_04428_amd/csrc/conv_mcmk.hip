@@ -197,16 +197,26 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
         const int rem = npb % c.wp, pbw = ceil_div(npb, c.wp);
         simd_blocks[w % 4] += c.rb * ((rem == 0 || wp < rem) ? pbw : pbw - 1);
     }
-    int simd_load = 0;
-    for (int i = 0; i < 4; ++i) simd_load = simd_blocks[i] > simd_load ? simd_blocks[i] : simd_load;
+    int simd_load = 0, simd_sum = 0;
+    for (int i = 0; i < 4; ++i) {
+        simd_load = simd_blocks[i] > simd_load ? simd_blocks[i] : simd_load;
+        simd_sum += simd_blocks[i];
+    }
     const bool bf16 = d->dtype == CONV_MCMK_BF16;
     // chunks each wave works through (the channel groups of a workgroup share them out)
     const int chunks = ceil_div(ceil_div(ceil_div(d->c, bf16 ? 32 : 16), c.csplit), c.kg);
     // fp32: 4 MFMAs of 32 cycles per tap and 16-channel chunk; bf16: 1 MFMA of 16 cycles per tap and 32-channel chunk
     const double steps = (double)chunks * ks * ks * (bf16 ? 0.5 : 4.0);
     const long long per_cu = (wgs + kNumCU - 1) / kNumCU;
-    // workgroups a CU can hold (LDS, VGPRs): the bf16 kernels need more than 128 registers, so 8 waves per CU
-    const int can_hold = c.kg > 1 ? 1 : (bf16 ? 8 : 16) / waves;
+    // workgroups a CU can hold (VGPRs: the bf16 kernels need more than 128 registers, so 8 waves per CU; fp32: the two
+    // double-buffered halo tiles of 16 channels in 160 KB of LDS)
+    int can_hold = c.kg > 1 ? 1 : (bf16 ? 8 : 16) / waves;
+    const int halo = ((c.th - 1) * d->stride + ks) * ((c.tw - 1) * d->stride + ks);
+    if (!bf16) {
+        const int fit = 163840 / (2 * c.kg * 16 * (((halo + 15) / 32) * 32 + 16) * 4);
+        can_hold = can_hold < fit ? can_hold : fit;
+        if (can_hold < 1) can_hold = 1;
+    }
     const long long held = per_cu < can_hold ? per_cu : can_hold;
     const double waves_per_simd = (double)held * waves / 4.0;
     double pipe_use = waves_per_simd >= 2.0 ? 0.9 : 0.7;
@@ -223,15 +233,25 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
         const double reuse_b = rows / (rows + 16.0) / 0.8;
         pipe_use *= (reuse_a < 1.1 ? reuse_a : 1.1) * (reuse_b < 1.0 ? reuse_b : 1.0);
     }
-    double us = (double)per_cu * simd_load * steps * 0.0139 / pipe_use;
+    // a ragged deal of blocks loads one SIMD more than the others; workgroups that share a CU even that out in part
+    const double blocks = (!bf16 && held >= 2) ? 0.5 * simd_load + 0.125 * simd_sum : (double)simd_load;
+    double us = (double)per_cu * blocks * steps * 0.0139 / pipe_use;
     // bf16: a wave has one chunk of staging loads in flight, so a workgroup cannot finish a chunk faster than
     // a round trip to memory (about 0.8 us when every CU asks at once), however little matrix work it holds
     if (bf16 && us < per_cu * chunks * 0.8) us = per_cu * chunks * 0.8;
     // staging-heavy cases: a 1 x 1 kernel uses every staged value once instead of k*k times, a
     // strided tile stages four input values per output position (both measured)
-    if (ks == 1 && c.shape != kGemmShape) us *= 1.35;
+    // (less so for the 16 x 16 tile, whose 256 positions per channel give every thread one position to stage)
+    if (ks == 1 && c.shape != kGemmShape) us *= (!bf16 && c.th * c.tw == 256) ? 1.1 : 1.35;
     if (d->stride == 2) us *= 1.25;
     us += bf16 ? 9.0 : 6.0;          // launch, first loads, output write (bf16 workgroups: twice the rows to write)
+    // every further workgroup a CU works through brings its own prologue (staging plan, first tile: grows with the
+    // tile elements a thread stages) and closing write, hidden in part behind the workgroups resident beside it
+    // (fitted to all candidates on layers of 1 to 32 chunks; what decides between many small and few large workgroups)
+    if (!bf16 && per_cu > 1) {
+        const int slots = ceil_div(16 * halo, 64 * group_waves);
+        us += (double)(per_cu - 1) * (2.8 + 0.2 * slots) / can_hold;
+    }
     // [M][Q][P] output of a bf16 call: every workgroup writes at the same time at the end, and rows of 14
     // floats make partial cache lines of that burst (measured 17 k cycles against 8 k with whole image rows)
     if (bf16 && !channels_last && c.tw < 28) {
