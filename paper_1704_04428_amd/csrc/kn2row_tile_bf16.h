@@ -126,9 +126,17 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_bf16(const Tile
     // one element inside the image (left / right border) reads a dword that lies wholly inside the
     // plane -- at the element, or one element earlier when it is the last of its plane -- and the
     // permute selector of the slot picks the half that holds it (or zeros).  Needs H*W >= 2.
+    // A dword at an odd element index costs the texture addresser 16 cycles per wave where an aligned
+    // one costs 6 (measured), and the gathers of a chunk queue up behind it: so the pairs of a row start
+    // at an even image column when the image width is even (every row and plane then starts at an even
+    // element), even if the tile's own first column is odd -- one more pair per row, whose outer halves
+    // fall outside the tile and are dropped.  Built where the extra pairs need no further staging slot
+    // (a slot more for everyone costs the 14 x 14 tiles more than the alignment of every second tile gains).
     // With channels-last input (CL) an item is simply (channel octet, position): one 16-byte load.
     constexpr int HT = S::kHT;
-    constexpr int PW = (WT + 1) / 2;                       // column pairs per tile row
+    constexpr int kPairsPlain = (WT + 1) / 2, kPairsEven = (WT + 2) / 2;
+    constexpr bool kEvenPairs = (4 * HT * kPairsEven + NT - 1) / NT == (4 * HT * kPairsPlain + NT - 1) / NT;
+    constexpr int PW = kEvenPairs ? kPairsEven : kPairsPlain;   // column pairs per tile row
     constexpr int PITEMS = 4 * HT * PW;
     constexpr int PSLOTS = (PITEMS + NT - 1) / NT;
     constexpr uint32_t kSelLo = 0x05040100u, kSelHi = 0x07060302u, kSelZero = 0x0c0c0c0cu;
@@ -142,34 +150,39 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_bf16(const Tile
     uint32_t g_off[NSEL];    // byte offset of the slot's dword in the first channel of its octet, chunk 0, or 2 GiB
     uint32_t sel_a[NSEL];    // permute selector for the first column of the pair, ...
     uint32_t sel_b[NSEL];    // ... and for the second
-    int l_off[NSEL];         // byte offset of the first column inside an LDS buffer, or -1 when the slot is unused
-    bool two_cols[NSEL];     // the tile row has the pair's second column
+    int l_off[NSEL];         // byte offset of the pair's first column inside an LDS buffer (one entry before the row when that column is -1)
+    bool put_a[NSEL];        // the tile row has the pair's first column, ...
+    bool put_b[NSEL];        // ... its second column
     if constexpr (!CL) {
+        const int shift = (kEvenPairs && (a.w & 1) == 0) ? (ix0 & 1) : 0;      // the same for the whole workgroup
 #pragma unroll
         for (int s = 0; s < PSLOTS; ++s) {
             const int e = tid + s * NT;
             const int oct = e / (HT * PW), rem = e % (HT * PW);
-            const int r = rem / PW, col = 2 * (rem % PW);
+            const int r = rem / PW, col = 2 * (rem % PW) - shift;              // -1: only the pair's second column is in the tile
             const int gy = iy0 + r, gx = ix0 + col;
             const bool used = e < PITEMS;
             const bool in_row = used && gy >= 0 && gy < a.h;
-            const bool v0 = in_row && gx >= 0 && gx < a.w;
-            const bool v1 = in_row && col + 1 < WT && gx + 1 >= 0 && gx + 1 < a.w;
+            const bool c0 = used && col >= 0 && col < WT, c1 = used && col + 1 < WT;
+            const bool v0 = in_row && c0 && gx >= 0 && gx < a.w;
+            const bool v1 = in_row && c1 && gx + 1 >= 0 && gx + 1 < a.w;
             long long p = (long long)gy * a.w + gx;         // element index of the dword's lower half inside a plane
             uint32_t sa = kSelZero, sb = kSelZero;
             if (v0 && v1) {
                 sa = kSelLo;  sb = kSelHi;
-            } else if (v0) {
-                if (p + 1 < (long long)plane) sa = kSelLo; else { p -= 1;  sa = kSelHi; }
-            } else if (v1) {
-                p += 1;
-                if (p + 1 < (long long)plane) sb = kSelLo; else { p -= 1;  sb = kSelHi; }
+            } else if (v0 || v1) {
+                // a single element: the aligned dword that holds it if that lies inside the plane, else the other one
+                const long long el = v0 ? p : p + 1;
+                const bool low = (el & 1) == 0 ? el + 1 < (long long)plane : el == 0;
+                p = low ? el : el - 1;
+                (v0 ? sa : sb) = low ? kSelLo : kSelHi;
             }
             g_off[s] = (v0 || v1) ? (uint32_t)(oct * 8) * plane_bytes + (uint32_t)p * 2u : 0x80000000u;
             sel_a[s] = sa;
             sel_b[s] = sb;
-            l_off[s] = used ? oct * PLB + r * RSB + col * 16 : -1;
-            two_cols[s] = col + 1 < WT;
+            l_off[s] = oct * PLB + r * RSB + col * 16;
+            put_a[s] = c0;
+            put_b[s] = c1;
         }
     }
 
@@ -221,10 +234,8 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_bf16(const Tile
                     first[e] = __builtin_amdgcn_perm(stage[s][2 * e + 1], stage[s][2 * e], sel_a[s]);
                     second[e] = __builtin_amdgcn_perm(stage[s][2 * e + 1], stage[s][2 * e], sel_b[s]);
                 }
-                if (l_off[s] >= 0) {
-                    *reinterpret_cast<u32x4 *>(buf + l_off[s]) = first;
-                    if (two_cols[s]) *reinterpret_cast<u32x4 *>(buf + l_off[s] + 16) = second;
-                }
+                if (put_a[s]) *reinterpret_cast<u32x4 *>(buf + l_off[s]) = first;
+                if (put_b[s]) *reinterpret_cast<u32x4 *>(buf + l_off[s] + 16) = second;
             }
         }
     };
