@@ -171,12 +171,23 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
     }
     static_assert(!kRegular || SLOTS * CSTEP == CC, "regular staging must cover the chunk exactly");
 
-    // channels last: item e = tid + s*NT is (channel quad e % (CC/4), position e / (CC/4)): one
-    // 16-byte load of four consecutive channels (the host requires C to be a multiple of 4, so
-    // every quad is aligned and whole).  Offsets are recomputed per chunk (an opaque copy of tid keeps the compiler from
+    // channels last: an item is (channel quad, position): one 16-byte load of four consecutive channels
+    // (the host requires C to be a multiple of 4, so every quad is aligned and whole), stored as four
+    // words CHS apart.  CHS is 16 mod 32, so channels four apart share their banks: a wave that held all
+    // the quads of 16 positions would put four lanes on every bank it touches.  Instead the 64 lanes of
+    // one store are two neighbouring quads of 32 consecutive positions (two lanes per bank, the least 64
+    // lanes can have), and the next 64 items are the next two quads of the same positions.
+    // Offsets are recomputed per chunk (an opaque copy of tid keeps the compiler from
     // hoisting them into more live registers).
     constexpr int QPC = CC / 4;                                   // channel quads per chunk
-    constexpr int VSLOTS = (QPC * POS + NT - 1) / NT;             // items per thread
+    constexpr int QH = QPC / 2;                                   // 64-item groups per 32 positions
+    constexpr int VITEMS = 64 * QH * ((POS + 31) / 32);
+    constexpr int VSLOTS = (VITEMS + NT - 1) / NT;                // items per thread
+    auto cl_item = [](int e, int &quad, int &pos) {
+        const int grp64 = e >> 6, l = e & 63;
+        quad = (l & 1) + 2 * (grp64 % QH);
+        pos = 32 * (grp64 / QH) + (l >> 1);
+    };
     constexpr int NSTAGE = CL ? 4 * VSLOTS : SLOTS;
     float stage[NSTAGE];
     auto load_chunk = [&](int chunk) {
@@ -185,12 +196,12 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
             asm volatile("" : "+v"(t));
 #pragma unroll
             for (int s = 0; s < VSLOTS; ++s) {
-                const int e = t + s * NT;
-                const int quad = e % QPC, pos = e / QPC;
+                int quad, pos;
+                cl_item(t + s * NT, quad, pos);
                 const int r = pos / WT, col = pos % WT;
                 const int gy = iy0 + r, gx = ix0 + col;
                 const int ch = chunk * CC + quad * 4;
-                const bool ok = e < QPC * POS && gy >= 0 && gy < a.h && gx >= 0 && gx < a.w;
+                const bool ok = pos < POS && gy >= 0 && gy < a.h && gx >= 0 && gx < a.w;
                 const uint32_t base = (uint32_t)((((size_t)gy * a.w + gx) * a.c + ch) * sizeof(float));
                 const f32x4 v = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
                     in_rsrc, (int)((ok && ch < a.c) ? base : 0x80000000u), 0, 0));
@@ -215,9 +226,9 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
             asm volatile("" : "+v"(t));
 #pragma unroll
             for (int s = 0; s < VSLOTS; ++s) {
-                const int e = t + s * NT;
-                const int quad = e % QPC, pos = e / QPC;
-                if (e < QPC * POS) {
+                int quad, pos;
+                cl_item(t + s * NT, quad, pos);
+                if (pos < POS) {
 #pragma unroll
                     for (int u = 0; u < 4; ++u)
                         buf[(quad * 4 + u) * CHS + (pos / WT) * WT + (pos % WT)] = stage[4 * s + u];
