@@ -183,10 +183,14 @@ int launch_tile(const conv_mcmk_desc *d, const Dims &dm, int ks, int shape, int 
 //     against 90 % with two or more);
 //   - each launch pays a fixed prologue / epilogue; the channel split pays a zero fill plus two
 //     device-scope atomic adds per output element.
+long long workgroups(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c)
+{
+    return (long long)d->n * ceil_div(dm.p, c.tw) * ceil_div(dm.q, c.th) * ceil_div(dm.mb, c.wm * c.rb) * c.csplit;
+}
+
 double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, int ks, bool channels_last = true)
 {
-    const long long tiles = (long long)d->n * ceil_div(dm.p, c.tw) * ceil_div(dm.q, c.th) * ceil_div(dm.mb, c.wm * c.rb);
-    const long long wgs = tiles * c.csplit;
+    const long long wgs = workgroups(d, dm, c);
     const int npb = ceil_div(c.th * c.tw, 16);
     const int group_waves = c.wm * c.wp;
     const int waves = group_waves * c.kg;
@@ -224,11 +228,11 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
     // larger, so LDS reads, operand loads and the per-chunk hand-over weigh more; measured slopes over
     // the channel count give 48 % of the pipe with one row block per wave and 59 % with two
     if (bf16) {
-        pipe_use *= c.rb > 1 ? 0.65 : 0.53;
+        pipe_use *= c.rb > 1 ? 0.65 : 0.60;
         // an A fragment (1 KB from L1/L2 per wave) is reused for the wave's position blocks, the staged
         // tile for the workgroup's rows: few blocks per wave or few rows per workgroup leave the
         // load path, not the matrix pipe, as the limit (fitted to the sweep of all shapes)
-        const double reuse_a = 0.25 + 0.107 * ceil_div(npb, c.wp);
+        const double reuse_a = 0.5 + 0.07 * ceil_div(npb, c.wp);
         const double rows = 16.0 * c.wm * c.rb;
         const double reuse_b = rows / (rows + 16.0) / 0.8;
         pipe_use *= (reuse_a < 1.1 ? reuse_a : 1.1) * (reuse_b < 1.0 ? reuse_b : 1.0);
@@ -237,14 +241,14 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
     const double blocks = (!bf16 && held >= 2) ? 0.5 * simd_load + 0.125 * simd_sum : (double)simd_load;
     double us = (double)per_cu * blocks * steps * 0.0139 / pipe_use;
     // bf16: a wave has one chunk of staging loads in flight, so a workgroup cannot finish a chunk faster than
-    // a round trip to memory (about 0.8 us when every CU asks at once), however little matrix work it holds
-    if (bf16 && us < per_cu * chunks * 0.8) us = per_cu * chunks * 0.8;
+    // a round trip to memory (0.2 us and more), however little matrix work it holds
+    if (bf16 && us < per_cu * chunks * 0.2) us = per_cu * chunks * 0.2;
     // staging-heavy cases: a 1 x 1 kernel uses every staged value once instead of k*k times, a
     // strided tile stages four input values per output position (both measured)
     // (less so for the 16 x 16 tile, whose 256 positions per channel give every thread one position to stage)
-    if (ks == 1 && c.shape != kGemmShape) us *= (!bf16 && c.th * c.tw == 256) ? 1.1 : 1.35;
+    if (ks == 1 && c.shape != kGemmShape) us *= c.th * c.tw == 256 ? (bf16 ? 1.2 : 1.1) : (bf16 ? 1.6 : 1.35);
     if (d->stride == 2) us *= 1.25;
-    us += bf16 ? 9.0 : 6.0;          // launch, first loads, output write (bf16 workgroups: twice the rows to write)
+    us += 6.0;                       // launch, first loads, output write
     // every further workgroup a CU works through brings its own prologue (staging plan, first tile: grows with the
     // tile elements a thread stages) and closing write, hidden in part behind the workgroups resident beside it
     // (fitted to all candidates on layers of 1 to 32 chunks; what decides between many small and few large workgroups)
@@ -252,13 +256,16 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
         const int slots = ceil_div(16 * halo, 64 * group_waves);
         us += (double)(per_cu - 1) * (2.8 + 0.2 * slots) / can_hold;
     }
+    // bf16: a microsecond each, six for the sixteen-wave workgroups with channel groups, which share a CU with nobody
+    // (fitted the same way, 230 candidate runs on ten layers)
+    if (bf16 && per_cu > 1) us += (double)(per_cu - 1) * (waves == 16 ? 6.0 : 1.0);
     // [M][Q][P] output of a bf16 call: every workgroup writes at the same time at the end, and rows of 14
     // floats make partial cache lines of that burst (measured 17 k cycles against 8 k with whole image rows)
     if (bf16 && !channels_last && c.tw < 28) {
         const double burst = (double)d->n * d->m * dm.q * dm.p * 4.0 / 25.7e6;     // relative to the layer it was measured on
-        us += 2.5 * (burst < 1.0 ? burst : 1.0);
+        us += 4.0 * (burst < 1.0 ? burst : 1.0);
     }
-    if (c.csplit > 1) us += 3.0 + 2.0 * (double)d->n * d->m * dm.q * dm.p * 6.25e-6;
+    if (c.csplit > 1) us += 3.0 + (bf16 ? 1.4 : 2.0) * (double)d->n * d->m * dm.q * dm.p * 6.25e-6;
     if (c.kg > 1) us += 1.5;                                            // the closing exchange through LDS
     return us;
 }
@@ -332,7 +339,13 @@ Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_la
             // 2 x 4 wave layout only (register budget of the staging gather)
             if (d->stride > 1 && d->dtype == CONV_MCMK_BF16 && !channels_last && d->k >= 5 && sh != 1) continue;
             const double cost = (force && atoi(force) == index) ? 0.0 : tile_cost(d, dm, c, d->k, channels_last);
-            if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = c; }
+            // equal estimates (layers that sit on a latency floor): the candidate with more workgroups keeps more
+            // loads in flight
+            const bool tie = best_cost >= 0 && cost <= best_cost + 1e-6 && cost >= best_cost - 1e-6;
+            if (best_cost < 0 || (tie ? workgroups(d, dm, c) > workgroups(d, dm, best) : cost < best_cost)) {
+                best_cost = cost;
+                best = c;
+            }
         }
     return best;
 }
