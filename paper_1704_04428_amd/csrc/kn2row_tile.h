@@ -73,7 +73,12 @@ struct TileShape {
     static constexpr int kNPB = (TH * TW + 15) / 16;     // 16-position blocks per tile
     static constexpr int kPBW = (kNPB + WP - 1) / WP;    // blocks per wave
     static constexpr int kSlots = (kCC * kPosStage + kGroupThreads - 1) / kGroupThreads;
-    static constexpr size_t kLdsBytes = 2 * (size_t)KG * kBuf * sizeof(float);
+    // LDS buffers per channel group: two (staging one chunk ahead, a barrier per chunk), or four (staging
+    // two chunks ahead, a barrier every second chunk) where four buffers for every workgroup that the
+    // wave count lets share a compute unit still fit its 160 KB
+    static constexpr int kNBuf =
+        (KG == 1 && 4 * (size_t)kBuf * sizeof(float) * (16 / (WM * WP) > 0 ? 16 / (WM * WP) : 1) <= 160 * 1024) ? 4 : 2;
+    static constexpr size_t kLdsBytes = (size_t)kNBuf * KG * kBuf * sizeof(float);
 };
 
 // CL = false: input [n][c][h][w], output [n][rows][q][p] (kn2row).
@@ -96,7 +101,7 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
     static_assert(CCH % 16 == 0, "a chunk is a whole number of packed 16-channel groups");
     constexpr int NQ = CCH / 16;                   // packed A vectors per tap and chunk
     constexpr int CC = S::kCC, NT = S::kGroupThreads, WT = S::kWT, POS = S::kPos, POSS = S::kPosStage, CHS = S::kCHS;
-    constexpr int PBW = S::kPBW, NPB = S::kNPB, SLOTS = S::kSlots, BUF = S::kBuf;
+    constexpr int PBW = S::kPBW, NPB = S::kNPB, SLOTS = S::kSlots, BUF = S::kBuf, NBUF = S::kNBuf;
     // position blocks are dealt evenly to the WP waves: the first REM waves own PBW blocks, the
     // others PBW-1 (all own PBW when the split is exact)
     constexpr int REM = NPB % WP;
@@ -114,7 +119,7 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
     const int tid = wave * 64 + lane;                             // thread index inside the group
     const int wm = wave % WM;
     const int wp = wave / WM;
-    float *const lds = lds_all + (size_t)kg * 2 * BUF;            // this group's two buffers
+    float *const lds = lds_all + (size_t)kg * NBUF * BUF;         // this group's buffers
 
     // ---- which tile.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2), so
     // the launch index is re-mapped to give every XCD a contiguous run of tiles: the row tiles that
@@ -284,10 +289,22 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
 
     AFrag a_queue[kDepth];
     const int chunk_first = chunk_lo + kg;                        // this group's chunks: first, +KG, +2KG, ...
+    const int nsteps = (chunk_hi - chunk_lo + KG - 1) / KG;       // the same for every group: barriers match
+    // With four buffers and enough chunks to repay a second staged chunk before the first product, the
+    // input is staged two chunks ahead and the workgroup meets at a barrier only after every second
+    // chunk.  The SIMD serves its oldest ready wave first, so the waves of a chunk finish one after the
+    // other and the last one runs its final stretch alone, with nobody to cover its LDS latency, before
+    // the barrier lets anyone go on: half as many barriers, half as many such tails.
+    const bool deep = NBUF == 4 && nsteps >= 8;                   // the same for the whole workgroup
+    const int ahead = deep ? 2 : 1;
     load_chunk(chunk_first);
 #pragma unroll
     for (int d = 0; d < kDepth; ++d) a_queue[d] = load_a(chunk_first + KG * (d / T), d % T);
     store_chunk(lds);
+    if (deep) {
+        load_chunk(chunk_first + KG);
+        store_chunk(lds + BUF);
+    }
     __syncthreads();
 
     // One chunk of matrix-core work for NB position blocks (NB is PBW, or PBW-1 for the wave that
@@ -296,7 +313,7 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
         constexpr int NB = decltype(nb_tag)::value;
         constexpr int VQ = CCH / 4;                // channel quads per chunk
         constexpr int G = T * VQ;                  // steps per chunk: (tap, channel quad)
-        const float *bsrc = lds + (((chunk - chunk_first) / KG) & 1) * BUF;
+        const float *bsrc = lds + (((chunk - chunk_first) / KG) & (NBUF - 1)) * BUF;
         float bq[2][NB];                           // B fragments: this step's and the next one's
 #pragma unroll
         for (int b = 0; b < NB; ++b) bq[0][b] = bsrc[b_off[b]];
@@ -336,16 +353,18 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
     // The loop body has no data-dependent branch around its loads: the prefetches for "the next
     // chunk" are issued in the last iteration too (A from the last chunk again, input from beyond
     // the last channel, which the buffer range check turns into zeros) and simply go unused.
-    const int nsteps = (chunk_hi - chunk_lo + KG - 1) / KG;       // the same for every group: barriers match
+    // Step s reads buffer s and refills buffer s + ahead (both modulo NBUF), which was last read in step
+    // s + ahead - NBUF: before the last barrier in either mode.  What step s + 1 reads was stored in step
+    // s + 1 - ahead, and a barrier lies between the two: after every step, or after every odd one.
     for (int step = 0; step < nsteps; ++step) {
         const int chunk = chunk_first + step * KG;
-        load_chunk(chunk + KG);
+        load_chunk(chunk + ahead * KG);
         if (KG == 1 || chunk < chunk_hi) {                        // wave-uniform
             if (kRagged && nb_wave != PBW) compute_chunk(std::integral_constant<int, kRagged ? PBW - 1 : PBW>{}, chunk);
             else compute_chunk(std::integral_constant<int, PBW>{}, chunk);
         }
-        store_chunk(lds + ((step + 1) & 1) * BUF);
-        __syncthreads();
+        store_chunk(lds + ((step + ahead) & (NBUF - 1)) * BUF);
+        if (!deep || (step & 1)) __syncthreads();
     }
 
     // ---- add the channel groups' partial sums: groups 1.. park theirs in LDS (the staging buffers
