@@ -139,6 +139,14 @@ struct Epilogue {
     bool any() const { return bias != nullptr || relu != 0; }
 };
 
+// Layers of up to four channels (an RGB first layer) have a leaner instantiation of three tile shapes: one channel
+// quad of the only chunk is staged and multiplied instead of four.
+bool lean_applies(const conv_mcmk_desc *d, int ks, int shape, int csplit, bool channels_last, int stride, int row_groups)
+{
+    return d->dtype == CONV_MCMK_F32 && d->c <= 4 && !channels_last && stride == 1 && row_groups == 1 && csplit == 1 &&
+           (ks == 3 || ks == 5 || ks == 7) && (shape == 0 || shape == 3 || shape == 4);
+}
+
 // One launch of the tile kernel: a convolution (ks x ks taps, row_groups = 1) or a plain GEMM
 // (ks = 1 over a 1 x cols image, row_groups row planes of m rows each).
 int launch_tile(const conv_mcmk_desc *d, const Dims &dm, int ks, int shape, int csplit, const void *in,
@@ -163,6 +171,7 @@ int launch_tile(const conv_mcmk_desc *d, const Dims &dm, int ks, int shape, int 
     rq.shape = shape;
     rq.channels_last = channels_last;
     rq.stride = stride;
+    rq.lean = in_c == d->c && lean_applies(d, ks, shape, csplit, channels_last, stride, row_groups);
     rq.stream = st;
     if (csplit > 1) {
         // partial sums are added into the output, so it starts from zero (a fill kernel, not a
@@ -209,8 +218,10 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
     const bool bf16 = d->dtype == CONV_MCMK_BF16;
     // chunks each wave works through (the channel groups of a workgroup share them out)
     const int chunks = ceil_div(ceil_div(ceil_div(d->c, bf16 ? 32 : 16), c.csplit), c.kg);
-    // fp32: 4 MFMAs of 32 cycles per tap and 16-channel chunk; bf16: 1 MFMA of 16 cycles per tap and 32-channel chunk
-    const double steps = (double)chunks * ks * ks * (bf16 ? 0.5 : 4.0);
+    // fp32: 4 MFMAs of 32 cycles per tap and 16-channel chunk (1 in the lean form); bf16: 1 MFMA of 16 cycles per tap
+    // and 32-channel chunk
+    const bool lean = ks == d->k && lean_applies(d, ks, c.shape, c.csplit, channels_last, d->stride, 1);
+    const double steps = (double)chunks * ks * ks * (bf16 ? 0.5 : lean ? 1.0 : 4.0);
     const long long per_cu = (wgs + kNumCU - 1) / kNumCU;
     // workgroups a CU can hold (VGPRs: the bf16 kernels need more than 128 registers, so 8 waves per CU; fp32: the two
     // double-buffered halo tiles of 16 channels in 160 KB of LDS)
@@ -253,7 +264,7 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
     // tile elements a thread stages) and closing write, hidden in part behind the workgroups resident beside it
     // (fitted to all candidates on layers of 1 to 32 chunks; what decides between many small and few large workgroups)
     if (!bf16 && per_cu > 1) {
-        const int slots = ceil_div(16 * halo, 64 * group_waves);
+        const int slots = ceil_div((lean ? 4 : 16) * halo, 64 * group_waves);
         us += (double)(per_cu - 1) * (2.8 + 0.2 * slots) / can_hold;
     }
     // bf16: a microsecond each, six for the sixteen-wave workgroups with channel groups, which share a CU with nobody
@@ -488,9 +499,10 @@ int conv_mcmk_describe_plan(const conv_mcmk_desc *d, int variant, char *buf, siz
     case CONV_MCMK_KN2COL: {
         const Candidate c = choose_fused(d, dm, variant == CONV_MCMK_KN2COL);
         const long long wgs = (long long)d->n * ceil_div(dm.p, c.tw) * ceil_div(dm.q, c.th) * ceil_div(dm.mb, c.wm * c.rb) * c.csplit;
-        snprintf(buf, n, "%s fused %s: tile %dx%d, waves %dx%d, row blocks %d, channel groups %d, channel split %d, %lld workgroups, est %.1f us",
+        const bool lean = lean_applies(d, d->k, c.shape, c.csplit, variant == CONV_MCMK_KN2COL, d->stride, 1);
+        snprintf(buf, n, "%s fused %s: tile %dx%d, waves %dx%d, row blocks %d, channel groups %d, channel split %d, %lld workgroups%s, est %.1f us",
                  variant == CONV_MCMK_KN2COL ? "kn2col" : "kn2row", type, c.th, c.tw, c.wm, c.wp, c.rb, c.kg, c.csplit, wgs,
-                 tile_cost(d, dm, c, d->k, variant == CONV_MCMK_KN2COL));
+                 lean ? ", one channel quad" : "", tile_cost(d, dm, c, d->k, variant == CONV_MCMK_KN2COL));
         break;
     }
     case CONV_MCMK_KN2ROW_2PASS:

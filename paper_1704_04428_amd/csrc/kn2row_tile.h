@@ -48,9 +48,10 @@ struct TileArgs {
     int relu;             // nonzero: negative results are stored as zero (csplit == 1 only)
 };
 
-template <int KS, int TH, int TW, int WM, int WP, int CCH = 16, int KG = 1, int ST = 1>
+template <int KS, int TH, int TW, int WM, int WP, int CCH = 16, int KG = 1, int ST = 1, int VQL = CCH / 4>
 struct TileShape {
     static constexpr int kCC = CCH;                      // channels per chunk, a multiple of 16
+    static constexpr int kSC = 4 * VQL;                  // channels of a chunk that are staged and multiplied
     static constexpr int kGroupThreads = 64 * WM * WP;   // one channel group: WM x WP waves
     static constexpr int kThreads = kGroupThreads * KG;
     static constexpr int kHT = (TH - 1) * ST + KS;       // input rows under a tile of TH output rows
@@ -69,10 +70,10 @@ struct TileShape {
     // fragment touches start 16 banks apart.  Stride 2: the 16 positions of a fragment sit on every
     // second bank, and an odd channel stride puts the next channel on the banks between them.
     static constexpr int kCHS = ST == 1 ? ((kPosStage + 15) / 32) * 32 + 16 : (kPosStage | 1);
-    static constexpr int kBuf = kCC * kCHS;              // words per LDS buffer
+    static constexpr int kBuf = kSC * kCHS;              // words per LDS buffer
     static constexpr int kNPB = (TH * TW + 15) / 16;     // 16-position blocks per tile
     static constexpr int kPBW = (kNPB + WP - 1) / WP;    // blocks per wave
-    static constexpr int kSlots = (kCC * kPosStage + kGroupThreads - 1) / kGroupThreads;
+    static constexpr int kSlots = (kSC * kPosStage + kGroupThreads - 1) / kGroupThreads;
     // LDS buffers per channel group: two (staging one chunk ahead, a barrier per chunk), or four (staging
     // two chunks ahead, a barrier every second chunk) where four buffers for every workgroup that the
     // wave count lets share a compute unit still fit its 160 KB
@@ -94,13 +95,17 @@ struct TileShape {
 //         contraction for layers with too few tiles to fill the chip (small images, deep channels):
 //         no atomics, no zero fill, and -- because group g's waves are rotated by g along the position
 //         axis -- every SIMD ends up with the same number of position blocks.
-template <int KS, int TH, int TW, int WM, int WP, int CCH = 16, bool CL = false, int KG = 1, int ST = 1>
+// VQL: channel quads of a chunk that are staged and multiplied: all CCH / 4 of them, or 1 for layers of up to
+//      four channels (an RGB first layer), whose single chunk would otherwise be three quarters zeros: a
+//      quarter of the loads, the LDS and the products.  The packed kernel is the same.
+template <int KS, int TH, int TW, int WM, int WP, int CCH = 16, bool CL = false, int KG = 1, int ST = 1, int VQL = CCH / 4>
 __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileArgs a)
 {
-    using S = TileShape<KS, TH, TW, WM, WP, CCH, KG, ST>;
+    using S = TileShape<KS, TH, TW, WM, WP, CCH, KG, ST, VQL>;
+    static_assert(VQL == CCH / 4 || (!CL && KG == 1 && CCH == 16), "the lean form exists for [C][H][W] input without channel groups");
     static_assert(CCH % 16 == 0, "a chunk is a whole number of packed 16-channel groups");
     constexpr int NQ = CCH / 16;                   // packed A vectors per tap and chunk
-    constexpr int CC = S::kCC, NT = S::kGroupThreads, WT = S::kWT, POS = S::kPos, POSS = S::kPosStage, CHS = S::kCHS;
+    constexpr int CC = S::kCC, SC = S::kSC, NT = S::kGroupThreads, WT = S::kWT, POS = S::kPos, POSS = S::kPosStage, CHS = S::kCHS;
     constexpr int PBW = S::kPBW, NPB = S::kNPB, SLOTS = S::kSlots, BUF = S::kBuf, NBUF = S::kNBuf;
     // position blocks are dealt evenly to the WP waves: the first REM waves own PBW blocks, the
     // others PBW-1 (all own PBW when the split is exact)
@@ -169,12 +174,12 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
         const int cl = e / POSS, pos = e % POSS;
         const int r = pos / WT, col = pos % WT;
         const int gy = iy0 + r, gx = ix0 + col;
-        const bool used = e < CC * POSS;
+        const bool used = e < SC * POSS;
         const bool inside = used && pos < POS && gy >= 0 && gy < a.h && gx >= 0 && gx < a.w;
         g_off[s] = inside ? (uint32_t)((cl * plane + (size_t)gy * a.w + gx) * sizeof(float)) : 0x80000000u;
         l_off[s] = used ? cl * CHS + pos : -1;          // pos == r * WT + col; beyond POS: the padding, CHS >= POSS
     }
-    static_assert(!kRegular || SLOTS * CSTEP == CC, "regular staging must cover the chunk exactly");
+    static_assert(!kRegular || SLOTS * CSTEP == SC, "regular staging must cover the staged channels exactly");
 
     // channels last: an item is (channel quad, position): one 16-byte load of four consecutive channels
     // (the host requires C to be a multiple of 4, so every quad is aligned and whole), stored as four
@@ -185,7 +190,7 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
     // Offsets are recomputed per chunk (an opaque copy of tid keeps the compiler from
     // hoisting them into more live registers).
     constexpr int QPC = CC / 4;                                   // channel quads per chunk
-    constexpr int QH = QPC / 2;                                   // 64-item groups per 32 positions
+    constexpr int QH = QPC / 2 > 0 ? QPC / 2 : 1;                 // 64-item groups per 32 positions
     constexpr int VITEMS = 64 * QH * ((POS + 31) / 32);
     constexpr int VSLOTS = (VITEMS + NT - 1) / NT;                // items per thread
     auto cl_item = [](int e, int &quad, int &pos) {
@@ -311,7 +316,7 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
     // owns the ragged last share); straight-line code, every LDS offset an immediate.
     auto compute_chunk = [&](auto nb_tag, int chunk) {
         constexpr int NB = decltype(nb_tag)::value;
-        constexpr int VQ = CCH / 4;                // channel quads per chunk
+        constexpr int VQ = VQL;                    // channel quads per chunk
         constexpr int G = T * VQ;                  // steps per chunk: (tap, channel quad)
         const float *bsrc = lds + (((chunk - chunk_first) / KG) & (NBUF - 1)) * BUF;
         float bq[2][NB];                           // B fragments: this step's and the next one's

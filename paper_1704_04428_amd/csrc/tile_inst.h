@@ -15,7 +15,7 @@
 namespace mcmk {
 namespace {
 
-template <int TH, int TW, int WM, int WP, int CCH = 16, bool CL = false, int KG = 1, int ST = 1, int RB = 1>
+template <int TH, int TW, int WM, int WP, int CCH = 16, bool CL = false, int KG = 1, int ST = 1, int RB = 1, int VQL = CCH / 4>
 int launch_shape(const TileRequest &rq)
 {
     TileArgs a = rq.args;
@@ -43,20 +43,20 @@ int launch_shape(const TileRequest &rq)
     hipLaunchKernelGGL((kn2row_tile_bf16<MCMK_KS, TH, TW, WM, WP, CL, ST, RB, KG>), dim3((unsigned)blocks), dim3(S::kThreads * KG),
                        kLds, rq.stream, a);
 #else
-    using S = TileShape<MCMK_KS, TH, TW, WM, WP, CCH, KG, ST>;
+    using S = TileShape<MCMK_KS, TH, TW, WM, WP, CCH, KG, ST, VQL>;
     if (S::kLdsBytes > 65536) {
         // more than 64 KiB of dynamic LDS has to be allowed per kernel, once per device
         static bool allowed[64] = {};
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 1;
         if (!allowed[dev]) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&kn2row_tile_f32<MCMK_KS, TH, TW, WM, WP, CCH, CL, KG, ST>),
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&kn2row_tile_f32<MCMK_KS, TH, TW, WM, WP, CCH, CL, KG, ST, VQL>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::kLdsBytes) != hipSuccess)
                 return 1;
             allowed[dev] = true;
         }
     }
-    hipLaunchKernelGGL((kn2row_tile_f32<MCMK_KS, TH, TW, WM, WP, CCH, CL, KG, ST>), dim3((unsigned)blocks), dim3(S::kThreads),
+    hipLaunchKernelGGL((kn2row_tile_f32<MCMK_KS, TH, TW, WM, WP, CCH, CL, KG, ST, VQL>), dim3((unsigned)blocks), dim3(S::kThreads),
                        S::kLdsBytes, rq.stream, a);
 #endif
     return hipGetLastError() == hipSuccess ? 0 : 1;
@@ -89,6 +89,17 @@ int MCMK_FN(const TileRequest &rq)
         }
     }
     if (rq.stride != 1) return 2;
+#if !MCMK_BF16 && MCMK_KS >= 3 && (MCMK_KS & 1)
+    if (rq.lean) {
+        // up to four channels, [C][H][W] input: one staged channel quad instead of four (kernel sides 3, 5, 7)
+        switch (rq.shape) {
+        case 0: return launch_shape<14, 14, 4, 2, 16, false, 1, 1, 1, 1>(rq);
+        case 3: return launch_shape<16, 16, 4, 2, 16, false, 1, 1, 1, 1>(rq);
+        case 4: return launch_shape<16, 16, 2, 4, 16, false, 1, 1, 1, 1>(rq);
+        default: return 2;
+        }
+    }
+#endif
     if (rq.channels_last) {
         switch (rq.shape) {
         case 0: return launch_shape<14, 14, 4, 2, 16, true>(rq);

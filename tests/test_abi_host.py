@@ -186,6 +186,11 @@ def test_plan_selection_for_benchmark_layers(lib, monkeypatch):
         B.conv_mcmk_describe_plan(B.desc(1, 128, 112, 112, 128, 3, 1), B.KN2ROW)
     # a 1 x 1 kernel on 16 x 16 tiles: one position per staging thread (measured 16.9 us against 18.5 us on 14 x 14 tiles)
     assert "tile 16x16, waves 2x4" in B.conv_mcmk_describe_plan(B.desc(8, 256, 56, 56, 64, 1, 0), B.KN2ROW)
+    # an RGB first layer: the instantiation with one channel quad (fp32, [C][H][W], k = 3 / 5 / 7, unit stride)
+    assert "one channel quad" in B.conv_mcmk_describe_plan(B.desc(8, 3, 224, 224, 64, 7, 3), B.KN2ROW)
+    assert "one channel quad" not in B.conv_mcmk_describe_plan(B.desc(8, 5, 224, 224, 64, 7, 3), B.KN2ROW)
+    assert "one channel quad" not in B.conv_mcmk_describe_plan(B.desc(8, 3, 224, 224, 64, 7, 3, stride=2), B.KN2ROW)
+    assert "one channel quad" not in B.conv_mcmk_describe_plan(B.desc(8, 4, 224, 224, 64, 7, 3), B.KN2COL)
     d = B.desc(1, 8, 10, 10, 8, 3, 1)
     assert "shift-add" in B.conv_mcmk_describe_plan(d, B.KN2ROW_2PASS)
     assert "patch matrix [72 x 100]" in B.conv_mcmk_describe_plan(d, B.IM2COL)
@@ -227,8 +232,8 @@ def test_kernel_register_budget():
     # kernels that sit at the 256-register limit; anything beyond 64 bytes per lane means a loop is spilling
     spilling = {k: v for k, v in usage.items() if v.get("ScratchSize", 0) > 64}
     assert not spilling, spilling
-    wide = [v for k, v in usage.items() if "kn2row_tile_f32ILi3ELi14ELi14ELi4ELi2ELi16E" in k and k.endswith("Li1ELi1EEEvNS_8TileArgsE")]
-    assert len(wide) == 2                                   # unit stride, one channel group: NCHW and channels-last
+    wide = [v for k, v in usage.items() if "kn2row_tile_f32ILi3ELi14ELi14ELi4ELi2ELi16E" in k and k.endswith("Li1ELi1ELi4EEEvNS_8TileArgsE")]
+    assert len(wide) == 2                                   # unit stride, one channel group, all four channel quads: NCHW and channels-last
     assert all(v["VGPRs"] + v.get("AGPRs", 0) <= 128 for v in wide), wide
 
 

@@ -282,6 +282,27 @@ def test_every_tile_shape_of_the_menu(k, pad, dtype, monkeypatch):
     monkeypatch.delenv("CONV_MCMK_TILE")
 
 
+@pytest.mark.parametrize("k,pad", [(3, 1), (5, 2), (7, 3), (3, 0), (7, 6)])
+@pytest.mark.parametrize("c", [1, 2, 3, 4, 5])
+def test_few_channel_layers(c, k, pad, monkeypatch):
+    """Layers of up to four channels run an instantiation of three tile shapes that stages and multiplies one
+    channel quad instead of four (five channels: the general kernels); every such shape against the oracle,
+    integer data so that the comparison is exact."""
+    n, h, w, m = 2, 37, 45, 40
+    I = wl.small_integers(900 + c, n * c * h * w, 0, 8).reshape(n, c, h, w)
+    K = wl.small_integers(901 + k, m * c * k * k, -4, 4).reshape(m, c, k, k)
+    ref, _ = oracle.mcmk(I, K, pad)
+    for index in (None, 0, 3, 4, 1):
+        announce("few channels", c, k, pad, "tile", index)
+        if index is None:
+            monkeypatch.delenv("CONV_MCMK_TILE", raising=False)
+        else:
+            monkeypatch.setenv("CONV_MCMK_TILE", str(index))
+        got = run_variant(B.KN2ROW, I, K, pad)
+        np.testing.assert_array_equal(got.astype(np.float64), ref)
+    monkeypatch.delenv("CONV_MCMK_TILE", raising=False)
+
+
 @pytest.mark.parametrize("case", [
     (1, 3, 600, 500, 8, 7, 3),        # large image, first-layer-like channel count
     (1, 8, 9, 2000, 16, 3, 1),        # very wide, few rows
