@@ -143,8 +143,9 @@ struct Epilogue {
 // quad of the only chunk is staged and multiplied instead of four.
 bool lean_applies(const conv_mcmk_desc *d, int ks, int shape, int csplit, bool channels_last, int stride, int row_groups)
 {
-    return d->dtype == CONV_MCMK_F32 && d->c <= 4 && !channels_last && stride == 1 && row_groups == 1 && csplit == 1 &&
-           (ks == 3 || ks == 5 || ks == 7) && (shape == 0 || shape == 3 || shape == 4);
+    return d->dtype == CONV_MCMK_F32 && d->c <= 4 && !channels_last && row_groups == 1 && csplit == 1 &&
+           (ks == 3 || ks == 5 || ks == 7) &&
+           ((stride == 1 && (shape == 0 || shape == 3 || shape == 4)) || (stride == 2 && (shape == 0 || shape == 1)));
 }
 
 // One launch of the tile kernel: a convolution (ks x ks taps, row_groups = 1) or a plain GEMM

@@ -52,7 +52,7 @@ struct TileRequest {
     int shape;           // index into kTileShapes
     bool channels_last;  // input [n][h][w][c], output [n][q][p][rows] (kn2col); convolution shapes only
     int stride;          // 1, or 2 with a shape index below kStridedShapes
-    bool lean;           // fp32, up to four channels, [C][H][W], unit stride, odd kernel side >= 3, shapes 0 / 3 / 4:
+    bool lean;           // fp32, up to four channels, [C][H][W], odd kernel side >= 3, shapes 0 / 3 / 4 (stride 2: 0 / 1):
                          // the instantiation that stages and multiplies one channel quad per chunk instead of four
     hipStream_t stream;
 };

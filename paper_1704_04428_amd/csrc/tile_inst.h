@@ -76,6 +76,16 @@ int MCMK_FN(const TileRequest &rq)
 {
     if (rq.stride == 2) {
         if (rq.shape < 0 || rq.shape >= kStridedShapes) return 2;
+#if !MCMK_BF16 && MCMK_KS >= 3 && (MCMK_KS & 1)
+        if (rq.lean) {
+            // up to four channels (a strided RGB first layer): one staged channel quad instead of four
+            switch (rq.shape) {
+            case 0: return launch_shape<14, 14, 4, 2, 16, false, 1, 2, 1, 1>(rq);
+            case 1: return launch_shape<14, 14, 2, 4, 16, false, 1, 2, 1, 1>(rq);
+            default: return 2;
+            }
+        }
+#endif
         switch (rq.shape + (rq.channels_last ? kStridedShapes : 0)) {
 #if !MCMK_STRIDED_BF16_NCHW_WIDE_ONLY
         case 0: return launch_shape<14, 14, 4, 2, 16, false, 1, 2>(rq);

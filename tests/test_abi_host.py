@@ -189,7 +189,8 @@ def test_plan_selection_for_benchmark_layers(lib, monkeypatch):
     # an RGB first layer: the instantiation with one channel quad (fp32, [C][H][W], k = 3 / 5 / 7, unit stride)
     assert "one channel quad" in B.conv_mcmk_describe_plan(B.desc(8, 3, 224, 224, 64, 7, 3), B.KN2ROW)
     assert "one channel quad" not in B.conv_mcmk_describe_plan(B.desc(8, 5, 224, 224, 64, 7, 3), B.KN2ROW)
-    assert "one channel quad" not in B.conv_mcmk_describe_plan(B.desc(8, 3, 224, 224, 64, 7, 3, stride=2), B.KN2ROW)
+    assert "one channel quad" in B.conv_mcmk_describe_plan(B.desc(8, 3, 224, 224, 64, 7, 3, stride=2), B.KN2ROW)
+    assert "one channel quad" not in B.conv_mcmk_describe_plan(B.desc(8, 3, 224, 224, 64, 6, 3, stride=2), B.KN2ROW)
     assert "one channel quad" not in B.conv_mcmk_describe_plan(B.desc(8, 4, 224, 224, 64, 7, 3), B.KN2COL)
     d = B.desc(1, 8, 10, 10, 8, 3, 1)
     assert "shift-add" in B.conv_mcmk_describe_plan(d, B.KN2ROW_2PASS)

@@ -300,6 +300,15 @@ def test_few_channel_layers(c, k, pad, monkeypatch):
             monkeypatch.setenv("CONV_MCMK_TILE", str(index))
         got = run_variant(B.KN2ROW, I, K, pad)
         np.testing.assert_array_equal(got.astype(np.float64), ref)
+    ref2, _ = oracle.mcmk(I, K, pad, 2)
+    for index in (None, 0, 1, 2):                 # stride 2: shapes 0 and 1 have the lean form, 2 has not
+        announce("few channels, stride 2", c, k, pad, "tile", index)
+        if index is None:
+            monkeypatch.delenv("CONV_MCMK_TILE", raising=False)
+        else:
+            monkeypatch.setenv("CONV_MCMK_TILE", str(index))
+        got = run_variant(B.KN2ROW, I, K, pad, stride=2)
+        np.testing.assert_array_equal(got.astype(np.float64), ref2)
     monkeypatch.delenv("CONV_MCMK_TILE", raising=False)
 
 
