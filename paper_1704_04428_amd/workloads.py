@@ -124,6 +124,9 @@ GENERALISED_LAYERS = {
     "gen_vgg56_stride2": Layer("gen_vgg56_stride2", 8, 256, 56, 56, 256, 3, 1, "u01", "he", _SEED_BASE + 16 * 8, 2),
     "gen_vgg56_k4": Layer("gen_vgg56_k4", 8, 256, 56, 56, 256, 4, 2, "u01", "he", _SEED_BASE + 16 * 9),
     "gen_vgg56_1x1": Layer("gen_vgg56_1x1", 8, 256, 56, 56, 256, 1, 0, "u01", "he", _SEED_BASE + 16 * 10),
+    # three-channel first layers of the networks the paper takes its layers from: 3 x 3 (VGG) and 7 x 7 with stride 2
+    "gen_rgb224_k3": Layer("gen_rgb224_k3", 8, 3, 224, 224, 64, 3, 1, "u01", "he", _SEED_BASE + 16 * 11),
+    "gen_rgb224_k7_stride2": Layer("gen_rgb224_k7_stride2", 8, 3, 224, 224, 64, 7, 3, "u01", "he", _SEED_BASE + 16 * 12, 2),
 }
 
 
