@@ -277,6 +277,9 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
         const double burst = (double)d->n * d->m * dm.q * dm.p * 4.0 / 25.7e6;     // relative to the layer it was measured on
         us += 4.0 * (burst < 1.0 ? burst : 1.0);
     }
+    // with one channel quad there is so little matrix work that the output write shows: half of it at 5 TB/s
+    // when the tile rows are whole 64-byte lines, at 3.3 TB/s when they are not (fitted to the first-layer shapes)
+    if (lean) us += 0.5 * 4.0 * (double)d->n * d->m * dm.q * dm.p / (c.tw % 16 == 0 ? 5.0e6 : 3.3e6);
     if (c.csplit > 1) us += 3.0 + (bf16 ? 1.4 : 2.0) * (double)d->n * d->m * dm.q * dm.p * 6.25e-6;
     if (c.kg > 1) us += 1.5;                                            // the closing exchange through LDS
     return us;
