@@ -282,6 +282,27 @@ def test_every_tile_shape_of_the_menu(k, pad, dtype, monkeypatch):
     monkeypatch.delenv("CONV_MCMK_TILE")
 
 
+@pytest.mark.parametrize("c", [128, 144, 176, 272])
+def test_layers_deep_enough_for_a_barrier_every_second_chunk(c, monkeypatch):
+    """From eight 16-channel chunks on, the fp32 shapes that have four LDS buffers stage two chunks ahead and meet
+    at a barrier after every second chunk: even and odd chunk counts (8, 9, 11, 17), with and without the two-way
+    channel split (which hands each half 8 and 9 chunks of the 17), every such shape; integer data, exact."""
+    n, h, w, m, k, pad = 1, 30, 33, 40, 3, 1
+    I = wl.small_integers(950 + c, n * c * h * w, 0, 4).reshape(n, c, h, w)
+    K = wl.small_integers(951 + c, m * c * k * k, -3, 3).reshape(m, c, k, k)
+    ref, _ = oracle.mcmk(I, K, pad)
+    for index in (None, 0, 1, 18, 19, 7, 8, 25):
+        for variant in (B.KN2ROW, B.KN2COL):
+            announce("deep", c, "tile", index, "variant", variant)
+            if index is None:
+                monkeypatch.delenv("CONV_MCMK_TILE", raising=False)
+            else:
+                monkeypatch.setenv("CONV_MCMK_TILE", str(index))
+            got = run_variant(variant, I, K, pad)
+            np.testing.assert_array_equal(got.astype(np.float64), ref)
+    monkeypatch.delenv("CONV_MCMK_TILE", raising=False)
+
+
 @pytest.mark.parametrize("k,pad", [(3, 1), (5, 2), (7, 3), (3, 0), (7, 6)])
 @pytest.mark.parametrize("c", [1, 2, 3, 4, 5])
 def test_few_channel_layers(c, k, pad, monkeypatch):
