@@ -35,6 +35,9 @@ def test_benchmark_layers_match_the_stated_configurations():
         assert (L.q, L.p) == (h, w) and L.flops == flops, name
     s2 = wl.GENERALISED_LAYERS["gen_vgg56_stride2"]
     assert (s2.q, s2.p, s2.stride) == (28, 28, 2) and s2.flops == 29_595_009_024 // 4
+    rgb = wl.GENERALISED_LAYERS["gen_rgb224_k7_stride2"]
+    assert (rgb.c, rgb.q, rgb.p, rgb.stride) == (3, 112, 112, 2) and rgb.flops == 2 * 8 * 64 * 3 * 49 * 112 * 112
+    assert wl.GENERALISED_LAYERS["gen_rgb224_k3"].flops == 2 * 8 * 64 * 3 * 9 * 224 * 224
 
 
 def test_inputs_follow_the_stated_distributions():

@@ -189,6 +189,8 @@ def test_one_by_one_entry_point_refuses_larger_kernels():
     (2, 128, 28, 28, 128, 3, 1, 1),
     (1, 16, 32, 32, 16, 3, 1, 1),
     (1, 8, 64, 64, 8, 8, 4, 3),
+    (2, 3, 224, 224, 64, 7, 3, 2),       # an RGB first layer, 7 x 7 with stride 2: the one-channel-quad kernels
+    (2, 3, 112, 112, 32, 3, 1, 1),
 ])
 def test_selected_variant_is_correct_and_near_the_fastest(case):
     """conv_mcmk_select + Plan.auto: the chosen variant gives the oracle's result, and none of the
