@@ -147,10 +147,13 @@ __global__ void im2row_build_kernel(const T *__restrict__ I, T *__restrict__ row
 // Shift-add post pass of section III-A: O[n][m][q][p] = sum over taps of T[n][t*M+m][s*q+di][s*p+dj]
 // (s = stride, 1 in the paper), offsets taken in the 2-D plane; positions outside the H x W plane are discarded.
 // One thread owns VEC consecutive columns of one output row (VEC > 1 needs P % VEC == 0).
-template <int VEC>
+// KS > 0: the kernel side is a compile-time constant (the tap loops unroll, so every load of the k*k planes is in
+// flight before the first add: the pass is a pure memory sweep and waits for nothing else); KS == 0: any side.
+template <int VEC, int KS>
 __global__ void shift_add_f32_kernel(const float *__restrict__ T, float *__restrict__ O,
-                                     int n, int m, int h, int w, int k, int pad, int stride, int q, int p)
+                                     int n, int m, int h, int w, int k_arg, int pad, int stride, int q, int p)
 {
+    const int k = KS > 0 ? KS : k_arg;
     struct alignas(sizeof(float) * VEC) Pack { float v[VEC]; };
     const int pv = p / VEC;
     const size_t hw = (size_t)h * w;
@@ -167,9 +170,11 @@ __global__ void shift_add_f32_kernel(const float *__restrict__ T, float *__restr
         Pack acc;
 #pragma unroll
         for (int u = 0; u < VEC; ++u) acc.v[u] = 0.0f;
+#pragma unroll
         for (int i = 0; i < k; ++i) {
             const int y = oq * stride - pad + i;
             if (y < 0 || y >= h) continue;
+#pragma unroll
             for (int j = 0; j < k; ++j) {
                 const float *row = Tn + ((size_t)(i * k + j) * m + im) * hw + (size_t)y * w;
                 const int x0 = xg * VEC * stride - pad + j;

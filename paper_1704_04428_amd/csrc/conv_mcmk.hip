@@ -651,12 +651,15 @@ int conv_mcmk_kn2row_2pass(const conv_mcmk_desc *d, const void *I_dev, const voi
     // pass 2: shift-add of the k*k planes
     const int vec = dm.p % 4 == 0 ? 4 : 1;
     const size_t total = (size_t)d->n * d->m * dm.q * (dm.p / vec);
-    if (vec == 4)
-        hipLaunchKernelGGL(shift_add_f32_kernel<4>, dim3(grid_for(total, 256)), dim3(256), 0, st, T,
-                           static_cast<float *>(O_dev), d->n, d->m, d->h, d->w, d->k, d->pad, d->stride, dm.q, dm.p);
-    else
-        hipLaunchKernelGGL(shift_add_f32_kernel<1>, dim3(grid_for(total, 256)), dim3(256), 0, st, T,
-                           static_cast<float *>(O_dev), d->n, d->m, d->h, d->w, d->k, d->pad, d->stride, dm.q, dm.p);
+    auto launch = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, T, static_cast<float *>(O_dev), d->n, d->m,
+                           d->h, d->w, d->k, d->pad, d->stride, dm.q, dm.p);
+    };
+    if (vec == 4 && d->k == 3) launch(shift_add_f32_kernel<4, 3>);
+    else if (vec == 4 && d->k == 5) launch(shift_add_f32_kernel<4, 5>);
+    else if (vec == 4) launch(shift_add_f32_kernel<4, 0>);
+    else if (d->k == 3) launch(shift_add_f32_kernel<1, 3>);
+    else launch(shift_add_f32_kernel<1, 0>);
     return launch_status();
 }
 
