@@ -267,7 +267,10 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
     // ---- A fragments: one f32x4 per lane per tap covers a 16-channel chunk.  They are fetched
     // straight from global memory kDepth taps ahead of use and handed down a short register queue.
     constexpr int T = KS * KS;                   // taps per chunk
-    constexpr int kDepth = 2;
+    // taps: the fragment has to cross the L2's latency while the wave works through kDepth taps of PBW blocks
+    // each, so waves with few blocks look further ahead (a quarter tile's tap is four products, 128 cycles)
+    // (not with a 1 x 1 kernel, whose next taps are the next chunks, nor with channel groups: both measured slower)
+    constexpr int kDepth = (PBW >= 6 || KG > 1 || T < 4) ? 2 : PBW >= 3 ? 3 : 8;
     const int nchunks = (a.cg + NQ - 1) / NQ;
     const int chunk_lo = (int)((long long)nchunks * part / a.csplit);
     const int chunk_hi = (int)((long long)nchunks * (part + 1) / a.csplit);
