@@ -11,9 +11,11 @@
 // Operands
 //   A (kernel): pre-ordered in global memory exactly as v_mfma_f32_16x16x4_f32 takes it, so a wave
 //     loads its fragments with one coalesced 16-byte load per lane and tap, straight into VGPRs
-//     (double-buffered one tap row ahead).  No LDS traffic for A.
+//     (a register queue two to eight taps deep, the deeper the fewer position blocks a wave has).
+//     No LDS traffic for A.
 //   B (input): a halo tile of 16 channels x (TH+KS-1) x (TW+KS-1), zero-filled outside the image,
-//     staged global -> registers -> LDS, double-buffered one 16-channel chunk ahead.
+//     staged global -> registers -> LDS one 16-channel chunk ahead through two buffers, or two
+//     chunks ahead through four with a barrier after every second chunk.
 //     Each lane keeps the LDS address of its output position; a tap is an immediate offset.
 //
 // MFMA 16x16x4 f32 layouts (lane l of 64):  A[row l%16][k l/16],  B[k l/16][col l%16],
