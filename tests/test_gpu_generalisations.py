@@ -111,7 +111,8 @@ def test_every_strided_tile_shape(k, pad, dtype, monkeypatch):
 @pytest.mark.parametrize("variant", [B.KN2ROW, B.KN2COL])
 @pytest.mark.parametrize("dtype", [B.F32, B.BF16])
 @pytest.mark.parametrize("case", [(2, 24, 17, 19, 35, 3, 1, 1), (1, 16, 30, 31, 20, 5, 2, 2), (1, 40, 14, 14, 33, 1, 0, 1),
-                                  (2, 512, 14, 14, 64, 3, 1, 1)])          # the last: a shape whose plain call splits the channels
+                                  (2, 512, 14, 14, 64, 3, 1, 1),           # a shape whose plain call splits the channels
+                                  (2, 3, 30, 31, 20, 3, 1, 1), (1, 4, 40, 33, 24, 7, 3, 2)])   # few channels: one channel quad
 def test_bias_and_rectifier_epilogue(variant, dtype, case):
     announce("epilogue", variant, dtype, case)
     I, K = _inputs(case, 3400 + sum(case))
