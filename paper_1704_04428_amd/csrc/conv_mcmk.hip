@@ -255,6 +255,9 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
     // bf16: a wave has one chunk of staging loads in flight, so a workgroup cannot finish a chunk faster than
     // a round trip to memory (0.2 us and more), however little matrix work it holds
     if (bf16 && us < per_cu * chunks * 0.2) us = per_cu * chunks * 0.2;
+    // fp32 chunks are half as long; the floor shows on 1 x 1 layers with hundreds of channels on small images
+    // (workgroups that share a CU walk their chains side by side)
+    if (!bf16 && us < ceil_div(per_cu, can_hold) * chunks * 0.19) us = ceil_div(per_cu, can_hold) * chunks * 0.19;
     // staging-heavy cases: a 1 x 1 kernel uses every staged value once instead of k*k times, a
     // strided tile stages four input values per output position (both measured)
     // (less so for the 16 x 16 tile, whose 256 positions per channel give every thread one position to stage)
