@@ -217,6 +217,9 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
         simd_sum += simd_blocks[i];
     }
     const bool bf16 = d->dtype == CONV_MCMK_BF16;
+    // the bf16 constants come in two sets: the [C][H][W] input is gathered in two-byte pairs and the [M][Q][P]
+    // output written in tile rows; channels last, both are 16-byte accesses (each set fitted to its own sweep)
+    const bool cl16 = bf16 && channels_last;
     // chunks each wave works through (the channel groups of a workgroup share them out)
     const int chunks = ceil_div(ceil_div(ceil_div(d->c, bf16 ? 32 : 16), c.csplit), c.kg);
     // fp32: 4 MFMAs of 32 cycles per tap and 16-channel chunk (1 in the lean form); bf16: 1 MFMA of 16 cycles per tap
@@ -238,13 +241,14 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
     double pipe_use = waves_per_simd >= 2.0 ? 0.9 : 0.7;
     // bf16: the product is four times shorter than the fp32 one while a B fragment is four times
     // larger, so LDS reads, operand loads and the per-chunk hand-over weigh more; measured slopes over
-    // the channel count give 48 % of the pipe with one row block per wave and 59 % with two
+    // the channel count give about half of the pipe (B fragments of 1 KB per product saturate the LDS port when
+    // a wave has one row block; the reuse factors below carry the difference)
     if (bf16) {
-        pipe_use *= c.rb > 1 ? 0.65 : 0.60;
+        pipe_use *= 0.60;
         // an A fragment (1 KB from L1/L2 per wave) is reused for the wave's position blocks, the staged
         // tile for the workgroup's rows: few blocks per wave or few rows per workgroup leave the
         // load path, not the matrix pipe, as the limit (fitted to the sweep of all shapes)
-        const double reuse_a = 0.5 + 0.07 * ceil_div(npb, c.wp);
+        const double reuse_a = (cl16 ? 0.8 : 0.4) + 0.07 * ceil_div(npb, c.wp);
         const double rows = 16.0 * c.wm * c.rb;
         const double reuse_b = rows / (rows + 16.0) / 0.8;
         pipe_use *= (reuse_a < 1.1 ? reuse_a : 1.1) * (reuse_b < 1.0 ? reuse_b : 1.0);
@@ -253,37 +257,42 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
     const double blocks = (!bf16 && held >= 2) ? 0.5 * simd_load + 0.125 * simd_sum : (double)simd_load;
     double us = (double)per_cu * blocks * steps * 0.0139 / pipe_use;
     // bf16: a wave has one chunk of staging loads in flight, so a workgroup cannot finish a chunk faster than
-    // a round trip to memory (0.2 us and more), however little matrix work it holds
-    if (bf16 && us < per_cu * chunks * 0.2) us = per_cu * chunks * 0.2;
+    // a round trip to memory allows, however little matrix work it holds
+    if (bf16 && us < ceil_div(per_cu, can_hold) * chunks * (cl16 ? 0.6 : 0.1)) us = ceil_div(per_cu, can_hold) * chunks * (cl16 ? 0.6 : 0.1);
     // fp32 chunks are half as long; the floor shows on 1 x 1 layers with hundreds of channels on small images
     // (workgroups that share a CU walk their chains side by side)
     if (!bf16 && us < ceil_div(per_cu, can_hold) * chunks * 0.19) us = ceil_div(per_cu, can_hold) * chunks * 0.19;
     // staging-heavy cases: a 1 x 1 kernel uses every staged value once instead of k*k times, a
     // strided tile stages four input values per output position (both measured)
     // (less so for the 16 x 16 tile, whose 256 positions per channel give every thread one position to stage)
-    if (ks == 1 && c.shape != kGemmShape) us *= c.th * c.tw == 256 ? (bf16 ? 1.2 : 1.1) : (bf16 ? 1.6 : 1.35);
+    if (ks == 1 && c.shape != kGemmShape) us *= c.th * c.tw == 256 ? (cl16 ? 1.2 : bf16 ? 1.4 : 1.1) : (cl16 ? 1.2 : bf16 ? 1.6 : 1.5);
     if (d->stride == 2) us *= 1.25;
-    us += 6.0;                       // launch, first loads, output write
-    // every further workgroup a CU works through brings its own prologue (staging plan, first tile: grows with the
-    // tile elements a thread stages) and closing write, hidden in part behind the workgroups resident beside it
-    // (fitted to all candidates on layers of 1 to 32 chunks; what decides between many small and few large workgroups)
-    if (!bf16 && per_cu > 1) {
-        const int slots = ceil_div((lean ? 4 : 16) * halo, 64 * group_waves);
-        us += (double)(per_cu - 1) * (2.8 + 0.2 * slots) / can_hold;
-    }
-    // bf16: a microsecond each, six for the sixteen-wave workgroups with channel groups, which share a CU with nobody
-    // (fitted the same way, 230 candidate runs on ten layers)
-    if (bf16 && per_cu > 1) us += (double)(per_cu - 1) * (waves == 16 ? 6.0 : 1.0);
-    // [M][Q][P] output of a bf16 call: every workgroup writes at the same time at the end, and rows of 14
-    // floats make partial cache lines of that burst (measured 17 k cycles against 8 k with whole image rows)
-    if (bf16 && !channels_last && c.tw < 28) {
-        const double burst = (double)d->n * d->m * dm.q * dm.p * 4.0 / 25.7e6;     // relative to the layer it was measured on
-        us += 4.0 * (burst < 1.0 ? burst : 1.0);
-    }
+    // bf16: staging the halo tile is serial with the matrix work of a workgroup that has a CU to itself
+    if (bf16) us += (double)per_cu * chunks * halo * c.kg / waves * (0.05 / 64.0);
+    us += cl16 ? 6.0 : 5.0;          // launch, first loads, output write
+    // fp32: every workgroup stages its halo tile of every channel, so workgroups of few rows re-read the input once
+    // per group of rows (from L2 when the rows of one tile run side by side, 0.04 us per MB; tile rows that are no
+    // whole 64-byte lines cost a fifth more): what decides between many small and few large workgroups, and what
+    // a 1 x 1 layer on a large image is bound by (2 x 768 x 224 x 224, M 128: 16 rows per workgroup 287 us, 64 rows 212 us)
+    if (!bf16)
+        us += 0.04 * (double)wgs * halo * ((double)d->c / c.csplit) * 4.0e-6 * ((c.tw % 16 == 0 || c.tw >= 28) ? 1.0 : 1.2);
+    // every further workgroup a CU works through brings its own prologue and closing write, hidden in part behind
+    // the workgroups resident beside it (fitted, like the other fp32 constants, to 2,246 timed candidates on 138 layers)
+    if (!bf16 && per_cu > 1) us += (double)(per_cu - 1) * 2.8 / can_hold;
+    // bf16: half a microsecond each, five for the sixteen-wave workgroups with channel groups, which share a CU with
+    // nobody (fitted, like the other bf16 constants, to 8,400 timed candidates on 450 layers, either layout)
+    if (bf16 && per_cu > 1)
+        us += (double)(per_cu - 1) * (cl16 ? (waves == 16 ? 4.0 : can_hold == 1 ? 2.0 : 1.0) : waves == 16 ? 3.6 : can_hold == 1 ? 0.5 : 0.6);
+    // [M][Q][P] output of a bf16 call: tile rows of 14 or 7 floats are partial cache lines, and with so little
+    // matrix time per output the write shows (0.2 us per MB; tiles 16 wide or whole image rows: nothing)
+    const double out_mb = (double)d->n * d->m * dm.q * dm.p * 4.0e-6;
+    const bool partial_lines = !channels_last && c.tw % 16 != 0 && c.tw < 28;
+    if (bf16 && partial_lines) us += 0.2 * out_mb;
     // with one channel quad there is so little matrix work that the output write shows: half of it at 5 TB/s
     // when the tile rows are whole 64-byte lines, at 3.3 TB/s when they are not (fitted to the first-layer shapes)
     if (lean) us += 0.5 * 4.0 * (double)d->n * d->m * dm.q * dm.p / (c.tw % 16 == 0 ? 5.0e6 : 3.3e6);
-    if (c.csplit > 1) us += 3.0 + (bf16 ? 1.4 : 2.0) * (double)d->n * d->m * dm.q * dm.p * 6.25e-6;
+    // the zero fill and two atomic adds per output: per MB of output ([M][Q][P]: tile rows of whole or partial lines)
+    if (c.csplit > 1) us += 3.0 + (channels_last ? (bf16 ? 3.5 : 3.125) : partial_lines ? (bf16 ? 3.5 : 2.2) : 1.5) * out_mb;
     if (c.kg > 1) us += 1.5;                                            // the closing exchange through LDS
     return us;
 }
@@ -351,6 +360,9 @@ Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_la
             // tiles would not fit the 160 KB of LDS) and are an alternative to, not a partner of, the
             // two-way split
             if (c.kg > 1 && (cs > 1 || d->k > 3)) continue;
+            // nor for a 1 x 1 kernel, whose chunks are too short to pay for the closing exchange (never the fastest
+            // candidate on any 1 x 1 layer timed, either precision)
+            if (c.kg > 1 && d->k == 1) continue;
             if (d->stride > 1 && sh >= kStridedShapes) continue;       // strided input tiles: 14 x 14 outputs only
             if (epilogue && cs > 1) continue;                          // partial sums cannot take the epilogue
             // strided bf16 tiles gathered from [C][H][W] with a kernel side of 5 or more exist for the
