@@ -174,7 +174,7 @@ def cpu_baseline(L, I, K, budget_s=12.0, max_passes=40):
     import oracle
     passes, t0 = 0, time.perf_counter()
     while True:
-        oracle.mcmk(I, K, L.pad)
+        oracle.mcmk(I, K, L.pad, L.stride)
         passes += 1
         dt = time.perf_counter() - t0
         if dt >= budget_s or passes >= max_passes:
@@ -213,12 +213,15 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     B.lib()
-    L = wl.LAYERS[args.workload]
+    layers = {**wl.LAYERS, **wl.GENERALISED_LAYERS}
+    if args.workload not in layers:
+        sys.exit("bench.py: unknown workload %r (known: %s)" % (args.workload, ", ".join(layers)))
+    L = layers[args.workload]
     dev = torch.device("cuda:0")
     I, K = wl.make_input(L), wl.make_kernel(L)
     I_dev, K_dev = torch.from_numpy(I).to(dev), torch.from_numpy(K).to(dev)
     dtype = B.BF16 if args.dtype == "bf16" else B.F32
-    d = B.desc(L.n, L.c, L.h, L.w, L.m, L.k, L.pad, 1, dtype)
+    d = B.desc(L.n, L.c, L.h, L.w, L.m, L.k, L.pad, L.stride, dtype)
     plan = B.Plan(d, B.VARIANTS[args.variant], K_dev)   # re-orders the kernel once, outside the timed region
     I_run = I_dev
     if dtype == B.BF16:
@@ -246,7 +249,7 @@ def main():
     out_nmqp = plan.out.permute(0, 3, 1, 2) if channels_last else plan.out
     got = out_nmqp.cpu().numpy()[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]].astype(np.float64)
     import oracle
-    ref, absref = oracle.mcmk_at(I, K, L.pad, pts)
+    ref, absref = oracle.mcmk_at(I, K, L.pad, pts, L.stride)
     worst = float(np.max(np.abs(got - ref) / np.maximum(absref, 1e-30)))
     if not worst <= (1e-2 if dtype == B.BF16 else 1e-4):
         sys.exit(f"bench.py: output fails parity (worst error {worst:.3e} of sum|K||I|)")
@@ -267,7 +270,7 @@ def main():
         "dtype": args.dtype,
         "data": "synthetic",
         "config": {"workload": L.name, "n": L.n, "c": L.c, "h": L.h, "w": L.w, "m": L.m, "k": L.k,
-                   "pad": L.pad, "variant": args.variant + (" (fused shift-add)" if args.variant == "kn2row" else ""),
+                   "pad": L.pad, "stride": L.stride, "variant": args.variant + (" (fused shift-add)" if args.variant == "kn2row" else ""),
                    "flops_per_step": L.flops, "plan": B.conv_mcmk_describe_plan(d, B.VARIANTS[args.variant])},
         "roofline": {"bound": "mfma", "achieved": round(achieved_tflops, 3), "peak": peak,
                      "unit": "TFLOP/s", "frac": round(achieved_tflops / peak, 4),
