@@ -137,10 +137,15 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
         const int per_xcd = gridDim.x / kXcds;
         if (bid < per_xcd * kXcds) bid = (bid % kXcds) * per_xcd + bid / kXcds;
     }
-    const int part = bid % a.csplit;   bid /= a.csplit;
-    const int rt = bid % a.row_tiles;  bid /= a.row_tiles;
-    const int tx = bid % a.tiles_x;    bid /= a.tiles_x;
-    const int ty = bid % a.tiles_y;    bid /= a.tiles_y;
+    // (unsigned: a division by a launch constant is thirty-odd dependent scalar instructions, and the signed
+    // form adds the sign handling on top)
+    unsigned ubid = (unsigned)bid;
+    int part = 0;
+    if (a.csplit > 1) { part = (int)(ubid % (unsigned)a.csplit);  ubid /= (unsigned)a.csplit; }
+    const int rt = (int)(ubid % (unsigned)a.row_tiles);  ubid /= (unsigned)a.row_tiles;
+    const int tx = (int)(ubid % (unsigned)a.tiles_x);    ubid /= (unsigned)a.tiles_x;
+    const int ty = (int)(ubid % (unsigned)a.tiles_y);    ubid /= (unsigned)a.tiles_y;
+    bid = (int)ubid;
     const int img = bid;
     const int x0 = tx * TW, y0 = ty * TH;                         // first output position of the tile
     const int ix0 = x0 * ST - a.pad, iy0 = y0 * ST - a.pad;       // input position under halo-tile element (0, 0)
@@ -149,8 +154,9 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
     int rb = rt * WM + wm;                       // this wave's 16-row block
     const bool rb_valid = rb < total_rb;
     if (!rb_valid) rb = total_rb - 1;            // keep loads in bounds; nothing is stored
-    const int grp = rb / a.mb_per_group;         // row group (tap index when rows are (tap, m))
-    const int mbi = rb % a.mb_per_group;
+    // row group (tap index when rows are (tap, m)): a convolution has one
+    const int grp = a.row_groups > 1 ? (int)((unsigned)rb / (unsigned)a.mb_per_group) : 0;
+    const int mbi = rb - grp * a.mb_per_group;
 
     // ---- staging plan: element e = tid + s*NT of the [CC][POS] halo tile.
     // The image is read through a raw buffer descriptor whose range check returns 0 for any offset
@@ -274,8 +280,9 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
     // (not with a 1 x 1 kernel, whose next taps are the next chunks, nor with channel groups: both measured slower)
     constexpr int kDepth = (PBW >= 6 || KG > 1 || T < 4) ? 2 : PBW >= 3 ? 3 : 8;
     const int nchunks = (a.cg + NQ - 1) / NQ;
-    const int chunk_lo = (int)((long long)nchunks * part / a.csplit);
-    const int chunk_hi = (int)((long long)nchunks * (part + 1) / a.csplit);
+    // this part's share of the chunks (nchunks * csplit stays far below 2^31: no 64-bit division)
+    const int chunk_lo = a.csplit > 1 ? (int)((unsigned)(nchunks * part) / (unsigned)a.csplit) : 0;
+    const int chunk_hi = a.csplit > 1 ? (int)((unsigned)(nchunks * (part + 1)) / (unsigned)a.csplit) : nchunks;
     const f32x4 *apk = reinterpret_cast<const f32x4 *>(a.apk);
     struct AFrag { f32x4 q[NQ]; };
     auto load_a = [&](int chunk, int t) {

@@ -96,10 +96,15 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_bf16(const Tile
         const int per_xcd = gridDim.x / kXcds;
         if (bid < per_xcd * kXcds) bid = (bid % kXcds) * per_xcd + bid / kXcds;
     }
-    const int part = bid % a.csplit;   bid /= a.csplit;
-    const int rt = bid % a.row_tiles;  bid /= a.row_tiles;
-    const int tx = bid % a.tiles_x;    bid /= a.tiles_x;
-    const int ty = bid % a.tiles_y;    bid /= a.tiles_y;
+    // (unsigned: a division by a launch constant is thirty-odd dependent scalar instructions, and the signed
+    // form adds the sign handling on top)
+    unsigned ubid = (unsigned)bid;
+    int part = 0;
+    if (a.csplit > 1) { part = (int)(ubid % (unsigned)a.csplit);  ubid /= (unsigned)a.csplit; }
+    const int rt = (int)(ubid % (unsigned)a.row_tiles);  ubid /= (unsigned)a.row_tiles;
+    const int tx = (int)(ubid % (unsigned)a.tiles_x);    ubid /= (unsigned)a.tiles_x;
+    const int ty = (int)(ubid % (unsigned)a.tiles_y);    ubid /= (unsigned)a.tiles_y;
+    bid = (int)ubid;
     const int img = bid;
     const int x0 = tx * TW, y0 = ty * TH;                         // first output position of the tile
     const int ix0 = x0 * ST - a.pad, iy0 = y0 * ST - a.pad;       // input position under halo-tile element (0, 0)
@@ -112,8 +117,8 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_bf16(const Tile
         int rb = (rt * WM + wm) * RB + r;
         rb_valid[r] = rb < total_rb;
         if (!rb_valid[r]) rb = total_rb - 1;     // keep loads in bounds; nothing is stored
-        grp[r] = rb / a.mb_per_group;
-        mbi[r] = rb % a.mb_per_group;
+        grp[r] = a.row_groups > 1 ? (int)((unsigned)rb / (unsigned)a.mb_per_group) : 0;
+        mbi[r] = rb - grp[r] * a.mb_per_group;
     }
 
     // ---- staging plan for [C][H][W] input.  The tile wants 8 channels of one position side by side,
@@ -259,8 +264,9 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_bf16(const Tile
     constexpr int D = KS;
     static_assert(T % D == 0, "ring slots must be static");
     const int nchunks = a.cg;
-    const int chunk_lo = (int)((long long)nchunks * part / a.csplit);
-    const int chunk_hi = (int)((long long)nchunks * (part + 1) / a.csplit);
+    // this part's share of the chunks (nchunks * csplit stays far below 2^31: no 64-bit division)
+    const int chunk_lo = a.csplit > 1 ? (int)((unsigned)(nchunks * part) / (unsigned)a.csplit) : 0;
+    const int chunk_hi = a.csplit > 1 ? (int)((unsigned)(nchunks * (part + 1)) / (unsigned)a.csplit) : nchunks;
     const u32x4 *apk = reinterpret_cast<const u32x4 *>(a.apk);
     struct AFrag { u32x4 r[RB]; };
     auto load_a = [&](int chunk, int t) {
