@@ -185,7 +185,8 @@ int launch_tile(const conv_mcmk_desc *d, const Dims &dm, int ks, int shape, int 
 }
 
 // Estimated run time of a candidate in microseconds; the constants were fitted to measurements of
-// every candidate on the benchmark layers.
+// every candidate on the benchmark layers, the layers of the networks the paper draws from and several hundred
+// random layers per precision and layout.
 //   - a block-step is one 16x16x4 MFMA, 32 cycles of a SIMD's matrix pipe (13.9 ns at 2.3 GHz);
 //   - a workgroup's waves are dealt round-robin to the 4 SIMDs, its time is that of the SIMD with
 //     the most position blocks; the busiest CU runs ceil(workgroups / 256) of them;
