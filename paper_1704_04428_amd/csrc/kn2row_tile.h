@@ -183,8 +183,11 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
         const int r = pos / WT, col = pos % WT;
         const int gy = iy0 + r, gx = ix0 + col;
         const bool used = e < SC * POSS;
-        const bool inside = used && pos < POS && gy >= 0 && gy < a.h && gx >= 0 && gx < a.w;
-        g_off[s] = inside ? (uint32_t)((cl * plane + (size_t)gy * a.w + gx) * sizeof(float)) : 0x80000000u;
+        // (unsigned compares fold the two-sided range checks; bitwise and 32-bit, so that the compiler selects
+        // instead of branching around a 64-bit product: an image has fewer than 2^29 elements)
+        const bool inside = used & (pos < POS) & ((unsigned)gy < (unsigned)a.h) & ((unsigned)gx < (unsigned)a.w);
+        const uint32_t elem = (uint32_t)cl * (uint32_t)plane + (uint32_t)gy * (uint32_t)a.w + (uint32_t)gx;
+        g_off[s] = inside ? elem * (uint32_t)sizeof(float) : 0x80000000u;
         l_off[s] = used ? cl * CHS + pos : -1;          // pos == r * WT + col; beyond POS: the padding, CHS >= POSS
     }
     static_assert(!kRegular || SLOTS * CSTEP == SC, "regular staging must cover the staged channels exactly");
