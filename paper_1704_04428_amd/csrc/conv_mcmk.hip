@@ -230,7 +230,8 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
     const long long per_cu = (wgs + kNumCU - 1) / kNumCU;
     // workgroups a CU can hold (VGPRs: the bf16 kernels need more than 128 registers, so 8 waves per CU; fp32: the two
     // double-buffered halo tiles of 16 channels in 160 KB of LDS)
-    int can_hold = c.kg > 1 ? 1 : (bf16 ? 8 : 16) / waves;
+    int can_hold = (bf16 ? 8 : 16) / waves;        // sixteen-wave workgroups (channel groups, tile pairs): one
+    if (can_hold < 1) can_hold = 1;
     const int halo = ((c.th - 1) * d->stride + ks) * ((c.tw - 1) * d->stride + ks);
     if (!bf16) {
         const int fit = 163840 / (2 * c.kg * 16 * (((halo + 15) / 32) * 32 + 16) * 4);
@@ -294,13 +295,14 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
     if (lean) us += 0.5 * 4.0 * (double)d->n * d->m * dm.q * dm.p / (c.tw % 16 == 0 ? 5.0e6 : 3.3e6);
     // the zero fill and two atomic adds per output: per MB of output ([M][Q][P]: tile rows of whole or partial lines)
     if (c.csplit > 1) us += 3.0 + (channels_last ? (bf16 ? 3.5 : 3.125) : partial_lines ? (bf16 ? 3.5 : 2.2) : 1.5) * out_mb;
-    if (c.kg > 1) us += 1.5;                                            // the closing exchange through LDS
+    if (c.kg > 1) us += waves == 16 ? 1.5 : 0.8;                        // the closing exchange through LDS (quarter tiles: a seventh of the data)
     return us;
 }
 
 // The candidate the cost estimate prefers for the fused kernel (or the one CONV_MCMK_TILE forces:
 // tuning aid, menu index = shape + 7 * (csplit - 1) for the seven common shapes, then
-// 14 + further shape + 7 * (csplit - 1) for the further shapes: bf16 with two row blocks per wave, quarter tiles, tile pairs).
+// 14 + further shape + 8 * (csplit - 1) for the eight further shapes: bf16 with two row blocks per wave, quarter tiles,
+// tile pairs, quarter tiles with two channel groups).
 Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, bool epilogue, const char *force);
 
 // The search walks the whole menu, a few microseconds of host time -- as long as the smallest layers
@@ -356,7 +358,7 @@ Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_la
             if (sh >= kPairTileShape && (d->dtype == CONV_MCMK_BF16 || d->k > 3)) continue;
             // the two-group pair is not built for 2 x 2 kernels, nor for channels-last operands (measured slower there
             // than single tiles: the 16-byte gathers of eight waves fill a 30-column tile less evenly)
-            if (sh > kPairTileShape && (d->k == 2 || channels_last)) continue;    // quarter tiles: unit stride, kernel sides up to 5
+            if (sh == kPairTileShape + 1 && (d->k == 2 || channels_last)) continue;    // quarter tiles: unit stride, kernel sides up to 5
             // channel groups exist for kernel sides up to 3 only (four groups of double-buffered 5x5 halo
             // tiles would not fit the 160 KB of LDS) and are an alternative to, not a partner of, the
             // two-way split

@@ -281,7 +281,7 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
     // taps: the fragment has to cross the L2's latency while the wave works through kDepth taps of PBW blocks
     // each, so waves with few blocks look further ahead (a quarter tile's tap is four products, 128 cycles)
     // (not with a 1 x 1 kernel, whose next taps are the next chunks, nor with channel groups: both measured slower)
-    constexpr int kDepth = (PBW >= 6 || KG > 1 || T < 4) ? 2 : PBW >= 3 ? 3 : 8;
+    constexpr int kDepth = (PBW >= 6 || (KG > 1 && PBW > 1) || T < 4) ? 2 : PBW >= 3 ? 3 : 8;
     const int nchunks = (a.cg + NQ - 1) / NQ;
     // this part's share of the chunks (nchunks * csplit stays far below 2^31: no 64-bit division)
     const int chunk_lo = a.csplit > 1 ? (int)((unsigned)(nchunks * part) / (unsigned)a.csplit) : 0;

@@ -36,14 +36,17 @@ constexpr TileShapeDesc kTileShapes[] = {
     // the same pair with two channel groups of eight waves, 32 rows per workgroup: twice the workgroups for layers
     // that have too few pairs (28 x 28 images), and a SIMD carries 12.5 blocks per chunk where single tiles give it 13
     {14, 28, 2, 4, 2, 1},
+    // quarter tiles with two channel groups of four waves: the split of the channel sum for single small images with
+    // hundreds of channels, without the zero fill and the atomics of the two-workgroup split
+    {7, 7, 1, 4, 2, 1},
 };
 constexpr int kConvShapes = 7;
 constexpr int kGemmShape = 7;
 constexpr int kStridedShapes = 3;
 constexpr int kMaxKernelSide = 7;      // kernel sides 1..7 are instantiated
 // shapes beyond the first seven (bf16 shapes with two row blocks per wave, quarter tiles): convolution shapes ...
-constexpr int kWideConvShapes = 7;
-constexpr int kWideConvShape[kWideConvShapes] = {8, 9, 10, 12, 13, 14, 15};
+constexpr int kWideConvShapes = 8;
+constexpr int kWideConvShape[kWideConvShapes] = {8, 9, 10, 12, 13, 14, 15, 16};
 constexpr int kWideGemmShape = 11;     // ... and the plain-GEMM shape
 constexpr int kPairTileShape = 14;     // the 14 x 28 shapes: this one and the next (two channel groups)
 

@@ -129,6 +129,7 @@ int MCMK_FN(const TileRequest &rq)
 #endif
 #if !MCMK_BF16 && MCMK_KS <= 3
         case 14: return launch_shape<14, 28, 4, 4, 16, true>(rq);
+        case 16: return launch_shape<7, 7, 1, 4, 16, true, 2>(rq);
 #endif
 #if MCMK_BF16 && MCMK_KS <= 3
         case 8: return launch_shape<14, 14, 4, 2, 16, true, 1, 1, 2>(rq);
@@ -160,6 +161,7 @@ int MCMK_FN(const TileRequest &rq)
 #endif
 #if !MCMK_BF16 && MCMK_KS <= 3
     case 14: return launch_shape<14, 28, 4, 4>(rq);                         // a pair of tiles under sixteen waves
+    case 16: return launch_shape<7, 7, 1, 4, 16, false, 2>(rq);             // quarter tiles, two channel groups
 #if MCMK_KS != 2                // the 15 x 29 halo tile of a 2 x 2 kernel has no regular staging plan for 512 threads: it would spill
     case 15: return launch_shape<14, 28, 2, 4, 16, false, 2>(rq);           // ... split into two channel groups
 #endif

@@ -262,9 +262,9 @@ def test_runtime_errors_through_binding():
 @pytest.mark.parametrize("dtype", [B.F32, B.BF16])
 @pytest.mark.parametrize("k,pad", [(1, 0), (2, 1), (3, 1), (4, 1), (5, 2), (6, 3), (7, 3)])
 def test_every_tile_shape_of_the_menu(k, pad, dtype, monkeypatch):
-    """The selector only ever launches the shape it prefers; force each of the 28 menu entries
-    (7 common tile / wave shapes, then 4 bf16-only shapes with two row blocks per wave, the quarter tiles and the two
-    fp32-only pairs of tiles under sixteen waves, each with channel split 1 and 2; entries the operand type or kernel side does not have fall back to the selector) so every
+    """The selector only ever launches the shape it prefers; force each of the 30 menu entries
+    (7 common tile / wave shapes, then 4 bf16-only shapes with two row blocks per wave, the quarter tiles, the two
+    fp32-only pairs of tiles under sixteen waves and the fp32-only quarter tiles with two channel groups, each with channel split 1 and 2; entries the operand type or kernel side does not have fall back to the selector) so every
     instantiation is checked."""
     from gpu_util import TOL_BF16
     case = (2, 72, 33, 30, 80, k, pad)        # 5 (fp32) / 3 (bf16) channel chunks: an uneven split
@@ -273,7 +273,7 @@ def test_every_tile_shape_of_the_menu(k, pad, dtype, monkeypatch):
     K = wl.normal(601 + k, m * c * k * k, 0.5).reshape(m, c, k, k)
     ref, absref = oracle.mcmk(I, K, pad)
     tol = TOL_BF16 if dtype == B.BF16 else TOL_F32
-    for index in range(28):
+    for index in range(30):
         for variant in (B.KN2ROW, B.KN2COL):
             announce("menu", "k", k, "dtype", dtype, "tile", index, "variant", variant)
             monkeypatch.setenv("CONV_MCMK_TILE", str(index))
@@ -291,7 +291,7 @@ def test_layers_deep_enough_for_a_barrier_every_second_chunk(c, monkeypatch):
     I = wl.small_integers(950 + c, n * c * h * w, 0, 4).reshape(n, c, h, w)
     K = wl.small_integers(951 + c, m * c * k * k, -3, 3).reshape(m, c, k, k)
     ref, _ = oracle.mcmk(I, K, pad)
-    for index in (None, 0, 1, 18, 19, 7, 8, 25):
+    for index in (None, 0, 1, 18, 19, 21, 7, 8, 26):
         for variant in (B.KN2ROW, B.KN2COL):
             announce("deep", c, "tile", index, "variant", variant)
             if index is None:
