@@ -362,7 +362,7 @@ Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_la
             // channel groups exist for kernel sides up to 3 only (four groups of double-buffered 5x5 halo
             // tiles would not fit the 160 KB of LDS) and are an alternative to, not a partner of, the
             // two-way split
-            if (c.kg > 1 && (cs > 1 || d->k > 3)) continue;
+            if (c.kg > 1 && ((cs > 1 && c.th != 7) || d->k > 3)) continue;     // (quarter tiles take both splits at once)
             // nor for a 1 x 1 kernel, whose chunks are too short to pay for the closing exchange (never the fastest
             // candidate on any 1 x 1 layer timed, either precision)
             if (c.kg > 1 && d->k == 1) continue;
