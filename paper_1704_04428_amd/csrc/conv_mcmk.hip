@@ -360,9 +360,9 @@ Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_la
             // than single tiles: the 16-byte gathers of eight waves fill a 30-column tile less evenly)
             if (sh == kPairTileShape + 1 && (d->k == 2 || channels_last)) continue;    // quarter tiles: unit stride, kernel sides up to 5
             // channel groups exist for kernel sides up to 3 only (four groups of double-buffered 5x5 halo
-            // tiles would not fit the 160 KB of LDS) and are an alternative to, not a partner of, the
-            // two-way split
-            if (c.kg > 1 && ((cs > 1 && c.th != 7) || d->k > 3)) continue;     // (quarter tiles take both splits at once)
+            // tiles would not fit the 160 KB of LDS); they combine with the two-way split (each workgroup's groups
+            // share its half of the chunks: 1 x 512 x 28 x 28, M 512 runs 43.7 us that way, 48.2 us on quarter tiles)
+            if (c.kg > 1 && d->k > 3) continue;
             // nor for a 1 x 1 kernel, whose chunks are too short to pay for the closing exchange (never the fastest
             // candidate on any 1 x 1 layer timed, either precision)
             if (c.kg > 1 && d->k == 1) continue;
