@@ -291,7 +291,7 @@ def test_layers_deep_enough_for_a_barrier_every_second_chunk(c, monkeypatch):
     I = wl.small_integers(950 + c, n * c * h * w, 0, 4).reshape(n, c, h, w)
     K = wl.small_integers(951 + c, m * c * k * k, -3, 3).reshape(m, c, k, k)
     ref, _ = oracle.mcmk(I, K, pad)
-    for index in (None, 0, 1, 18, 19, 21, 7, 8, 26):
+    for index in (None, 0, 1, 18, 19, 21, 7, 8, 26, 6, 13, 20, 28, 29):        # the last five: channel groups, alone and under the split
         for variant in (B.KN2ROW, B.KN2COL):
             announce("deep", c, "tile", index, "variant", variant)
             if index is None:
