@@ -354,7 +354,8 @@ def test_stretched_shapes(case):
 
 
 @pytest.mark.parametrize("case", [(2, 40, 28, 28, 48, 3, 1),        # single launch
-                                  (8, 128, 14, 14, 128, 3, 1)])     # channel split: zero-fill kernel + atomics
+                                  (8, 128, 14, 14, 128, 3, 1),      # quarter tiles with channel groups
+                                  (1, 512, 14, 14, 512, 3, 1)])     # ... under the channel split: zero-fill kernel + atomics
 def test_calls_can_be_captured_into_a_graph(case):
     """The library launches only kernels on the caller's stream (no allocation, no synchronisation,
     no memset node), so a call can be captured once and replayed; every replay must reproduce the
