@@ -295,7 +295,7 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
     if (lean) us += 0.5 * 4.0 * (double)d->n * d->m * dm.q * dm.p / (c.tw % 16 == 0 ? 5.0e6 : 3.3e6);
     // the zero fill and two atomic adds per output: per MB of output ([M][Q][P]: tile rows of whole or partial lines)
     if (c.csplit > 1) us += 3.0 + (channels_last ? (bf16 ? 3.5 : 3.125) : partial_lines ? (bf16 ? 3.5 : 2.2) : 1.5) * out_mb;
-    if (c.kg > 1) us += waves == 16 ? 1.5 : 0.8;                        // the closing exchange through LDS (quarter tiles: a seventh of the data)
+    if (c.kg > 1) us += c.kg == 4 ? 1.5 : waves == 16 ? 0.5 : 0.8;                        // the closing exchange through LDS (quarter tiles: a seventh of the data)
     return us;
 }
 
