@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the kn2row MCMK convolution on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-table] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-table] [--no-cpu] [--vendor]
 
 A step is one call of conv_mcmk_kn2row (the 1x1 GEMMs of all k*k taps with the shift-add fused,
 paper section III-A) on one batch of synthetic input that is already resident in HBM; the kernel
@@ -26,9 +26,28 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0    # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0
 DEFAULT_WORKLOAD = "cfg5a_vgg_deep56"
 
-# HBM bytes per launch of the fused kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE
-# scaled by a copy kernel of known size); filled in from the committed summaries, None = not measured.
-MEASURED_TRAFFIC_BYTES = {"cfg5a_vgg_deep56": 74_260_000}   # profiles/kn2row_tile_f32_cfg5a_hbm_traffic.txt
+# The GPU needs some tens of milliseconds under load to reach its steady clock.  Whatever --warmup says, the timed
+# plan first runs untimed for at least this long (reported as clock_ramp_ms); --steps and --warmup stay as given.
+CLOCK_RAMP_MS = 150.0
+
+# HBM bytes per launch of the fused kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE scaled by a copy
+# kernel of known size), from the committed summaries.  A figure belongs to one kernel on one layer, so the key is
+# (workload, operand type, the plan the library reports for it, without its time estimate); a launch whose plan is
+# not in the table reports no traffic rather than another kernel's.
+MEASURED_TRAFFIC_BYTES = {
+    # profiles/kn2row_tile_f32_cfg5a_hbm_traffic.txt
+    ("cfg5a_vgg_deep56", "f32", "kn2row fused f32: tile 14x28, waves 4x4, row blocks 1, channel groups 1, channel split 1, "
+                                "256 workgroups"): 74_260_000,
+}
+
+
+def plan_key(plan_text):
+    """The plan line without its trailing time estimate."""
+    return plan_text.split(", est ")[0]
+
+
+def measured_traffic(workload, dtype_name, plan_text):
+    return MEASURED_TRAFFIC_BYTES.get((workload, dtype_name, plan_key(plan_text)))
 
 
 def log(*a):
@@ -51,6 +70,41 @@ def time_calls(fn, steps, warmup):
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     return wall_ms / steps, start.elapsed_time(stop) / steps
+
+
+def ramp_clocks(fn, min_ms=CLOCK_RAMP_MS):
+    """Run `fn` back to back, untimed, until at least `min_ms` of device time have passed.  Returns the ms spent."""
+    import torch
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    while True:
+        for _ in range(50):
+            fn()
+        torch.cuda.synchronize()
+        spent = (time.perf_counter() - t0) * 1e3
+        if spent >= min_ms:
+            return spent
+
+
+def measured_machine_rates(dev):
+    """What the device at hand sustains: the matrix-core instructions in a register-only loop (fp32 and bf16) and
+    a plain 16-byte copy, through the library's probe kernels.  TFLOP/s, TFLOP/s, GB/s (read + written)."""
+    import torch
+    from paper_1704_04428_amd import binding as B
+    blocks = 2048                                    # 8 workgroups of 4 waves per compute unit
+    sink = torch.empty(blocks * 256, dtype=torch.float32, device=dev)
+    out = {}
+    for name, dtype, iters, flop in (("f32", B.F32, 2000, 2048.0), ("bf16", B.BF16, 4000, 16384.0)):
+        run = lambda: B.conv_mcmk_probe_mfma(dtype, blocks, iters, sink)        # noqa: E731
+        _, ms = time_calls(run, 10, 10)
+        out["mfma_" + name + "_tflops"] = round(blocks * 4 * iters * 16 * flop / (ms * 1e-3) / 1e12, 1)
+    nbytes = 256 << 20
+    src = torch.ones(nbytes // 4, dtype=torch.float32, device=dev)
+    dst = torch.empty_like(src)
+    run = lambda: B.conv_mcmk_probe_copy(src, dst, nbytes)                       # noqa: E731
+    _, ms = time_calls(run, 20, 10)
+    out["copy_gbs"] = round(2 * nbytes / (ms * 1e-3) / 1e9, 1)
+    return out
 
 
 def auto_counts(fn, warm_ms=60.0, timed_ms=120.0):
@@ -198,9 +252,8 @@ def main():
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"], help="operand type of the timed steps")
     ap.add_argument("--no-table", action="store_true", help="skip the other variants and layers")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--probe-copy", action="store_true",
-                    help="also run a 256 MiB elementwise copy kernel (dst = src + 1) a few times (known HBM traffic, for scaling "
-                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
+    ap.add_argument("--vendor", action="store_true",
+                    help="context only: also time the vendor libraries (torch.matmul, torch conv2d) on the table's layers")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (one process, one MI355X); use --gpus 1")
@@ -232,15 +285,9 @@ def main():
         I_run = I_run.permute(0, 2, 3, 1).contiguous()
     torch.cuda.synchronize()
 
-    if args.probe_copy:
-        src = torch.ones(64 << 20, dtype=torch.float32, device=dev)
-        dst = torch.empty_like(src)
-        for _ in range(5):
-            torch.add(src, 1.0, out=dst)     # reads 256 MiB, writes 256 MiB
-        torch.cuda.synchronize()
-        del src, dst
-
+    ramp_ms = ramp_clocks(lambda: plan.run(I_run))
     wall_ms, dev_ms = time_calls(lambda: plan.run(I_run), args.steps, args.warmup)
+    rates = measured_machine_rates(dev)
     gflops = L.flops / (wall_ms * 1e-3) / 1e9
     achieved_tflops = L.flops / (dev_ms * 1e-3) / 1e12
 
@@ -255,7 +302,8 @@ def main():
         sys.exit(f"bench.py: output fails parity (worst error {worst:.3e} of sum|K||I|)")
 
     peak = PEAK_BF16_MFMA_TFLOPS if dtype == B.BF16 else PEAK_F32_MFMA_TFLOPS
-    headline = args.variant == "kn2row" and dtype == B.F32
+    measured_peak = rates["mfma_bf16_tflops" if dtype == B.BF16 else "mfma_f32_tflops"]
+    plan_text = B.conv_mcmk_describe_plan(d, B.VARIANTS[args.variant])
     result = {
         "metric": f"conv GFLOP/s (2*M*C*k^2*P*Q*N / time), {args.variant}",
         "value": round(gflops, 1),
@@ -271,11 +319,16 @@ def main():
         "data": "synthetic",
         "config": {"workload": L.name, "n": L.n, "c": L.c, "h": L.h, "w": L.w, "m": L.m, "k": L.k,
                    "pad": L.pad, "stride": L.stride, "variant": args.variant + (" (fused shift-add)" if args.variant == "kn2row" else ""),
-                   "flops_per_step": L.flops, "plan": B.conv_mcmk_describe_plan(d, B.VARIANTS[args.variant])},
+                   "flops_per_step": L.flops, "plan": plan_text},
+        "clock_ramp_ms": round(ramp_ms, 1),
         "roofline": {"bound": "mfma", "achieved": round(achieved_tflops, 3), "peak": peak,
                      "unit": "TFLOP/s", "frac": round(achieved_tflops / peak, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(L.name) if headline else None,
-                     "kernel_ms": round(dev_ms, 5)},
+                     "traffic": measured_traffic(L.name, args.dtype, plan_text) if args.variant == "kn2row" else None,
+                     "kernel_ms": round(dev_ms, 5),
+                     # the same instruction in a register-only loop on this device, measured just now
+                     "measured_peak": measured_peak,
+                     "frac_of_measured_peak": round(achieved_tflops / measured_peak, 4)},
+        "machine": rates,
         "parity_worst_err_over_bound_norm": worst,
     }
     if not args.no_cpu:
@@ -289,8 +342,8 @@ def main():
             table[name] = bench_layer(layer, variants, steps, None, I_dev if same else None, K_dev if same else None)
             r = table[name]
             r["kn2row_over_im2col_time"] = round(r["kn2row"]["ms"] / r["im2col"]["ms"], 4)
-            r["library_conv_ms"] = {"f32": round(library_conv_ms(layer), 5)}
-            if layer.flops > 1e9:
+            if args.vendor:
+                r["library_conv_ms"] = {"f32": round(library_conv_ms(layer), 5)}
                 # how the hand-written GEMM of the im2col baseline compares with the vendor BLAS on the same product
                 r["library_gemm_ms"] = {"f32": round(library_gemm_ms(layer), 5)}
             r["frac_f32_mfma_peak"] = round(r["kn2row"]["gflops"] / 1e3 / PEAK_F32_MFMA_TFLOPS, 4)
@@ -298,8 +351,9 @@ def main():
                 b = bench_layer(layer, ["kn2row", "kn2col", "im2col", "im2row", "kn2row_2pass"], steps, None,
                                 I_dev if same else None, K_dev if same else None, dtype=B.BF16)
                 b["frac_bf16_mfma_peak"] = round(b["kn2row"]["gflops"] / 1e3 / PEAK_BF16_MFMA_TFLOPS, 4)
-                r["library_gemm_ms"]["bf16"] = round(library_gemm_ms(layer, bf16=True), 5)
-                r["library_conv_ms"]["bf16"] = round(library_conv_ms(layer, bf16=True), 5)
+                if args.vendor:
+                    r["library_gemm_ms"]["bf16"] = round(library_gemm_ms(layer, bf16=True), 5)
+                    r["library_conv_ms"]["bf16"] = round(library_conv_ms(layer, bf16=True), 5)
                 r["bf16"] = b
             log(name, json.dumps(r))
         result["table"] = table

@@ -84,6 +84,14 @@ const char *conv_mcmk_strerror(int code);
 int conv_mcmk_check(const conv_mcmk_desc *desc, int variant);
 
 /*
+ * Rows and columns of one output plane (section II-A's output height and width, generalised to any pad
+ * and stride): *q = floor((H + 2 pad - k) / stride) + 1, *p likewise from W.  Host only.  Either
+ * pointer may be NULL.  Returns CONV_MCMK_OK, or the shape error conv_mcmk_check gives (nothing is
+ * written then); the variant plays no part.
+ */
+int conv_mcmk_output_dims(const conv_mcmk_desc *desc, int *q, int *p);
+
+/*
  * Host-only introspection: writes one line of text saying how `variant` would run `desc` (for the
  * fused kernel: the tile shape, wave layout and channel split the cost estimate picks -- the
  * per-layer selection the paper's conclusion asks for -- and the number of workgroups) into buf,
@@ -95,7 +103,8 @@ int conv_mcmk_describe_plan(const conv_mcmk_desc *desc, int variant, char *buf, 
  * Bytes of caller-provided scratch a variant needs (0 for KN2ROW, KN2COL and DIRECT; 0 also for an invalid
  * desc -- use conv_mcmk_check for the reason).
  *   KN2ROW_2PASS: N * k*k*M * H*W floats -- the GEMM result of section III-A, per image
- *                 T[t*M + m][y*W + x], t = i*k + j ("some increase in the size of the output").
+ *                 T[t*M + m][y*W + x], t = i*k + j (k*k times the output: the price section III names
+ *                 for leaving the input unreplicated).
  *   IM2COL:       N * C*k*k * Q*P elements of the input's type -- the input-patch-matrix of
  *                 section II-B, per image Ihat[(c*k + i)*k + j][q*P + p] (k*k times the input).
  *   IM2ROW:       the same number of elements, per image rows[q*P + p][(i*k + j)*C + c].
@@ -105,7 +114,7 @@ size_t conv_mcmk_workspace_bytes(const conv_mcmk_desc *desc, int variant);
 
 /*
  * Bytes of the re-ordered kernel a variant consumes (0 for DIRECT, which reads K as is, and for an
- * invalid desc).  The re-ordering is the "made statically ahead of time" step of section III-A: the
+ * invalid desc).  The re-ordering is the one-off, ahead-of-time step of section III-A: the
  * logical matrix is [k*k*M] x [C] for the kn2row variants (row t*M + m, channel innermost) and
  * [M] x [C*k*k] for im2col (section II-B's kernel-patch-matrix).  Physically it is stored in the order
  * the matrix-core instruction takes its operand, zero-padded to whole tiles:
@@ -215,6 +224,32 @@ int conv_mcmk_1x1(const conv_mcmk_desc *desc, const void *I_dev, const void *Kp_
 
 /* float -> bfloat16 (round to nearest even), `count` elements, device to device. */
 int conv_mcmk_cvt_f32_bf16(const void *src_dev, void *dst_dev, size_t count, void *stream);
+
+/*
+ * Tuning aids (host only, process-wide, thread-safe; no part of the method).  The fused kernels and the
+ * matrix product of the staged variants each pick a tile shape from a menu by a cost estimate;
+ * conv_mcmk_force_tile / conv_mcmk_force_gemm_tile make every later call take menu entry `index` instead
+ * (for an entry the layer's operand type, kernel side or stride does not have, the estimate still chooses); a
+ * negative index gives the choice back to the estimate.  The environment variables CONV_MCMK_TILE / CONV_MCMK_GEMM_TILE set
+ * the initial value; they are read once, when the library is first used.
+ */
+void conv_mcmk_force_tile(int index);
+void conv_mcmk_force_gemm_tile(int index);
+
+/*
+ * Measurement aids for the benchmark (no part of the method): the two machine rates the roofline
+ * figures are compared with, measured on the device at hand.
+ *   conv_mcmk_probe_mfma: launches `blocks` workgroups of 256 threads that each issue `iters` x 16
+ *     independent matrix-core products from registers only (dtype CONV_MCMK_F32: v_mfma_f32_16x16x4_f32,
+ *     2048 flop each; CONV_MCMK_BF16: v_mfma_f32_16x16x32_bf16, 16384 flop each) and store one value per
+ *     lane to sink_dev (blocks * 256 floats, so that the products cannot be dropped).  Flop of a launch:
+ *     blocks * 4 waves * iters * 16 * (2048 or 16384).
+ *   conv_mcmk_probe_copy: copies `bytes` (a multiple of 16) from src_dev to dst_dev with 16-byte
+ *     accesses, the plain streaming kernel of known traffic (bytes read + bytes written).
+ * Both validate pointers and alignment like the other calls and launch on `stream`.
+ */
+int conv_mcmk_probe_mfma(int dtype, int blocks, int iters, float *sink_dev, void *stream);
+int conv_mcmk_probe_copy(const void *src_dev, void *dst_dev, size_t bytes, void *stream);
 
 #ifdef __cplusplus
 }

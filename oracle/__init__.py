@@ -21,6 +21,11 @@ from . import build as _build
 _lib = None
 
 
+class OracleDesc(ctypes.Structure):
+    """conv_oracle_desc of oracle/conv_oracle.h."""
+    _fields_ = [(name, ctypes.c_int) for name in ("n", "c", "h", "w", "m", "k", "pad", "stride")]
+
+
 def _load():
     global _lib
     if _lib is None:
@@ -30,10 +35,11 @@ def _load():
         fp = ctypes.POINTER(ctypes.c_float)
         dp = ctypes.POINTER(ctypes.c_double)
         ip = ctypes.POINTER(ctypes.c_int)
-        lib.mcmk_oracle_f64.argtypes = [i] * 8 + [fp, fp, dp, dp]
-        lib.mcmk_oracle_f64.restype = i
-        lib.mcmk_oracle_f64_at.argtypes = [i] * 8 + [fp, fp, i, ip, dp, dp]
-        lib.mcmk_oracle_f64_at.restype = i
+        desc = ctypes.POINTER(OracleDesc)
+        lib.conv_mcmk_oracle_f64.argtypes = [desc, fp, fp, dp, dp]
+        lib.conv_mcmk_oracle_f64.restype = i
+        lib.conv_mcmk_oracle_f64_at.argtypes = [desc, fp, fp, i, ip, dp, dp]
+        lib.conv_mcmk_oracle_f64_at.restype = i
         _lib = lib
     return _lib
 
@@ -77,7 +83,8 @@ def mcmk(I, K, pad, stride=1):
     q, p = (h + 2 * pad - k) // stride + 1, (w + 2 * pad - k) // stride + 1
     O = np.empty((n, m, q, p), dtype=np.float64)
     A = np.empty_like(O)
-    rc = _load().mcmk_oracle_f64(n, c, h, w, m, k, pad, stride, _f(I), _f(K), _d(O), _d(A))
+    d = OracleDesc(n, c, h, w, m, k, pad, stride)
+    rc = _load().conv_mcmk_oracle_f64(ctypes.byref(d), _f(I), _f(K), _d(O), _d(A))
     if rc:
         raise ValueError(f"oracle rejected the shape (code {rc})")
     return (O[0], A[0]) if squeeze else (O, A)
@@ -92,8 +99,9 @@ def mcmk_at(I, K, pad, points, stride=1):
     pts = np.ascontiguousarray(points, dtype=np.int32).reshape(-1, 4)
     O = np.empty(len(pts), dtype=np.float64)
     A = np.empty_like(O)
-    rc = _load().mcmk_oracle_f64_at(n, c, h, w, m, k, pad, stride, _f(I), _f(K), len(pts),
-                                    pts.ctypes.data_as(ctypes.POINTER(ctypes.c_int)), _d(O), _d(A))
+    d = OracleDesc(n, c, h, w, m, k, pad, stride)
+    rc = _load().conv_mcmk_oracle_f64_at(ctypes.byref(d), _f(I), _f(K), len(pts),
+                                         pts.ctypes.data_as(ctypes.POINTER(ctypes.c_int)), _d(O), _d(A))
     if rc:
         raise ValueError(f"oracle rejected the request (code {rc})")
     return O, A

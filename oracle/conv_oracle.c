@@ -31,6 +31,8 @@
  * linearity, constant-input closed form, im2col and kn2row reformulations,
  * the k = 1 matrix product, and a library convolution in float64).
  */
+#include "conv_oracle.h"
+
 #include <math.h>
 #include <stddef.h>
 
@@ -64,13 +66,11 @@ static void one_output(int c, int h, int w, int k, int pad, int stride,
     *absvalue = aacc;
 }
 
-/*
- * Whole output.  O and absO are [N][M][Q][P] doubles; absO may be NULL.
- * Returns 0, or 1 when the shape is not a valid convolution.
- */
-int mcmk_oracle_f64(int n, int c, int h, int w, int m, int k, int pad, int stride,
-                    const float *I, const float *K, double *O, double *absO)
+/* Whole output (Eq. 3 plus the loop over the images of a batch); see conv_oracle.h. */
+int conv_mcmk_oracle_f64(const conv_oracle_desc *d, const float *I, const float *K, double *O, double *absO)
 {
+    if (!d) return 1;
+    const int n = d->n, c = d->c, h = d->h, w = d->w, m = d->m, k = d->k, pad = d->pad, stride = d->stride;
     if (bad_shape(n, c, h, w, m, k, pad, stride) || !I || !K || !O) return 1;
     const int Q = out_size(h, k, pad, stride), P = out_size(w, k, pad, stride);
 #pragma omp parallel for collapse(2) schedule(static)
@@ -88,15 +88,12 @@ int mcmk_oracle_f64(int n, int c, int h, int w, int m, int k, int pad, int strid
     return 0;
 }
 
-/*
- * Selected outputs only: pts holds npts quadruples (n, m, q, p); O and absO
- * get npts doubles.  Used where the full output is too slow to compute.
- * Returns 0, 1 for a bad shape, 2 for a point outside the output.
- */
-int mcmk_oracle_f64_at(int n, int c, int h, int w, int m, int k, int pad, int stride,
-                       const float *I, const float *K,
-                       int npts, const int *pts, double *O, double *absO)
+/* Selected outputs only; see conv_oracle.h. */
+int conv_mcmk_oracle_f64_at(const conv_oracle_desc *d, const float *I, const float *K,
+                            int npts, const int *pts, double *O, double *absO)
 {
+    if (!d) return 1;
+    const int n = d->n, c = d->c, h = d->h, w = d->w, m = d->m, k = d->k, pad = d->pad, stride = d->stride;
     if (bad_shape(n, c, h, w, m, k, pad, stride) || !I || !K || !O || !pts || npts < 0) return 1;
     const int Q = out_size(h, k, pad, stride), P = out_size(w, k, pad, stride);
     for (int t = 0; t < npts; ++t) {

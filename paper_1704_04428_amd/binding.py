@@ -26,6 +26,7 @@ EXPORTS = (
     "conv_mcmk_prepack", "conv_mcmk_kn2row", "conv_mcmk_kn2row_2pass", "conv_mcmk_im2col",
     "conv_mcmk_direct", "conv_mcmk_kn2col", "conv_mcmk_im2row", "conv_mcmk_cvt_f32_bf16",
     "conv_mcmk_kn2row_bias_relu", "conv_mcmk_kn2col_bias_relu", "conv_mcmk_1x1", "conv_mcmk_select", "conv_mcmk_run",
+    "conv_mcmk_output_dims", "conv_mcmk_force_tile", "conv_mcmk_force_gemm_tile", "conv_mcmk_probe_mfma", "conv_mcmk_probe_copy",
 )
 
 
@@ -86,6 +87,16 @@ def lib():
         L.conv_mcmk_1x1.restype = i
         L.conv_mcmk_cvt_f32_bf16.argtypes = [vp, vp, sz, vp]
         L.conv_mcmk_cvt_f32_bf16.restype = i
+        L.conv_mcmk_output_dims.argtypes = [dp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
+        L.conv_mcmk_output_dims.restype = i
+        L.conv_mcmk_force_tile.argtypes = [i]
+        L.conv_mcmk_force_tile.restype = None
+        L.conv_mcmk_force_gemm_tile.argtypes = [i]
+        L.conv_mcmk_force_gemm_tile.restype = None
+        L.conv_mcmk_probe_mfma.argtypes = [i, i, i, vp, vp]
+        L.conv_mcmk_probe_mfma.restype = i
+        L.conv_mcmk_probe_copy.argtypes = [vp, vp, sz, vp]
+        L.conv_mcmk_probe_copy.restype = i
         _lib = L
     return _lib
 
@@ -117,8 +128,31 @@ def conv_mcmk_check(d: Desc, variant: int) -> int:
     return lib().conv_mcmk_check(ctypes.byref(d), variant)
 
 
+def conv_mcmk_output_dims(d: Desc):
+    """(Q, P): rows and columns of one output plane."""
+    q, p = ctypes.c_int(0), ctypes.c_int(0)
+    _raise(lib().conv_mcmk_output_dims(ctypes.byref(d), ctypes.byref(q), ctypes.byref(p)))
+    return q.value, p.value
+
+
+def conv_mcmk_force_tile(index: int) -> None:
+    lib().conv_mcmk_force_tile(int(index))
+
+
+def conv_mcmk_force_gemm_tile(index: int) -> None:
+    lib().conv_mcmk_force_gemm_tile(int(index))
+
+
+def conv_mcmk_probe_mfma(dtype: int, blocks: int, iters: int, sink, stream=None) -> None:
+    _raise(lib().conv_mcmk_probe_mfma(dtype, blocks, iters, _ptr(sink), _stream(stream)))
+
+
+def conv_mcmk_probe_copy(src, dst, nbytes: int, stream=None) -> None:
+    _raise(lib().conv_mcmk_probe_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)))
+
+
 def conv_mcmk_describe_plan(d: Desc, variant: int) -> str:
-    buf = ctypes.create_string_buffer(256)
+    buf = ctypes.create_string_buffer(512)
     _raise(lib().conv_mcmk_describe_plan(ctypes.byref(d), variant, buf, len(buf)))
     return buf.value.decode()
 
@@ -215,7 +249,7 @@ class Plan:
             conv_mcmk_prepack(d, variant, K_dev, self.kernel)
         ws_bytes = conv_mcmk_workspace_bytes(d, variant)
         self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev) if ws_bytes else None
-        q, p = (d.h + 2 * d.pad - d.k) // d.stride + 1, (d.w + 2 * d.pad - d.k) // d.stride + 1
+        q, p = conv_mcmk_output_dims(d)
         shape = (d.n, q, p, d.m) if variant in CHANNELS_LAST else (d.n, d.m, q, p)
         self.out = torch.empty(shape, dtype=torch.float32, device=dev)
 

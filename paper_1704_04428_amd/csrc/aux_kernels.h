@@ -112,34 +112,84 @@ __global__ void im2col_build_kernel(const T *__restrict__ I, T *__restrict__ col
     }
 }
 
+// The same matrix for the common case -- unit stride, kernel side KS known at compile time, P a multiple of VEC --
+// arranged for memory throughput (the build is k*k-fold write traffic and nothing else): one item per thread and a
+// grid as large as the work (no loop-carried index arithmetic; measured faster than several items per thread or a
+// grid capped to the chip), 32-bit indices inside one image (images along the grid's second dimension), every load
+// of an item issued before its first store, loads through a range-checked buffer descriptor (zero padding = an
+// offset beyond the image, no branches), stores marked non-temporal (written once, read by the next kernel).
+template <typename T, int VEC, int KS>
+__global__ __launch_bounds__(256) void im2col_build_fast_kernel(const T *__restrict__ I, T *__restrict__ cols,
+                                                                int n, int c, int h, int w, int pad, int q, int p)
+{
+    typedef T vec_t __attribute__((ext_vector_type(VEC)));
+    const unsigned pv = (unsigned)p / VEC;
+    const unsigned hw = (unsigned)h * w, qp = (unsigned)q * p;
+    const unsigned per_image = (unsigned)c * q * pv;
+    for (unsigned in = blockIdx.y; in < (unsigned)n; in += gridDim.y) {
+        const T *In = I + (size_t)in * c * hw;
+        T *Cn = cols + (size_t)in * c * (KS * KS) * qp;
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<T *>(In), 0, (int)((size_t)c * hw * sizeof(T)), 0x00020000);
+        for (unsigned e = blockIdx.x * 256u + threadIdx.x; e < per_image; e += gridDim.x * 256u) {
+            const unsigned xg = e % pv, rest = e / pv;
+            const unsigned oq = rest % (unsigned)q, ch = rest / (unsigned)q;
+            T in_px[KS][VEC + KS - 1];               // the input patch under VEC neighbouring outputs
+#pragma unroll
+            for (int r = 0; r < KS; ++r) {
+                const int y = (int)oq - pad + r;
+#pragma unroll
+                for (int u = 0; u < VEC + KS - 1; ++u) {
+                    const int x = (int)(xg * VEC) - pad + u;
+                    const bool ok = (unsigned)y < (unsigned)h && (unsigned)x < (unsigned)w;
+                    const int off = ok ? (int)((ch * hw + (unsigned)y * w + (unsigned)x) * (unsigned)sizeof(T)) : (int)0x80000000u;
+                    if constexpr (sizeof(T) == 4) in_px[r][u] = __builtin_bit_cast(T, __builtin_amdgcn_raw_buffer_load_b32(rs, off, 0, 0));
+                    else in_px[r][u] = __builtin_bit_cast(T, __builtin_amdgcn_raw_buffer_load_b16(rs, off, 0, 0));
+                }
+            }
+            T *dst0 = Cn + (size_t)ch * (KS * KS) * qp + (size_t)oq * p + xg * VEC;
+#pragma unroll
+            for (int i = 0; i < KS; ++i)
+#pragma unroll
+                for (int j = 0; j < KS; ++j) {
+                    vec_t out;
+#pragma unroll
+                    for (int u = 0; u < VEC; ++u) out[u] = in_px[i][j + u];
+                    __builtin_nontemporal_store(out, reinterpret_cast<vec_t *>(dst0 + (size_t)(i * KS + j) * qp));
+                }
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // im2row (section II-B, last paragraph): patches unrolled into ROWS, from a channels-last input:
 //   rows[n][q*P+p][(i*k+j)*C + c] = I[n][stride*q-pad+i][stride*p-pad+j][c]  (zero outside the image).
 // One thread copies one VEC-wide channel vector (VEC elements = 16 bytes; C % VEC == 0), so both the
 // read and the write are contiguous runs of C elements.
 template <typename T, int VEC>
-__global__ void im2row_build_kernel(const T *__restrict__ I, T *__restrict__ rows,
-                                    int n, int c, int h, int w, int k, int pad, int stride, int q, int p)
+__global__ __launch_bounds__(256) void im2row_build_kernel(const T *__restrict__ I, T *__restrict__ rows,
+                                                           int n, int c, int h, int w, int k, int pad, int stride, int q, int p)
 {
-    struct alignas(sizeof(T) * VEC) Pack { T v[VEC]; };
-    const int cv = c / VEC;
-    const size_t total = (size_t)n * q * p * k * k * cv;
-    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total;
-         e += (size_t)gridDim.x * blockDim.x) {
-        const int ic = (int)(e % cv);
-        size_t rest = e / cv;
-        const int j = (int)(rest % k);  rest /= k;
-        const int i = (int)(rest % k);  rest /= k;
-        const int op = (int)(rest % p); rest /= p;
-        const int oq = (int)(rest % q);
-        const size_t in = rest / q;
-        const int y = oq * stride - pad + i, x = op * stride - pad + j;
-        Pack out;
+    typedef T vec_t __attribute__((ext_vector_type(VEC)));
+    const unsigned cv = (unsigned)c / VEC;
+    const unsigned per_image = (unsigned)q * p * k * k * cv;          // below 2^29: 32-bit indices inside an image
+    for (unsigned in = blockIdx.y; in < (unsigned)n; in += gridDim.y) {
+        const T *In = I + (size_t)in * h * w * c;
+        T *Rn = rows + (size_t)in * per_image * VEC;
+        for (unsigned e = blockIdx.x * 256u + threadIdx.x; e < per_image; e += gridDim.x * 256u) {
+            const unsigned ic = e % cv;
+            unsigned rest = e / cv;
+            const int j = (int)(rest % (unsigned)k);  rest /= (unsigned)k;
+            const int i = (int)(rest % (unsigned)k);  rest /= (unsigned)k;
+            const int op = (int)(rest % (unsigned)p);
+            const int oq = (int)(rest / (unsigned)p);
+            const int y = oq * stride - pad + i, x = op * stride - pad + j;
+            vec_t out;
 #pragma unroll
-        for (int u = 0; u < VEC; ++u) out.v[u] = T(0);
-        if (y >= 0 && y < h && x >= 0 && x < w)
-            out = *reinterpret_cast<const Pack *>(I + ((in * h + y) * w + x) * (size_t)c + (size_t)ic * VEC);
-        *reinterpret_cast<Pack *>(rows + e * VEC) = out;
+            for (int u = 0; u < VEC; ++u) out[u] = T(0);
+            if ((unsigned)y < (unsigned)h && (unsigned)x < (unsigned)w)
+                out = *reinterpret_cast<const vec_t *>(In + ((size_t)y * w + x) * c + (size_t)ic * VEC);
+            __builtin_nontemporal_store(out, reinterpret_cast<vec_t *>(Rn + (size_t)e * VEC));
+        }
     }
 }
 
@@ -189,6 +239,64 @@ __global__ void shift_add_f32_kernel(const float *__restrict__ T, float *__restr
     }
 }
 
+// The same post pass for the common case -- unit stride, kernel side KS known at compile time, P a multiple of VEC,
+// one image's product matrix below 2 GiB -- arranged for memory throughput like im2col_build_fast_kernel: one item per
+// thread, a grid as large as the work, 32-bit indices inside an image, all k*k loads of an item in flight before the
+// first add.  Each tap contributes one VEC-wide load at the tap's column offset (4-byte aligned, not 16): a vector
+// that crosses a row end of the plane picks up the neighbouring row's values, which the column test below drops, and
+// a row outside the plane gets an offset beyond the buffer, which the range check answers with zeros.  Only the
+// vectors that reach before the first or beyond the last element of the whole matrix are fetched element by
+// element instead (how a partly out-of-range vector load is answered is not relied on).
+template <int VEC, int KS>
+__global__ __launch_bounds__(256) void shift_add_fast_kernel(const float *__restrict__ T, float *__restrict__ O,
+                                                             int n, int m, int h, int w, int pad, int q, int p)
+{
+    typedef float vec_t __attribute__((ext_vector_type(VEC)));
+    const unsigned pv = (unsigned)p / VEC;
+    const unsigned hw = (unsigned)h * w;
+    const unsigned per_image = (unsigned)m * q * pv;
+    const int t_elems = (int)((unsigned)(KS * KS) * m * hw);                 // below 2^29
+    for (unsigned in = blockIdx.y; in < (unsigned)n; in += gridDim.y) {
+        const float *Tn = T + (size_t)in * t_elems;
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(Tn), 0, t_elems * 4, 0x00020000);
+        for (unsigned e = blockIdx.x * 256u + threadIdx.x; e < per_image; e += gridDim.x * 256u) {
+            const unsigned xg = e % pv, rest = e / pv;
+            const unsigned oq = rest % (unsigned)q, im = rest / (unsigned)q;
+            vec_t v[KS][KS];
+#pragma unroll
+            for (int i = 0; i < KS; ++i)
+#pragma unroll
+                for (int j = 0; j < KS; ++j) {
+                    const int y = (int)oq - pad + i;
+                    const int x0 = (int)(xg * VEC) - pad + j;
+                    const bool row_ok = (unsigned)y < (unsigned)h;
+                    const int off = (int)(((unsigned)(i * KS + j) * m + im) * hw) + y * w + x0;      // element index in the matrix
+                    const int boff = row_ok ? off * 4 : (int)0x80000000u;
+                    if constexpr (VEC == 4) v[i][j] = __builtin_bit_cast(vec_t, __builtin_amdgcn_raw_buffer_load_b128(rs, boff, 0, 0));
+                    else if constexpr (VEC == 2) v[i][j] = __builtin_bit_cast(vec_t, __builtin_amdgcn_raw_buffer_load_b64(rs, boff, 0, 0));
+                    else v[i][j] = __builtin_bit_cast(vec_t, __builtin_amdgcn_raw_buffer_load_b32(rs, boff, 0, 0));
+                    if (VEC > 1 && row_ok && (off < 0 || off + VEC > t_elems)) {
+#pragma unroll
+                        for (int u = 0; u < VEC; ++u) v[i][j][u] = (off + u >= 0 && off + u < t_elems) ? Tn[off + u] : 0.0f;
+                    }
+                }
+            vec_t acc;
+#pragma unroll
+            for (int u = 0; u < VEC; ++u) acc[u] = 0.0f;
+#pragma unroll
+            for (int i = 0; i < KS; ++i)
+#pragma unroll
+                for (int j = 0; j < KS; ++j) {
+                    const int x0 = (int)(xg * VEC) - pad + j;
+#pragma unroll
+                    for (int u = 0; u < VEC; ++u)
+                        if ((unsigned)(x0 + u) < (unsigned)w) acc[u] += v[i][j][u];
+                }
+            *reinterpret_cast<vec_t *>(O + ((size_t)in * m * q + (size_t)im * q + oq) * p + xg * VEC) = acc;
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Direct loop nest (Eq. 1-3): one output element per thread, plain fp32 FMA.
 __global__ void direct_f32_kernel(const float *__restrict__ I, const float *__restrict__ K,
@@ -230,6 +338,52 @@ __global__ void fill_zero_kernel(float *__restrict__ dst, size_t count)
     for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < vec; e += (size_t)gridDim.x * blockDim.x)
         d4[e] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (blockIdx.x == 0 && threadIdx.x < count - vec * 4) dst[vec * 4 + threadIdx.x] = 0.f;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Measurement aids: the machine rates the benchmark compares the kernels with.
+//
+// Register-only matrix-core loop: 16 independent accumulators per wave, operands fixed in registers, no memory
+// access inside the loop.  The instruction is written out so that operands and accumulators stay where they are
+// (the compiler's own allocation for the builtin moves accumulators between the two register files).
+template <bool BF16>
+__global__ __launch_bounds__(256) void probe_mfma_kernel(float *__restrict__ sink, int iters)
+{
+    typedef float v4f __attribute__((ext_vector_type(4)));
+    constexpr int NACC = 16;
+    v4f acc[NACC];
+#pragma unroll
+    for (int i = 0; i < NACC; ++i) acc[i] = v4f{0.f, 0.f, 0.f, 0.f};
+    // operand bit patterns that are ordinary small numbers in either type (0x3c003c00: two bf16 of 2^-7)
+    const unsigned lane = threadIdx.x & 63u;
+    v4f a4, b4;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        a4[e] = __uint_as_float(0x3c003c00u + ((lane & 7u) << 16));
+        b4[e] = __uint_as_float(0x3c003c00u + ((lane >> 3) << 16));
+    }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < NACC; ++i) {
+            if constexpr (BF16) asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc[i]) : "v"(a4), "v"(b4));
+            else asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+v"(acc[i]) : "v"(a4[0]), "v"(b4[0]));
+        }
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < NACC; ++i) sum += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
+    sink[(size_t)blockIdx.x * 256 + threadIdx.x] = sum;
+}
+
+// Plain copy, 16 bytes per thread, non-temporal (the form that measured fastest: more accesses per thread or a grid
+// capped to the chip are slower).
+__global__ __launch_bounds__(256) void probe_copy_kernel(const float4 *__restrict__ src, float4 *__restrict__ dst, size_t count)
+{
+    typedef float v4f __attribute__((ext_vector_type(4)));
+    const v4f *s = reinterpret_cast<const v4f *>(src);
+    v4f *d = reinterpret_cast<v4f *>(dst);
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < count; e += (size_t)gridDim.x * 256)
+        __builtin_nontemporal_store(__builtin_nontemporal_load(s + e), d + e);
 }
 
 __global__ void cvt_f32_bf16_kernel(const float *__restrict__ src, uint16_t *__restrict__ dst, size_t count)

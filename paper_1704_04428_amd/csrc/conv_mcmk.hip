@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -31,8 +32,10 @@ int validate(const conv_mcmk_desc *d, int variant, Dims *out)
     if ((long long)d->h + 2LL * d->pad < d->k || (long long)d->w + 2LL * d->pad < d->k) return CONV_MCMK_ERR_SHAPE;
     const long long q = ((long long)d->h + 2LL * d->pad - d->k) / d->stride + 1;
     const long long p = ((long long)d->w + 2LL * d->pad - d->k) / d->stride + 1;
-    // the tile kernel addresses one image through a 32-bit byte offset with 2 GiB kept free
-    if (((long long)d->c + 32) * d->h * d->w >= (1LL << 29)) return CONV_MCMK_ERR_SHAPE;
+    // the tile kernel addresses one image through a 32-bit byte offset with 2 GiB kept free: the "outside the image"
+    // offset of 2 GiB plus a staging slot's channel (below 32) plus the first chunk beyond the data (below C + 32)
+    // must not wrap
+    if (((long long)d->c + 64) * d->h * d->w >= (1LL << 29)) return CONV_MCMK_ERR_SHAPE;
     const long long lim = 1LL << 31;
     const long long kk = (long long)d->k * d->k;
     if ((long long)d->c * d->h * d->w >= lim || (long long)d->m * q * p >= lim ||
@@ -59,7 +62,7 @@ int validate(const conv_mcmk_desc *d, int variant, Dims *out)
     case CONV_MCMK_IM2COL:
     case CONV_MCMK_IM2ROW:
         // the GEMM reads the patch matrix of one image through the same 32-bit byte offsets
-        if (((long long)d->c * kk + 32) * q * p >= (1LL << 29)) return CONV_MCMK_ERR_SHAPE;
+        if (((long long)d->c * kk + 64) * q * p >= (1LL << 29)) return CONV_MCMK_ERR_SHAPE;
         if (variant == CONV_MCMK_IM2ROW && d->c % (d->dtype == CONV_MCMK_BF16 ? 8 : 4) != 0) return CONV_MCMK_ERR_UNSUPPORTED;
         break;
     case CONV_MCMK_DIRECT:
@@ -77,11 +80,34 @@ int validate(const conv_mcmk_desc *d, int variant, Dims *out)
     return CONV_MCMK_OK;
 }
 
+// Tuning overrides (conv_mcmk_force_tile / conv_mcmk_force_gemm_tile): -1 none, -2 not yet taken from the environment.
+std::atomic<int> g_force_tile{-2}, g_force_gemm_tile{-2};
+
+int forced_index(std::atomic<int> &slot, const char *env_name)
+{
+    int v = slot.load(std::memory_order_relaxed);
+    if (v == -2) {
+        const char *text = getenv(env_name);
+        int from_env = (text && text[0] >= '0' && text[0] <= '9') ? atoi(text) : -1;
+        slot.compare_exchange_strong(v, from_env, std::memory_order_relaxed);    // a concurrent force call wins
+        v = slot.load(std::memory_order_relaxed);
+    }
+    return v;
+}
+
 inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 int launch_status()
 {
     return hipGetLastError() == hipSuccess ? CONV_MCMK_OK : CONV_MCMK_ERR_DEVICE;
+}
+
+// Grid for a streaming kernel whose threads take `per_thread` items each in one sweep: as many workgroups of 256 as
+// the items need (the loop inside the kernel covers whatever the 2^31 limit cuts off).
+int stream_grid(size_t items, int per_thread)
+{
+    const size_t g = (items + (size_t)256 * per_thread - 1) / ((size_t)256 * per_thread);
+    return (int)(g < 1 ? 1 : (g > 0x7fffffffull ? 0x7fffffffull : g));
 }
 
 int grid_for(size_t total, int block)
@@ -95,7 +121,7 @@ int grid_for(size_t total, int block)
 // Tile-shape menu for the fused kernel and the cost estimate that picks from it.
 struct Candidate {
     int shape;     // index into kTileShapes
-    int csplit;    // 1 or 2
+    int csplit;    // 1 or 2 (the flat shapes of a staged variant's matrix product: also 4 and 8)
     int th, tw, wm, wp, kg, rb;
 };
 
@@ -267,7 +293,7 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
     // staging-heavy cases: a 1 x 1 kernel uses every staged value once instead of k*k times, a
     // strided tile stages four input values per output position (both measured)
     // (less so for the 16 x 16 tile, whose 256 positions per channel give every thread one position to stage)
-    if (ks == 1 && c.shape != kGemmShape) us *= c.th * c.tw == 256 ? (cl16 ? 1.2 : bf16 ? 1.4 : 1.1) : (cl16 ? 1.2 : bf16 ? 1.6 : 1.5);
+    if (ks == 1 && c.shape != kGemmShape && c.shape != kWideGemmShape) us *= c.th * c.tw == 256 ? (cl16 ? 1.2 : bf16 ? 1.4 : 1.1) : (cl16 ? 1.2 : bf16 ? 1.6 : 1.5);
     if (d->stride == 2) us *= 1.25;
     // bf16: staging the halo tile is serial with the matrix work of a workgroup that has a CU to itself
     if (bf16) us += (double)per_cu * chunks * halo * c.kg / waves * (0.05 / 64.0);
@@ -287,14 +313,17 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
         us += (double)(per_cu - 1) * (cl16 ? (waves == 16 ? 4.0 : can_hold == 1 ? 2.0 : 1.0) : waves == 16 ? 3.6 : can_hold == 1 ? 0.5 : 0.6);
     // [M][Q][P] output of a bf16 call: tile rows of 14 or 7 floats are partial cache lines, and with so little
     // matrix time per output the write shows (0.2 us per MB; tiles 16 wide or whole image rows: nothing)
-    const double out_mb = (double)d->n * d->m * dm.q * dm.p * 4.0e-6;
+    // (rows: M, or k*k*M when the rows of a staged variant's matrix product are (tap, kernel) pairs)
+    const double out_rows = (double)d->m * (dm.mb / ceil_div(d->m, 16));
+    const double out_mb = (double)d->n * out_rows * dm.q * dm.p * 4.0e-6;
     const bool partial_lines = !channels_last && c.tw % 16 != 0 && c.tw < 28;
     if (bf16 && partial_lines) us += 0.2 * out_mb;
     // with one channel quad there is so little matrix work that the output write shows: half of it at 5 TB/s
     // when the tile rows are whole 64-byte lines, at 3.3 TB/s when they are not (fitted to the first-layer shapes)
     if (lean) us += 0.5 * 4.0 * (double)d->n * d->m * dm.q * dm.p / (c.tw % 16 == 0 ? 5.0e6 : 3.3e6);
     // the zero fill and two atomic adds per output: per MB of output ([M][Q][P]: tile rows of whole or partial lines)
-    if (c.csplit > 1) us += 3.0 + (channels_last ? (bf16 ? 3.5 : 3.125) : partial_lines ? (bf16 ? 3.5 : 2.2) : 1.5) * out_mb;
+    // (a split into more parts -- the flat shapes of a staged variant's matrix product -- adds its parts' worth of atomics)
+    if (c.csplit > 1) us += 3.0 + (channels_last ? (bf16 ? 3.5 : 3.125) : partial_lines ? (bf16 ? 3.5 : 2.2) : 1.5) * out_mb * (c.csplit / 2.0);
     if (c.kg > 1) us += c.kg == 4 ? 1.5 : waves == 16 ? 0.5 : 0.8;                        // the closing exchange through LDS (quarter tiles: a seventh of the data)
     return us;
 }
@@ -303,23 +332,23 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
 // tuning aid, menu index = shape + 7 * (csplit - 1) for the seven common shapes, then
 // 14 + further shape + 8 * (csplit - 1) for the eight further shapes: bf16 with two row blocks per wave, quarter tiles,
 // tile pairs, quarter tiles with two channel groups).
-Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, bool epilogue, const char *force);
+Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, bool epilogue, int force, bool gemm = false);
 
 // The search walks the whole menu, a few microseconds of host time -- as long as the smallest layers
 // run on the GPU -- so the last few answers are remembered (per layer, layout, epilogue and override).
-Candidate choose_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, bool epilogue = false)
+Candidate choose_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, bool epilogue = false, bool gemm = false)
 {
-    const char *force = getenv("CONV_MCMK_TILE");
-    if (force && (force[0] < '0' || force[0] > '9')) force = nullptr;
+    const int force = gemm ? forced_index(g_force_gemm_tile, "CONV_MCMK_GEMM_TILE") : forced_index(g_force_tile, "CONV_MCMK_TILE");
     struct Key {
         conv_mcmk_desc d;
-        int flags, forced;
+        int flags, forced, mb;
     };
     Key key;
     memset(&key, 0, sizeof(key));
     key.d = *d;
-    key.flags = (channels_last ? 1 : 0) | (epilogue ? 2 : 0);
-    key.forced = force ? atoi(force) : -1;
+    key.flags = (channels_last ? 1 : 0) | (epilogue ? 2 : 0) | (gemm ? 4 : 0);
+    key.forced = force;
+    key.mb = dm.mb;                       // a matrix product's rows may be (tap, kernel) pairs
     constexpr int kSlots = 32;
     static std::mutex mu;
     static Key keys[kSlots];
@@ -330,7 +359,7 @@ Candidate choose_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_la
         for (int i = 0; i < used; ++i)
             if (memcmp(&keys[i], &key, sizeof(Key)) == 0) return vals[i];
     }
-    const Candidate best = search_fused(d, dm, channels_last, epilogue, force);
+    const Candidate best = search_fused(d, dm, channels_last, epilogue, force, gemm);
     {
         std::lock_guard<std::mutex> lock(mu);
         keys[next] = key;
@@ -341,16 +370,25 @@ Candidate choose_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_la
     return best;
 }
 
-Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, bool epilogue, const char *force)
+// gemm: the layer is the matrix product of a staged variant seen as a 1 x 1 convolution (d->k == 1, no padding, unit
+// stride; the channels are the contraction index, the plane is the patch matrix's or the two-pass product's).  The
+// whole menu applies, and after it come the two flat shapes (1 x 224 columns of the plane taken as one row, 32-channel
+// chunks), each with the channels unsplit and split two, four and eight ways: indices 30 .. 37.
+Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, bool epilogue, int force, bool gemm)
 {
     Candidate best{};
     double best_cost = -1.0;
     const int menu_len = kConvShapes + kWideConvShapes;
-    for (int pass = 0, index = 0; pass < 2; ++pass)                    // common shapes, then the wide ones
-    for (int cs = 1; cs <= 2; ++cs)
-        for (int pos = pass == 0 ? 0 : kConvShapes; pos < (pass == 0 ? kConvShapes : menu_len); ++pos, ++index) {
-            const int sh = pos < kConvShapes ? pos : kWideConvShape[pos - kConvShapes];
+    // (the flat shapes also with the contraction split four and eight ways: a staged variant's product over C k k
+    // channels on a small plane has few tiles, and unlike the fused kernel's two-way split more than two partial sums
+    // meet at the atomics, so the last bits of such a result depend on the order they arrive in)
+    for (int pass = 0, index = 0; pass < (gemm ? 3 : 2); ++pass)       // common shapes, then the wide ones, then the flat ones
+    for (int cs = 1; cs <= (pass == 2 ? 8 : 2); cs *= 2)
+        for (int pos = pass == 0 ? 0 : pass == 1 ? kConvShapes : menu_len; pos < (pass == 0 ? kConvShapes : pass == 1 ? menu_len : menu_len + 2);
+             ++pos, ++index) {
+            const int sh = pos < kConvShapes ? pos : pos < menu_len ? kWideConvShape[pos - kConvShapes] : pos == menu_len ? kGemmShape : kWideGemmShape;
             const Candidate c = candidate(sh, cs);
+            if (sh == kWideGemmShape && d->dtype != CONV_MCMK_BF16) continue;
             // two row blocks per wave: bf16 operands, unit stride
             if (c.rb > 1 && (d->dtype != CONV_MCMK_BF16 || d->stride > 1 || d->k > 3)) continue;
             if (c.th == 7 && (d->stride > 1 || d->k > 5)) continue;
@@ -365,13 +403,23 @@ Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_la
             if (c.kg > 1 && d->k > 3) continue;
             // nor for a 1 x 1 kernel, whose chunks are too short to pay for the closing exchange (never the fastest
             // candidate on any 1 x 1 layer timed, either precision)
-            if (c.kg > 1 && d->k == 1) continue;
+            // (a staged variant's product contracts over C k k: thousands of channels on the deep layers, and
+            // there the groups are what fills the chip)
+            if (c.kg > 1 && d->k == 1 && !(gemm && d->c >= 1024) && force != index) continue;
             if (d->stride > 1 && sh >= kStridedShapes) continue;       // strided input tiles: 14 x 14 outputs only
             if (epilogue && cs > 1) continue;                          // partial sums cannot take the epilogue
             // strided bf16 tiles gathered from [C][H][W] with a kernel side of 5 or more exist for the
             // 2 x 4 wave layout only (register budget of the staging gather)
             if (d->stride > 1 && d->dtype == CONV_MCMK_BF16 && !channels_last && d->k >= 5 && sh != 1) continue;
-            const double cost = (force && atoi(force) == index) ? 0.0 : tile_cost(d, dm, c, d->k, channels_last);
+            double cost;
+            if (force == index) cost = 0.0;
+            else if (sh == kGemmShape || sh == kWideGemmShape) {
+                // the flat shapes see the plane as a single row of H W columns
+                conv_mcmk_desc flat = *d;
+                flat.h = 1;  flat.w = dm.q * dm.p;
+                const Dims fdm{1, dm.q * dm.p, dm.mb, 1};
+                cost = 1.2 * tile_cost(&flat, fdm, c, 1, channels_last);
+            } else cost = tile_cost(d, dm, c, d->k, channels_last);
             // equal estimates (layers that sit on a latency floor): the candidate with more workgroups keeps more
             // loads in flight
             const bool tie = best_cost >= 0 && cost <= best_cost + 1e-6 && cost >= best_cost - 1e-6;
@@ -388,14 +436,35 @@ Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_la
 // paper's conclusion calls for).  Pieces: the tile-kernel estimate above for the matrix work; the
 // memory-bound passes at the 3.5 TB/s they were measured to sustain plus a launch; the direct loop
 // nest at its measured 3 TFLOP/s.
-double gemm_cost(const conv_mcmk_desc *d, long long kc, long long cols, int row_groups)
+// The matrix product of a staged variant as the tile kernels see it: a 1 x 1 convolution of `kc` channels over a
+// ph x pw plane per image (im2col / im2row: the patch matrix, plane = the output's; two-pass: the input itself), rows =
+// row_groups x M.
+struct GemmView {
+    conv_mcmk_desc d;
+    Dims dm;
+};
+
+GemmView gemm_view(const conv_mcmk_desc *d, long long kc, int ph, int pw, int row_groups)
 {
-    conv_mcmk_desc g = *d;
-    g.c = (int)kc;  g.h = 1;  g.w = (int)cols;  g.k = 1;  g.pad = 0;  g.stride = 1;
-    Dims dm{1, (int)cols, ceil_div(d->m, 16) * row_groups, 1};
-    const Candidate c = candidate(kGemmShape, 1);
-    // a staged tile serves one tap, not k*k: about 1.2 x the fused kernel's time per MFMA
-    return 1.2 * tile_cost(&g, dm, c, 1);
+    GemmView v;
+    v.d = *d;
+    v.d.c = (int)kc;  v.d.h = ph;  v.d.w = pw;  v.d.k = 1;  v.d.pad = 0;  v.d.stride = 1;
+    v.dm = Dims{ph, pw, ceil_div(d->m, 16) * row_groups, 1};
+    return v;
+}
+
+double gemm_cost(const conv_mcmk_desc *d, long long kc, int ph, int pw, int row_groups, bool channels_last = false)
+{
+    const GemmView v = gemm_view(d, kc, ph, pw, row_groups);
+    const Candidate c = choose_fused(&v.d, v.dm, channels_last, false, true);
+    if (c.shape == kGemmShape || c.shape == kWideGemmShape) {
+        conv_mcmk_desc flat = v.d;
+        flat.h = 1;  flat.w = ph * pw;
+        const Dims fdm{1, ph * pw, v.dm.mb, 1};
+        // (deeper chunks, but a staged tile serves one tap, not k*k: about 1.2 x the fused kernel's time per MFMA)
+        return 1.2 * tile_cost(&flat, fdm, c, 1, channels_last);
+    }
+    return tile_cost(&v.d, v.dm, c, 1, channels_last);
 }
 
 // a memory-bound pass before or after the matrix kernel: its bytes, its launch, and the drain / fill
@@ -413,12 +482,13 @@ double variant_cost(const conv_mcmk_desc *d, const Dims &dm, int variant)
         return tile_cost(d, dm, choose_fused(d, dm, variant == CONV_MCMK_KN2COL), d->k, variant == CONV_MCMK_KN2COL);
     case CONV_MCMK_KN2ROW_2PASS: {
         const double planes = (double)d->n * d->m * d->h * d->w;
-        return gemm_cost(d, d->c, (long long)d->h * d->w, dm.taps) +
+        return gemm_cost(d, d->c, d->h, d->w, dm.taps) +
                stream_cost(4.0 * (dm.taps * planes + (double)d->n * d->m * dm.q * dm.p));
     }
     case CONV_MCMK_IM2COL:
     case CONV_MCMK_IM2ROW:
-        return stream_cost(elt * (in_elems + patch_elems)) + gemm_cost(d, (long long)d->c * dm.taps, (long long)dm.q * dm.p, 1);
+        return stream_cost(elt * (in_elems + patch_elems)) +
+               gemm_cost(d, (long long)d->c * dm.taps, dm.q, dm.p, 1, variant == CONV_MCMK_IM2ROW);
     default: {
         // one thread per output walks its C*k*k terms one after the other (0.12 us each when the chip
         // is not full); a full chip sustains 3 TFLOP/s
@@ -437,27 +507,20 @@ int launch_fused(const conv_mcmk_desc *d, const Dims &dm, const void *in, const 
                        channels_last, d->stride, ep);
 }
 
-// bf16 GEMMs take the shape with two row blocks per wave (128 rows per workgroup) when that still
-// leaves a workgroup for every compute unit (CONV_MCMK_GEMM_TILE = 7 or 11 overrides: tuning aid).
-int gemm_shape(const conv_mcmk_desc *d, const Dims &dm, long long cols, int row_groups)
+// Plain matrix product [row_groups M x kc] . [kc x ph pw] per image on the tile kernels: a 1 x 1 "convolution" over
+// the ph x pw plane, with the tile shape (2-D tiles, channel groups, channel split, or the flat 1 x 224 shape over the
+// plane taken as one row) chosen by the same estimate that serves the fused kernel.
+int launch_gemm(const conv_mcmk_desc *d, const void *bmat, const void *apk, float *cmat,
+                long long kc, int ph, int pw, int row_groups, hipStream_t st, bool channels_last = false)
 {
-    if (d->dtype != CONV_MCMK_BF16) return kGemmShape;
-    const char *force = getenv("CONV_MCMK_GEMM_TILE");
-    if (force && atoi(force) == kWideGemmShape) return kWideGemmShape;
-    if (force && atoi(force) == kGemmShape) return kGemmShape;
-    const TileShapeDesc &w = kTileShapes[kWideGemmShape];
-    const long long wide_wgs = (long long)d->n * ceil_div(cols, w.tw) * ceil_div((long long)dm.mb * row_groups, w.wm * w.rb);
-    return wide_wgs >= kNumCU ? kWideGemmShape : kGemmShape;
-}
-
-// Plain GEMM [rows x kc] . [kc x cols] per image on the same tile kernel: a 1x1 "convolution" over a
-// 1 x cols image.
-int launch_gemm(const conv_mcmk_desc *d, const Dims &dm, const void *bmat, const void *apk, float *cmat,
-                int kc, long long cols, int row_groups, hipStream_t st, bool channels_last = false)
-{
-    if (cols >= (1LL << 31)) return CONV_MCMK_ERR_SHAPE;
-    return launch_tile(d, dm, 1, gemm_shape(d, dm, cols, row_groups), 1, bmat, apk, cmat, kc, 1, (int)cols, 1, (int)cols, 0,
-                       row_groups, st, channels_last);
+    if ((long long)ph * pw >= (1LL << 31) || kc >= (1LL << 31)) return CONV_MCMK_ERR_SHAPE;
+    const GemmView v = gemm_view(d, kc, ph, pw, row_groups);
+    const Candidate c = choose_fused(&v.d, v.dm, channels_last, false, true);
+    const bool flat = c.shape == kGemmShape || c.shape == kWideGemmShape;
+    const int h = flat ? 1 : ph, w = flat ? ph * pw : pw;
+    Dims dm = v.dm;
+    dm.mb = ceil_div(d->m, 16);                  // launch_tile takes the blocks of one row group
+    return launch_tile(d, dm, 1, c.shape, c.csplit, bmat, apk, cmat, (int)kc, h, w, h, w, 0, row_groups, st, channels_last);
 }
 
 int common_ptr_checks(const void *I, const void *K, const void *O)
@@ -508,6 +571,43 @@ const char *conv_mcmk_strerror(int code)
 
 int conv_mcmk_check(const conv_mcmk_desc *desc, int variant) { return validate(desc, variant, nullptr); }
 
+int conv_mcmk_output_dims(const conv_mcmk_desc *desc, int *q, int *p)
+{
+    Dims dm;
+    // the staged two-pass variant takes every shape the library takes at all
+    const int rc = validate(desc, CONV_MCMK_KN2ROW_2PASS, &dm);
+    if (rc) return rc;
+    if (q) *q = dm.q;
+    if (p) *p = dm.p;
+    return CONV_MCMK_OK;
+}
+
+void conv_mcmk_force_tile(int index) { g_force_tile.store(index < 0 ? -1 : index, std::memory_order_relaxed); }
+void conv_mcmk_force_gemm_tile(int index) { g_force_gemm_tile.store(index < 0 ? -1 : index, std::memory_order_relaxed); }
+
+int conv_mcmk_probe_mfma(int dtype, int blocks, int iters, float *sink_dev, void *stream)
+{
+    if (!sink_dev) return CONV_MCMK_ERR_NULL;
+    if (misaligned(sink_dev)) return CONV_MCMK_ERR_ALIGN;
+    if (blocks < 1 || blocks > (1 << 20) || iters < 1) return CONV_MCMK_ERR_SHAPE;
+    if (dtype != CONV_MCMK_F32 && dtype != CONV_MCMK_BF16) return CONV_MCMK_ERR_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dtype == CONV_MCMK_BF16) hipLaunchKernelGGL(probe_mfma_kernel<true>, dim3(blocks), dim3(256), 0, st, sink_dev, iters);
+    else hipLaunchKernelGGL(probe_mfma_kernel<false>, dim3(blocks), dim3(256), 0, st, sink_dev, iters);
+    return launch_status();
+}
+
+int conv_mcmk_probe_copy(const void *src_dev, void *dst_dev, size_t bytes, void *stream)
+{
+    if (!src_dev || !dst_dev) return CONV_MCMK_ERR_NULL;
+    if (misaligned(src_dev) || misaligned(dst_dev)) return CONV_MCMK_ERR_ALIGN;
+    if (bytes % 16 != 0) return CONV_MCMK_ERR_SHAPE;
+    if (bytes == 0) return CONV_MCMK_OK;
+    hipLaunchKernelGGL(probe_copy_kernel, dim3(stream_grid(bytes / 16, 1)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const float4 *>(src_dev), static_cast<float4 *>(dst_dev), bytes / 16);
+    return launch_status();
+}
+
 int conv_mcmk_describe_plan(const conv_mcmk_desc *d, int variant, char *buf, size_t n)
 {
     Dims dm;
@@ -515,7 +615,17 @@ int conv_mcmk_describe_plan(const conv_mcmk_desc *d, int variant, char *buf, siz
     if (rc) return rc;
     if (!buf || n == 0) return CONV_MCMK_ERR_NULL;
     const char *type = d->dtype == CONV_MCMK_BF16 ? "bf16" : "f32";
-    const TileShapeDesc &g = kTileShapes[kGemmShape];
+    // the tile the matrix product of a staged variant would run on
+    auto gemm_text = [&](long long kc, int ph, int pw, int row_groups, bool cl, char *out, size_t len) {
+        const GemmView v = gemm_view(d, kc, ph, pw, row_groups);
+        const Candidate c = choose_fused(&v.d, v.dm, cl, false, true);
+        const bool flat = c.shape == kGemmShape || c.shape == kWideGemmShape;
+        const long long cols = flat ? ceil_div((long long)ph * pw, c.tw) : (long long)ceil_div(pw, c.tw) * ceil_div(ph, c.th);
+        snprintf(out, len, "tile %dx%d%s, waves %dx%d, row blocks %d, channel groups %d, channel split %d, %lld workgroups",
+                 c.th, c.tw, flat ? " over the flattened plane" : "", c.wm, c.wp, c.rb, c.kg, c.csplit,
+                 (long long)d->n * cols * ceil_div(v.dm.mb, c.wm * c.rb) * c.csplit);
+    };
+    char tile[160];
     switch (variant) {
     case CONV_MCMK_KN2ROW:
     case CONV_MCMK_KN2COL: {
@@ -528,17 +638,20 @@ int conv_mcmk_describe_plan(const conv_mcmk_desc *d, int variant, char *buf, siz
         break;
     }
     case CONV_MCMK_KN2ROW_2PASS:
-        snprintf(buf, n, "kn2row two-pass %s: GEMM [%d x %d].[%d x %d] per image (tile 1x%d, waves %dx%d), then shift-add, est %.1f us",
-                 type, dm.taps * d->m, d->c, d->c, d->h * d->w, g.tw, g.wm, g.wp, variant_cost(d, dm, variant));
+        gemm_text(d->c, d->h, d->w, dm.taps, false, tile, sizeof(tile));
+        snprintf(buf, n, "kn2row two-pass %s: GEMM [%d x %d].[%d x %d] per image (%s), then shift-add, est %.1f us",
+                 type, dm.taps * d->m, d->c, d->c, d->h * d->w, tile, variant_cost(d, dm, variant));
         break;
     case CONV_MCMK_IM2COL:
-        snprintf(buf, n, "im2col %s: patch matrix [%d x %d] per image, GEMM [%d x %d].[%d x %d] (tile 1x%d, waves %dx%d), est %.1f us",
-                 type, d->c * dm.taps, dm.q * dm.p, d->m, d->c * dm.taps, d->c * dm.taps, dm.q * dm.p, g.tw, g.wm, g.wp,
+        gemm_text((long long)d->c * dm.taps, dm.q, dm.p, 1, false, tile, sizeof(tile));
+        snprintf(buf, n, "im2col %s: patch matrix [%d x %d] per image, GEMM [%d x %d].[%d x %d] (%s), est %.1f us",
+                 type, d->c * dm.taps, dm.q * dm.p, d->m, d->c * dm.taps, d->c * dm.taps, dm.q * dm.p, tile,
                  variant_cost(d, dm, variant));
         break;
     case CONV_MCMK_IM2ROW:
-        snprintf(buf, n, "im2row %s: patch matrix [%d x %d] per image (channels last), GEMM [%d x %d].[%d x %d] (tile 1x%d, waves %dx%d), est %.1f us",
-                 type, dm.q * dm.p, d->c * dm.taps, dm.q * dm.p, d->c * dm.taps, d->c * dm.taps, d->m, g.tw, g.wm, g.wp,
+        gemm_text((long long)d->c * dm.taps, dm.q, dm.p, 1, true, tile, sizeof(tile));
+        snprintf(buf, n, "im2row %s: patch matrix [%d x %d] per image (channels last), GEMM [%d x %d].[%d x %d] (%s), est %.1f us",
+                 type, dm.q * dm.p, d->c * dm.taps, dm.q * dm.p, d->c * dm.taps, d->c * dm.taps, d->m, tile,
                  variant_cost(d, dm, variant));
         break;
     default:
@@ -649,7 +762,7 @@ int conv_mcmk_1x1(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_dev
     // without padding or stride the image is just H*W columns of the matrix [C x HW] (section III-A):
     // a plain GEMM with no tile edges inside the image
     if (d->pad == 0 && d->stride == 1)
-        return launch_gemm(d, dm, I_dev, Kp_dev, static_cast<float *>(O_dev), d->c, (long long)d->h * d->w, 1, st);
+        return launch_gemm(d, I_dev, Kp_dev, static_cast<float *>(O_dev), d->c, d->h, d->w, 1, st);
     return launch_fused(d, dm, I_dev, Kp_dev, static_cast<float *>(O_dev), st, false);
 }
 
@@ -664,18 +777,28 @@ int conv_mcmk_kn2row_2pass(const conv_mcmk_desc *d, const void *I_dev, const voi
     hipStream_t st = static_cast<hipStream_t>(stream);
     float *T = static_cast<float *>(ws);
     // pass 1: T[n][t*M+m][HW] = Kp[k*k*M x C] . I[n][C x HW]
-    rc = launch_gemm(d, dm, I_dev, Kp_dev, T, d->c, (long long)d->h * d->w, dm.taps, st);
+    rc = launch_gemm(d, I_dev, Kp_dev, T, d->c, d->h, d->w, dm.taps, st);
     if (rc) return rc;
     // pass 2: shift-add of the k*k planes
-    const int vec = dm.p % 4 == 0 ? 4 : 1;
-    const size_t total = (size_t)d->n * d->m * dm.q * (dm.p / vec);
+    const int vec = dm.p % 4 == 0 ? 4 : dm.p % 2 == 0 ? 2 : 1;
+    if (d->stride == 1 && (d->k == 3 || d->k == 5) && (size_t)dm.taps * d->m * d->h * d->w * sizeof(float) < (1ull << 31)) {
+        // the common case: the streaming form (one item per thread, images along the grid's second dimension)
+        const dim3 grid(stream_grid((size_t)d->m * dm.q * (dm.p / vec), 1), d->n < 65535 ? d->n : 65535);
+        auto launch = [&](auto kernel) {
+            hipLaunchKernelGGL(kernel, grid, dim3(256), 0, st, T, static_cast<float *>(O_dev), d->n, d->m, d->h, d->w, d->pad, dm.q, dm.p);
+        };
+        if (d->k == 3) { if (vec == 4) launch(shift_add_fast_kernel<4, 3>); else if (vec == 2) launch(shift_add_fast_kernel<2, 3>); else launch(shift_add_fast_kernel<1, 3>); }
+        else           { if (vec == 4) launch(shift_add_fast_kernel<4, 5>); else if (vec == 2) launch(shift_add_fast_kernel<2, 5>); else launch(shift_add_fast_kernel<1, 5>); }
+        return launch_status();
+    }
+    const int gvec = vec == 4 ? 4 : 1;
+    const size_t total = (size_t)d->n * d->m * dm.q * (dm.p / gvec);
     auto launch = [&](auto kernel) {
         hipLaunchKernelGGL(kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, T, static_cast<float *>(O_dev), d->n, d->m,
                            d->h, d->w, d->k, d->pad, d->stride, dm.q, dm.p);
     };
-    if (vec == 4 && d->k == 3) launch(shift_add_f32_kernel<4, 3>);
-    else if (vec == 4 && d->k == 5) launch(shift_add_f32_kernel<4, 5>);
-    else if (vec == 4) launch(shift_add_f32_kernel<4, 0>);
+    if (gvec == 4 && d->k == 3) launch(shift_add_f32_kernel<4, 3>);
+    else if (gvec == 4) launch(shift_add_f32_kernel<4, 0>);
     else if (d->k == 3) launch(shift_add_f32_kernel<1, 3>);
     else launch(shift_add_f32_kernel<1, 0>);
     return launch_status();
@@ -690,19 +813,39 @@ int conv_mcmk_im2col(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_
     if ((rc = common_ptr_checks(I_dev, Kp_dev, O_dev))) return rc;
     if ((rc = workspace_check(d, CONV_MCMK_IM2COL, ws, ws_bytes))) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    // widest store the row length allows: 16 bytes when P is a multiple of 4 (fp32) / 8 (bf16)
     const bool bf16 = d->dtype == CONV_MCMK_BF16;
-    const int vec = bf16 ? (dm.p % 8 == 0 ? 8 : 1) : (dm.p % 4 == 0 ? 4 : 1);
-    const size_t total = (size_t)d->n * d->c * dm.q * (dm.p / vec);
-    const dim3 grid(grid_for(total, 256)), block(256);
+    if (d->stride == 1 && (d->k == 3 || d->k == 5)) {
+        // the common case: the streaming form; the widest store the row length allows, up to 16 bytes
+        const int vmax = bf16 ? 8 : 4;
+        int vec = vmax;
+        while (dm.p % vec != 0) vec /= 2;
+        const dim3 grid(stream_grid((size_t)d->c * dm.q * (dm.p / vec), 1), d->n < 65535 ? d->n : 65535), block(256);
+#define MCMK_IM2COL_FAST(T, V, KS)                                                                            \
+    hipLaunchKernelGGL((im2col_build_fast_kernel<T, V, KS>), grid, block, 0, st, static_cast<const T *>(I_dev), \
+                       static_cast<T *>(ws), d->n, d->c, d->h, d->w, d->pad, dm.q, dm.p)
+#define MCMK_IM2COL_FAST_K(T, V) do { if (d->k == 3) MCMK_IM2COL_FAST(T, V, 3); else MCMK_IM2COL_FAST(T, V, 5); } while (0)
+        if (bf16) {
+            if (vec == 8) MCMK_IM2COL_FAST_K(uint16_t, 8); else if (vec == 4) MCMK_IM2COL_FAST_K(uint16_t, 4);
+            else if (vec == 2) MCMK_IM2COL_FAST_K(uint16_t, 2); else MCMK_IM2COL_FAST_K(uint16_t, 1);
+        } else {
+            if (vec == 4) MCMK_IM2COL_FAST_K(float, 4); else if (vec == 2) MCMK_IM2COL_FAST_K(float, 2); else MCMK_IM2COL_FAST_K(float, 1);
+        }
+#undef MCMK_IM2COL_FAST_K
+#undef MCMK_IM2COL_FAST
+    } else {
+        // any kernel side and stride: 16-byte stores when P is a multiple of 4 (fp32) / 8 (bf16)
+        const int vec = bf16 ? (dm.p % 8 == 0 ? 8 : 1) : (dm.p % 4 == 0 ? 4 : 1);
+        const size_t total = (size_t)d->n * d->c * dm.q * (dm.p / vec);
+        const dim3 grid(grid_for(total, 256)), block(256);
 #define MCMK_IM2COL(T, V)                                                                             \
     hipLaunchKernelGGL((im2col_build_kernel<T, V>), grid, block, 0, st, static_cast<const T *>(I_dev), \
                        static_cast<T *>(ws), d->n, d->c, d->h, d->w, d->k, d->pad, d->stride, dm.q, dm.p)
-    if (bf16) { if (vec == 8) MCMK_IM2COL(uint16_t, 8); else MCMK_IM2COL(uint16_t, 1); }
-    else      { if (vec == 4) MCMK_IM2COL(float, 4);    else MCMK_IM2COL(float, 1); }
+        if (bf16) { if (vec == 8) MCMK_IM2COL(uint16_t, 8); else MCMK_IM2COL(uint16_t, 1); }
+        else      { if (vec == 4) MCMK_IM2COL(float, 4);    else MCMK_IM2COL(float, 1); }
 #undef MCMK_IM2COL
+    }
     if ((rc = launch_status())) return rc;
-    return launch_gemm(d, dm, ws, Kp_dev, static_cast<float *>(O_dev), d->c * dm.taps, (long long)dm.q * dm.p, 1, st);
+    return launch_gemm(d, ws, Kp_dev, static_cast<float *>(O_dev), (long long)d->c * dm.taps, dm.q, dm.p, 1, st);
 }
 
 int conv_mcmk_im2row(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_dev, void *O_dev,
@@ -716,8 +859,7 @@ int conv_mcmk_im2row(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool bf16 = d->dtype == CONV_MCMK_BF16;
     const int vec = bf16 ? 8 : 4;
-    const size_t total = (size_t)d->n * dm.q * dm.p * dm.taps * (d->c / vec);
-    const dim3 grid(grid_for(total, 256)), block(256);
+    const dim3 grid(stream_grid((size_t)dm.q * dm.p * dm.taps * (d->c / vec), 1), d->n < 65535 ? d->n : 65535), block(256);
     if (bf16)
         hipLaunchKernelGGL((im2row_build_kernel<uint16_t, 8>), grid, block, 0, st, static_cast<const uint16_t *>(I_dev),
                            static_cast<uint16_t *>(ws), d->n, d->c, d->h, d->w, d->k, d->pad, d->stride, dm.q, dm.p);
@@ -726,7 +868,7 @@ int conv_mcmk_im2row(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_
                            static_cast<float *>(ws), d->n, d->c, d->h, d->w, d->k, d->pad, d->stride, dm.q, dm.p);
     if ((rc = launch_status())) return rc;
     // O[n][q*P+p][m] = rows[n][q*P+p][:] . Khat[:][m]: the channels-last GEMM
-    return launch_gemm(d, dm, ws, Kp_dev, static_cast<float *>(O_dev), d->c * dm.taps, (long long)dm.q * dm.p, 1, st, true);
+    return launch_gemm(d, ws, Kp_dev, static_cast<float *>(O_dev), (long long)d->c * dm.taps, dm.q, dm.p, 1, st, true);
 }
 
 int conv_mcmk_direct(const conv_mcmk_desc *d, const void *I_dev, const void *K_dev, void *O_dev,

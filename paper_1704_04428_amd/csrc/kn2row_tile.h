@@ -390,6 +390,7 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
     // ---- add the channel groups' partial sums: groups 1.. park theirs in LDS (the staging buffers
     // are free now), group 0 adds them in group order and goes on to write the tile
     if constexpr (KG > 1) {
+        static_assert((size_t)(KG - 1) * WM * WP * PBW * 64 * sizeof(f32x4) <= S::kLdsBytes, "parked sums must fit the staging buffers");
         f32x4 *park = reinterpret_cast<f32x4 *>(lds_all);
         const int slot = (wm + WM * wp) * PBW;                    // same (wm, wp) in every group
         if (kg > 0) {

@@ -2,6 +2,8 @@
 //   MCMK_KS    kernel side (1 to 7)
 //   MCMK_BF16  0: fp32 operands, 1: bf16 operands
 // and gets run_tile_<type>_k<KS>() with every tile shape of kTileShapes instantiated.
+#include <atomic>
+
 #include "tile_dispatch.h"
 #if MCMK_BF16
 #include "kn2row_tile_bf16.h"
@@ -29,15 +31,16 @@ int launch_shape(const TileRequest &rq)
     constexpr size_t kLds = S::kLdsBytes;            // every channel group has its own pair of buffers
     static_assert(kLds <= 160 * 1024, "the tile does not fit the LDS of a compute unit");
     if (kLds > 65536) {
-        // more than 64 KiB of dynamic LDS has to be allowed per kernel, once per device
-        static bool allowed[64] = {};
+        // more than 64 KiB of dynamic LDS has to be allowed per kernel, once per device (two threads that both find
+        // the flag clear both set the attribute, which is harmless; the flag itself is read and written atomically)
+        static std::atomic<bool> allowed[64] = {};
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 1;
-        if (!allowed[dev]) {
+        if (!allowed[dev].load(std::memory_order_acquire)) {
             if (hipFuncSetAttribute(reinterpret_cast<const void *>(&kn2row_tile_bf16<MCMK_KS, TH, TW, WM, WP, CL, ST, RB, KG>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds) != hipSuccess)
                 return 1;
-            allowed[dev] = true;
+            allowed[dev].store(true, std::memory_order_release);
         }
     }
     hipLaunchKernelGGL((kn2row_tile_bf16<MCMK_KS, TH, TW, WM, WP, CL, ST, RB, KG>), dim3((unsigned)blocks), dim3(S::kThreads * KG),
@@ -45,15 +48,16 @@ int launch_shape(const TileRequest &rq)
 #else
     using S = TileShape<MCMK_KS, TH, TW, WM, WP, CCH, KG, ST, VQL>;
     if (S::kLdsBytes > 65536) {
-        // more than 64 KiB of dynamic LDS has to be allowed per kernel, once per device
-        static bool allowed[64] = {};
+        // more than 64 KiB of dynamic LDS has to be allowed per kernel, once per device (two threads that both find
+        // the flag clear both set the attribute, which is harmless; the flag itself is read and written atomically)
+        static std::atomic<bool> allowed[64] = {};
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 1;
-        if (!allowed[dev]) {
+        if (!allowed[dev].load(std::memory_order_acquire)) {
             if (hipFuncSetAttribute(reinterpret_cast<const void *>(&kn2row_tile_f32<MCMK_KS, TH, TW, WM, WP, CCH, CL, KG, ST, VQL>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::kLdsBytes) != hipSuccess)
                 return 1;
-            allowed[dev] = true;
+            allowed[dev].store(true, std::memory_order_release);
         }
     }
     hipLaunchKernelGGL((kn2row_tile_f32<MCMK_KS, TH, TW, WM, WP, CCH, CL, KG, ST, VQL>), dim3((unsigned)blocks), dim3(S::kThreads),

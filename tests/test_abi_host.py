@@ -162,7 +162,7 @@ def test_plan_selection_for_benchmark_layers(lib, monkeypatch):
     """The per-layer choice of the fused kernel (host logic only): the shapes measured fastest on
     the benchmark layers."""
     from paper_1704_04428_amd import workloads as wl
-    monkeypatch.delenv("CONV_MCMK_TILE", raising=False)
+    B.conv_mcmk_force_tile(-1)
     want = {
         # single small images: quarter tiles, so that 4 x 16 (tiles x row blocks) becomes 256 workgroups
         "cfg3_alexnet_conv2": "tile 7x7, waves 1x4, row blocks 1, channel groups 1, channel split 1, 256 workgroups",
@@ -202,21 +202,21 @@ def test_plan_selection_for_benchmark_layers(lib, monkeypatch):
         B.conv_mcmk_describe_plan(B.desc(1, 8, 10, 10, 8, 3, 1, stride=3), B.KN2ROW)
     # stride 2: 14 x 14 output tiles only, Q = P = 5 here
     assert "tile 14x14" in B.conv_mcmk_describe_plan(B.desc(1, 8, 10, 10, 8, 3, 1, stride=2), B.KN2ROW)
-    monkeypatch.setenv("CONV_MCMK_TILE", "5")
+    B.conv_mcmk_force_tile(5)
     assert "tile 16x16, waves 1x4, row blocks 1, channel groups 1, channel split 1" in B.conv_mcmk_describe_plan(d, B.KN2ROW)
     assert "tile 14x14" in B.conv_mcmk_describe_plan(B.desc(1, 8, 10, 10, 8, 3, 1, stride=2), B.KN2ROW)   # 16 x 16: not with a stride
-    monkeypatch.setenv("CONV_MCMK_TILE", "6")
+    B.conv_mcmk_force_tile(6)
     assert "channel groups 4" in B.conv_mcmk_describe_plan(d, B.KN2ROW)
     # bf16 operands on the deep 56 x 56 layer: two row blocks per wave; whole image rows for the [M][Q][P] output
     L = wl.LAYERS["cfg5a_vgg_deep56"]
-    monkeypatch.delenv("CONV_MCMK_TILE")
+    B.conv_mcmk_force_tile(-1)
     db = B.desc(L.n, L.c, L.h, L.w, L.m, L.k, L.pad, 1, B.BF16)
     assert "tile 4x56, waves 4x2, row blocks 2" in B.conv_mcmk_describe_plan(db, B.KN2ROW)
     assert "tile 14x14, waves 4x2, row blocks 2" in B.conv_mcmk_describe_plan(db, B.KN2COL)
     # a 1 x 1 layer with many tiles: no channel groups (they measured 24 us against 9.9 us on 16 x 16 tiles)
     plan = B.conv_mcmk_describe_plan(B.desc(8, 256, 56, 56, 64, 1, 0, 1, B.BF16), B.KN2ROW)
     assert "tile 16x16" in plan and "channel groups 1" in plan, plan
-    monkeypatch.setenv("CONV_MCMK_TILE", "6")
+    B.conv_mcmk_force_tile(6)
     assert "channel groups 4" in B.conv_mcmk_describe_plan(B.desc(1, 8, 10, 10, 8, 3, 1, 1, B.BF16), B.KN2ROW)
     # an entry the kernel side does not have is ignored: the selector's own choice stands
     assert "channel groups 1" in B.conv_mcmk_describe_plan(B.desc(1, 8, 10, 10, 8, 5, 2), B.KN2ROW)
@@ -243,7 +243,7 @@ def test_variant_selection(lib, monkeypatch):
     staged variant where it does not, the workspace limit honoured."""
     import ctypes
     from paper_1704_04428_amd import workloads as wl
-    monkeypatch.delenv("CONV_MCMK_TILE", raising=False)
+    B.conv_mcmk_force_tile(-1)
     for L in list(wl.LAYERS.values()) + list(wl.GENERALISED_LAYERS.values()):
         d = B.desc(L.n, L.c, L.h, L.w, L.m, L.k, L.pad, L.stride)
         variant, est = B.conv_mcmk_select(d)

@@ -1,6 +1,9 @@
-"""The benchmark configurations at full size, in the launch configuration bench.py times:
-sampled outputs against the oracle (it computes single outputs one by one), plus whole-output
-comparison for the shapes the oracle finishes in seconds."""
+"""The benchmark configurations at full size, in the launch configuration bench.py times: the whole
+output of the fused kernels (kn2row, kn2col; fp32 and bf16 operands) against the oracle, element by
+element, on every configuration; the staged variants whole on the small configurations and on sampled
+outputs (which the oracle computes one by one) plus agreement with the fused kernel on the large ones."""
+import functools
+
 import numpy as np
 import pytest
 
@@ -27,8 +30,36 @@ def test_whole_output(layer, name, variant):
     assert_within_bound(got, ref, absref, TOL_F32, f"{name} {layer}")
 
 
+LARGE = ["cfg4_vgg_early", "cfg5a_vgg_deep56", "cfg5b_vgg_deep28", "cfg5c_vgg_deep14"]
+
+
+@functools.lru_cache(maxsize=None)
+def _whole_oracle(layer):
+    """Inputs and the oracle's whole output of a large configuration (a few seconds on the host's cores), shared by
+    the tests below."""
+    L = wl.LAYERS[layer]
+    I, K = wl.make_input(L), wl.make_kernel(L)
+    ref, absref = oracle.mcmk(I, K, L.pad)
+    return I, K, ref, absref
+
+
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+@pytest.mark.parametrize("name,variant", [("kn2row", B.KN2ROW), ("kn2col", B.KN2COL)])
+@pytest.mark.parametrize("layer", LARGE)
+def test_whole_output_of_the_fused_kernels_on_the_large_layers(layer, name, variant, dtype):
+    """Every output element of the VGG-like layers, in the tile shape the selector picks for them (the one the
+    benchmark times), within 1e-4 (fp32) / 1e-2 (bf16) of sum|K||I| of the oracle's value."""
+    from gpu_util import TOL_BF16
+    L = wl.LAYERS[layer]
+    announce("whole", layer, name, "bf16" if dtype == B.BF16 else "f32")
+    I, K, ref, absref = _whole_oracle(layer)
+    got = run_variant(variant, I, K, L.pad, dtype=dtype)
+    assert got.shape == (L.n, L.m, L.q, L.p)
+    assert_within_bound(got, ref, absref, TOL_BF16 if dtype == B.BF16 else TOL_F32, f"{name} {layer} whole output")
+
+
 @pytest.mark.parametrize("name,variant", VARIANTS)
-@pytest.mark.parametrize("layer", ["cfg4_vgg_early", "cfg5a_vgg_deep56", "cfg5b_vgg_deep28", "cfg5c_vgg_deep14"])
+@pytest.mark.parametrize("layer", LARGE)
 def test_sampled_outputs(layer, name, variant):
     L = wl.LAYERS[layer]
     if variant == B.DIRECT and L.flops > 1e10:

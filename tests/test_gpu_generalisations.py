@@ -100,10 +100,10 @@ def test_every_strided_tile_shape(k, pad, dtype, monkeypatch):
     for index in (0, 1, 2, 3, 6, 7, 8, 9):
         for variant in (B.KN2ROW, B.KN2COL):
             announce("strided menu", "k", k, "dtype", dtype, "tile", index, "variant", variant)
-            monkeypatch.setenv("CONV_MCMK_TILE", str(index))
+            B.conv_mcmk_force_tile(index)
             got = run_variant(variant, I, K, pad, dtype=dtype, stride=2)
             assert_within_bound(got, ref, absref, tol, f"strided tile {index} k={k} dtype={dtype} variant={variant}")
-    monkeypatch.delenv("CONV_MCMK_TILE")
+    B.conv_mcmk_force_tile(-1)
 
 
 # ------------------------------------------------------------------ bias / rectifier epilogue
@@ -142,13 +142,13 @@ def test_epilogue_on_integer_data_is_bit_exact(monkeypatch):
     for index in (None, 0, 2, 5, 6, 7, 13):          # 7 and 13 ask for a channel split, which the epilogue must refuse to use
         announce("epilogue exact-int", "tile", index)
         if index is None:
-            monkeypatch.delenv("CONV_MCMK_TILE", raising=False)
+            B.conv_mcmk_force_tile(-1)
         else:
-            monkeypatch.setenv("CONV_MCMK_TILE", str(index))
+            B.conv_mcmk_force_tile(index)
         for variant in (B.KN2ROW, B.KN2COL):
             got = run_variant(variant, I, K, pad, epilogue=(bias, True))
             np.testing.assert_array_equal(got.astype(np.float64), want)
-    monkeypatch.delenv("CONV_MCMK_TILE")
+    B.conv_mcmk_force_tile(-1)
 
 
 # ------------------------------------------------------------------ the 1 x 1 entry point (section III-A's building block)
@@ -195,9 +195,9 @@ def test_one_by_one_entry_point_refuses_larger_kernels():
     (2, 3, 224, 224, 64, 7, 3, 2),       # an RGB first layer, 7 x 7 with stride 2: the one-channel-quad kernels
     (2, 3, 112, 112, 32, 3, 1, 1),
 ])
-def test_selected_variant_is_correct_and_near_the_fastest(case):
-    """conv_mcmk_select + Plan.auto: the chosen variant gives the oracle's result, and none of the
-    other variants in the same layout is more than 1.5 x faster when timed here."""
+def test_selected_variant_is_correct(case):
+    """conv_mcmk_select + Plan.auto: the chosen variant runs and gives the oracle's result.  (How close the choice
+    is to the fastest variant is a timing question: bench.py --selector reports it.)"""
     import torch
     announce("select", case)
     n, c, h, w, m, k, pad, stride = case
@@ -205,30 +205,17 @@ def test_selected_variant_is_correct_and_near_the_fastest(case):
     ref, absref = oracle.mcmk(I, K, pad, stride)
     d = B.desc(n, c, h, w, m, k, pad, stride)
     I_dev, K_dev = torch.from_numpy(I).cuda(), torch.from_numpy(K).cuda()
-    chosen, _ = B.conv_mcmk_select(d)
+    chosen, est = B.conv_mcmk_select(d)
+    assert est > 0
     plan = B.Plan.auto(d, K_dev)
     assert plan.variant == chosen
     got = plan.run(I_dev).cpu().numpy()
     assert_within_bound(got, ref, absref, TOL_F32, f"selected variant {chosen} {case}")
-
-    def timed(p):
-        for _ in range(20):
-            p.run(I_dev)
-        torch.cuda.synchronize()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(50):
-            p.run(I_dev)
-        b.record()
-        torch.cuda.synchronize()
-        return a.elapsed_time(b) / 50
-
-    times = {}
+    # every other variant that takes the layer agrees with the oracle too, so the choice is a matter of time only
     for variant in (B.KN2ROW, B.KN2ROW_2PASS, B.IM2COL, B.DIRECT):
-        if B.conv_mcmk_check(d, variant) == B.OK:
-            times[variant] = timed(B.Plan(d, variant, K_dev))
-    announce("select times (ms)", {v: round(t, 4) for v, t in times.items()}, "chosen", chosen)
-    assert times[chosen] <= 1.5 * min(times.values()), (times, chosen)
+        if variant != chosen and B.conv_mcmk_check(d, variant) == B.OK:
+            got = B.Plan(d, variant, K_dev).run(I_dev).cpu().numpy()
+            assert_within_bound(got, ref, absref, TOL_F32, f"variant {variant} {case}")
 
 
 # ------------------------------------------------------------------ the one-call form of the binding

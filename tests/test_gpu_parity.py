@@ -276,10 +276,32 @@ def test_every_tile_shape_of_the_menu(k, pad, dtype, monkeypatch):
     for index in range(30):
         for variant in (B.KN2ROW, B.KN2COL):
             announce("menu", "k", k, "dtype", dtype, "tile", index, "variant", variant)
-            monkeypatch.setenv("CONV_MCMK_TILE", str(index))
+            B.conv_mcmk_force_tile(index)
             got = run_variant(variant, I, K, pad, dtype=dtype)
             assert_within_bound(got, ref, absref, tol, f"tile {index} k={k} dtype={dtype} variant={variant}")
-    monkeypatch.delenv("CONV_MCMK_TILE")
+    B.conv_mcmk_force_tile(-1)
+
+
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16])
+@pytest.mark.parametrize("case", [(2, 24, 19, 22, 40, 3, 1, 1), (1, 40, 30, 17, 24, 2, 1, 1), (2, 16, 21, 21, 20, 3, 1, 2)])
+def test_every_tile_shape_of_the_staged_variants_matrix_product(case, dtype):
+    """The matrix product of im2col, im2row and the two-pass variant (sections II-B, III-A) runs on the same tile
+    kernels as a 1 x 1 convolution over the patch matrix / the input, with the tile shape picked from the fused
+    kernel's menu plus the flat shapes (38 entries); force every entry, so that each instantiation is checked with
+    rows that are (tap, kernel) pairs, with the channel split and with channel groups."""
+    from gpu_util import TOL_BF16
+    n, c, h, w, m, k, pad, stride = case
+    I = wl.uniform(700 + k, n * c * h * w, -1, 1).reshape(n, c, h, w)
+    K = wl.normal(701 + k, m * c * k * k, 0.5).reshape(m, c, k, k)
+    ref, absref = oracle.mcmk(I, K, pad, stride)
+    tol = TOL_BF16 if dtype == B.BF16 else TOL_F32
+    for index in list(range(38)) + [-1]:
+        for variant in (B.IM2COL, B.KN2ROW_2PASS, B.IM2ROW):
+            announce("gemm menu", case, "dtype", dtype, "tile", index, "variant", variant)
+            B.conv_mcmk_force_gemm_tile(index)
+            got = run_variant(variant, I, K, pad, dtype=dtype, stride=stride)
+            assert_within_bound(got, ref, absref, tol, f"gemm tile {index} {case} dtype={dtype} variant={variant}")
+    B.conv_mcmk_force_gemm_tile(-1)
 
 
 @pytest.mark.parametrize("c", [128, 144, 176, 272])
@@ -295,12 +317,12 @@ def test_layers_deep_enough_for_a_barrier_every_second_chunk(c, monkeypatch):
         for variant in (B.KN2ROW, B.KN2COL):
             announce("deep", c, "tile", index, "variant", variant)
             if index is None:
-                monkeypatch.delenv("CONV_MCMK_TILE", raising=False)
+                B.conv_mcmk_force_tile(-1)
             else:
-                monkeypatch.setenv("CONV_MCMK_TILE", str(index))
+                B.conv_mcmk_force_tile(index)
             got = run_variant(variant, I, K, pad)
             np.testing.assert_array_equal(got.astype(np.float64), ref)
-    monkeypatch.delenv("CONV_MCMK_TILE", raising=False)
+    B.conv_mcmk_force_tile(-1)
 
 
 @pytest.mark.parametrize("k,pad", [(3, 1), (5, 2), (7, 3), (3, 0), (7, 6)])
@@ -316,21 +338,21 @@ def test_few_channel_layers(c, k, pad, monkeypatch):
     for index in (None, 0, 3, 4, 1):
         announce("few channels", c, k, pad, "tile", index)
         if index is None:
-            monkeypatch.delenv("CONV_MCMK_TILE", raising=False)
+            B.conv_mcmk_force_tile(-1)
         else:
-            monkeypatch.setenv("CONV_MCMK_TILE", str(index))
+            B.conv_mcmk_force_tile(index)
         got = run_variant(B.KN2ROW, I, K, pad)
         np.testing.assert_array_equal(got.astype(np.float64), ref)
     ref2, _ = oracle.mcmk(I, K, pad, 2)
     for index in (None, 0, 1, 2):                 # stride 2: shapes 0 and 1 have the lean form, 2 has not
         announce("few channels, stride 2", c, k, pad, "tile", index)
         if index is None:
-            monkeypatch.delenv("CONV_MCMK_TILE", raising=False)
+            B.conv_mcmk_force_tile(-1)
         else:
-            monkeypatch.setenv("CONV_MCMK_TILE", str(index))
+            B.conv_mcmk_force_tile(index)
         got = run_variant(B.KN2ROW, I, K, pad, stride=2)
         np.testing.assert_array_equal(got.astype(np.float64), ref2)
-    monkeypatch.delenv("CONV_MCMK_TILE", raising=False)
+    B.conv_mcmk_force_tile(-1)
 
 
 @pytest.mark.parametrize("case", [
