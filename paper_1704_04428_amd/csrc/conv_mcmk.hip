@@ -334,6 +334,40 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
 // tile pairs, quarter tiles with two channel groups).
 Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, bool epilogue, int force, bool gemm = false);
 
+// The tile a staged variant's matrix product runs on unless one is forced: the flat shape (64 or 128 rows x 224
+// columns of the plane taken as one row, 32-channel chunks), with the contraction split 1, 2, 4 or 8 ways.  A split
+// buys workgroups for a product with few tiles (two per compute unit hide each other's staging; below one per unit
+// the chip is idle in proportion) and pays a zero fill plus one atomic add per part and output element.  The rates
+// are what the kernel sustained on the benchmark layers; timings of every menu entry there put this rule within a
+// tenth of the best entry (the 2-D tiles of the fused kernel stage too little per barrier for a product whose every
+// value is used once, and the estimate that serves the fused kernel misjudges them by up to 40 % here).
+Candidate flat_gemm_candidate(const conv_mcmk_desc *d, const Dims &dm, bool channels_last)
+{
+    const bool bf16 = d->dtype == CONV_MCMK_BF16;
+    const long long cols = (long long)dm.q * dm.p;
+    const int chunks = ceil_div(d->c, 32);
+    auto wgs = [&](int shape) {
+        const TileShapeDesc &t = kTileShapes[shape];
+        return (long long)d->n * ceil_div(cols, t.tw) * ceil_div(dm.mb, t.wm * t.rb);
+    };
+    // bf16: two row blocks per wave (half the LDS reads per product) where that alone fills the chip twice over
+    if (bf16 && wgs(kWideGemmShape) >= 2 * kNumCU) return candidate(kWideGemmShape, 1);
+    const double flop = 2.0 * d->n * (dm.mb * 16.0) * cols * d->c;
+    const double out_mb = (double)d->n * (dm.mb * 16.0) * cols * 4.0e-6;
+    int best = 1;
+    double best_us = 0.0;
+    for (int cs = 1; cs <= 8 && (cs == 1 || chunks / cs >= 2); cs *= 2) {
+        const long long w = wgs(kGemmShape) * cs;
+        // fraction of the matrix peak the kernel sustains: two workgroups per unit, one, or a partly idle chip
+        const double full = bf16 ? 0.14 : 0.62, single = bf16 ? 0.09 : 0.50;
+        const double eff = w >= 448 ? full : w >= kNumCU ? single : single * (double)w / kNumCU;
+        double us = flop / ((bf16 ? 2500.0e6 : 157.3e6) * eff);
+        if (cs > 1) us += 3.0 + (channels_last ? 3.1 : 1.6) * out_mb * (cs / 2.0);
+        if (cs == 1 || us < best_us) { best = cs; best_us = us; }
+    }
+    return candidate(kGemmShape, best);
+}
+
 // The search walks the whole menu, a few microseconds of host time -- as long as the smallest layers
 // run on the GPU -- so the last few answers are remembered (per layer, layout, epilogue and override).
 Candidate choose_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, bool epilogue = false, bool gemm = false)
@@ -359,7 +393,7 @@ Candidate choose_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_la
         for (int i = 0; i < used; ++i)
             if (memcmp(&keys[i], &key, sizeof(Key)) == 0) return vals[i];
     }
-    const Candidate best = search_fused(d, dm, channels_last, epilogue, force, gemm);
+    const Candidate best = (gemm && force < 0) ? flat_gemm_candidate(d, dm, channels_last) : search_fused(d, dm, channels_last, epilogue, force, gemm);
     {
         std::lock_guard<std::mutex> lock(mu);
         keys[next] = key;
@@ -549,6 +583,38 @@ int fused_entry(const conv_mcmk_desc *d, int variant, const void *I_dev, const v
     if (ep.bias && (reinterpret_cast<uintptr_t>(ep.bias) & 3u) != 0) return CONV_MCMK_ERR_ALIGN;
     return launch_fused(d, dm, I_dev, Kp_dev, static_cast<float *>(O_dev), static_cast<hipStream_t>(stream),
                         variant == CONV_MCMK_KN2COL, ep);
+}
+
+// The two passes of section III-A on a product buffer T of N * k*k*M * H*W floats.
+int two_pass(const conv_mcmk_desc *d, const Dims &dm, const void *I_dev, const void *Kp_dev, void *O_dev, float *T, hipStream_t st)
+{
+    int rc;
+    // pass 1: T[n][t*M+m][HW] = Kp[k*k*M x C] . I[n][C x HW]
+    rc = launch_gemm(d, I_dev, Kp_dev, T, d->c, d->h, d->w, dm.taps, st);
+    if (rc) return rc;
+    // pass 2: shift-add of the k*k planes
+    const int vec = dm.p % 4 == 0 ? 4 : dm.p % 2 == 0 ? 2 : 1;
+    if (d->stride == 1 && (d->k == 3 || d->k == 5) && (size_t)dm.taps * d->m * d->h * d->w * sizeof(float) < (1ull << 31)) {
+        // the common case: the streaming form (one item per thread, images along the grid's second dimension)
+        const dim3 grid(stream_grid((size_t)d->m * dm.q * (dm.p / vec), 1), d->n < 65535 ? d->n : 65535);
+        auto launch = [&](auto kernel) {
+            hipLaunchKernelGGL(kernel, grid, dim3(256), 0, st, T, static_cast<float *>(O_dev), d->n, d->m, d->h, d->w, d->pad, dm.q, dm.p);
+        };
+        if (d->k == 3) { if (vec == 4) launch(shift_add_fast_kernel<4, 3>); else if (vec == 2) launch(shift_add_fast_kernel<2, 3>); else launch(shift_add_fast_kernel<1, 3>); }
+        else           { if (vec == 4) launch(shift_add_fast_kernel<4, 5>); else if (vec == 2) launch(shift_add_fast_kernel<2, 5>); else launch(shift_add_fast_kernel<1, 5>); }
+        return launch_status();
+    }
+    const int gvec = vec == 4 ? 4 : 1;
+    const size_t total = (size_t)d->n * d->m * dm.q * (dm.p / gvec);
+    auto launch = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, T, static_cast<float *>(O_dev), d->n, d->m,
+                           d->h, d->w, d->k, d->pad, d->stride, dm.q, dm.p);
+    };
+    if (gvec == 4 && d->k == 3) launch(shift_add_f32_kernel<4, 3>);
+    else if (gvec == 4) launch(shift_add_f32_kernel<4, 0>);
+    else if (d->k == 3) launch(shift_add_f32_kernel<1, 3>);
+    else launch(shift_add_f32_kernel<1, 0>);
+    return launch_status();
 }
 
 }  // namespace
@@ -774,34 +840,7 @@ int conv_mcmk_kn2row_2pass(const conv_mcmk_desc *d, const void *I_dev, const voi
     if (rc) return rc;
     if ((rc = common_ptr_checks(I_dev, Kp_dev, O_dev))) return rc;
     if ((rc = workspace_check(d, CONV_MCMK_KN2ROW_2PASS, ws, ws_bytes))) return rc;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    float *T = static_cast<float *>(ws);
-    // pass 1: T[n][t*M+m][HW] = Kp[k*k*M x C] . I[n][C x HW]
-    rc = launch_gemm(d, I_dev, Kp_dev, T, d->c, d->h, d->w, dm.taps, st);
-    if (rc) return rc;
-    // pass 2: shift-add of the k*k planes
-    const int vec = dm.p % 4 == 0 ? 4 : dm.p % 2 == 0 ? 2 : 1;
-    if (d->stride == 1 && (d->k == 3 || d->k == 5) && (size_t)dm.taps * d->m * d->h * d->w * sizeof(float) < (1ull << 31)) {
-        // the common case: the streaming form (one item per thread, images along the grid's second dimension)
-        const dim3 grid(stream_grid((size_t)d->m * dm.q * (dm.p / vec), 1), d->n < 65535 ? d->n : 65535);
-        auto launch = [&](auto kernel) {
-            hipLaunchKernelGGL(kernel, grid, dim3(256), 0, st, T, static_cast<float *>(O_dev), d->n, d->m, d->h, d->w, d->pad, dm.q, dm.p);
-        };
-        if (d->k == 3) { if (vec == 4) launch(shift_add_fast_kernel<4, 3>); else if (vec == 2) launch(shift_add_fast_kernel<2, 3>); else launch(shift_add_fast_kernel<1, 3>); }
-        else           { if (vec == 4) launch(shift_add_fast_kernel<4, 5>); else if (vec == 2) launch(shift_add_fast_kernel<2, 5>); else launch(shift_add_fast_kernel<1, 5>); }
-        return launch_status();
-    }
-    const int gvec = vec == 4 ? 4 : 1;
-    const size_t total = (size_t)d->n * d->m * dm.q * (dm.p / gvec);
-    auto launch = [&](auto kernel) {
-        hipLaunchKernelGGL(kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, T, static_cast<float *>(O_dev), d->n, d->m,
-                           d->h, d->w, d->k, d->pad, d->stride, dm.q, dm.p);
-    };
-    if (gvec == 4 && d->k == 3) launch(shift_add_f32_kernel<4, 3>);
-    else if (gvec == 4) launch(shift_add_f32_kernel<4, 0>);
-    else if (d->k == 3) launch(shift_add_f32_kernel<1, 3>);
-    else launch(shift_add_f32_kernel<1, 0>);
-    return launch_status();
+    return two_pass(d, dm, I_dev, Kp_dev, O_dev, static_cast<float *>(ws), static_cast<hipStream_t>(stream));
 }
 
 int conv_mcmk_im2col(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_dev, void *O_dev,
