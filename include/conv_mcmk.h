@@ -176,6 +176,24 @@ int conv_mcmk_direct(const conv_mcmk_desc *desc, const void *I_dev, const void *
                      void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * conv_mcmk_kn2row_2pass for callers that cannot allocate device memory and have no workspace to hand in: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The k*k*M x H*W product of
+ * pass 1 goes to a buffer inside the library's own device image instead of a caller-provided workspace; the
+ * call allocates and frees nothing (no hipMalloc, no hipFree, no allocating library routine) and otherwise
+ * behaves like conv_mcmk_kn2row_2pass: same kernels, same results, same validation and error codes.
+ *   - The buffer holds CONV_MCMK_STATIC_SCRATCH_BYTES (32 MiB); a layer whose conv_mcmk_workspace_bytes(desc,
+ *     CONV_MCMK_KN2ROW_2PASS) exceeds that gets CONV_MCMK_ERR_WORKSPACE and nothing is launched.
+ *   - Every GPU the library is used on holds its own copy of the buffer from the first use until the process
+ *     ends; its address on the current device is looked up once (CONV_MCMK_ERR_DEVICE if that fails).
+ *   - All calls on one GPU share the buffer, and it keeps the previous call's contents; a call relies on
+ *     none of them (pass 1 writes every element pass 2 reads).  Calls that overlap on one GPU -- two streams,
+ *     two threads -- race on it: issue them on one stream, or one after the other.
+ */
+#define CONV_MCMK_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+int conv_mcmk_kn2row_2pass_static(const conv_mcmk_desc *desc, const void *I_dev, const void *Kp_dev, void *O_dev,
+                                  void *stream);
+
+/*
  * kn2col (section III-A, last paragraph): the same sum of k*k 1x1 products with the layouts swapped so
  * that the channel is the innermost dimension -- the GEMM becomes [H*W x C] . [C x k*k*M].
  *   I_dev   input  I[N][H][W][C]  (float with C a multiple of 4, or bfloat16 with C a multiple of 8:

@@ -20,13 +20,14 @@ VARIANTS = {"kn2row": KN2ROW, "kn2row_2pass": KN2ROW_2PASS, "im2col": IM2COL, "d
             "im2row": IM2ROW}
 
 OK, ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_DEVICE, ERR_ALIGN = range(7)
+STATIC_SCRATCH_BYTES = 32 << 20        # CONV_MCMK_STATIC_SCRATCH_BYTES
 
 EXPORTS = (
     "conv_mcmk_strerror", "conv_mcmk_check", "conv_mcmk_describe_plan", "conv_mcmk_workspace_bytes", "conv_mcmk_packed_kernel_bytes",
     "conv_mcmk_prepack", "conv_mcmk_kn2row", "conv_mcmk_kn2row_2pass", "conv_mcmk_im2col",
     "conv_mcmk_direct", "conv_mcmk_kn2col", "conv_mcmk_im2row", "conv_mcmk_cvt_f32_bf16",
     "conv_mcmk_kn2row_bias_relu", "conv_mcmk_kn2col_bias_relu", "conv_mcmk_1x1", "conv_mcmk_select", "conv_mcmk_run",
-    "conv_mcmk_output_dims", "conv_mcmk_force_tile", "conv_mcmk_force_gemm_tile", "conv_mcmk_probe_mfma", "conv_mcmk_probe_copy",
+    "conv_mcmk_kn2row_2pass_static", "conv_mcmk_output_dims", "conv_mcmk_force_tile", "conv_mcmk_force_gemm_tile", "conv_mcmk_probe_mfma", "conv_mcmk_probe_copy",
 )
 
 
@@ -87,6 +88,8 @@ def lib():
         L.conv_mcmk_1x1.restype = i
         L.conv_mcmk_cvt_f32_bf16.argtypes = [vp, vp, sz, vp]
         L.conv_mcmk_cvt_f32_bf16.restype = i
+        L.conv_mcmk_kn2row_2pass_static.argtypes = [dp, vp, vp, vp, vp]
+        L.conv_mcmk_kn2row_2pass_static.restype = i
         L.conv_mcmk_output_dims.argtypes = [dp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
         L.conv_mcmk_output_dims.restype = i
         L.conv_mcmk_force_tile.argtypes = [i]
@@ -181,6 +184,10 @@ def conv_mcmk_kn2row(d, I, Kp, O, ws=None, stream=None):
 
 def conv_mcmk_kn2row_2pass(d, I, Kp, O, ws=None, stream=None):
     _run("conv_mcmk_kn2row_2pass", d, I, Kp, O, ws, stream)
+
+
+def conv_mcmk_kn2row_2pass_static(d, I, Kp, O, stream=None):
+    _raise(lib().conv_mcmk_kn2row_2pass_static(ctypes.byref(d), _ptr(I), _ptr(Kp), _ptr(O), _stream(stream)))
 
 
 def conv_mcmk_im2col(d, I, Kp, O, ws=None, stream=None):

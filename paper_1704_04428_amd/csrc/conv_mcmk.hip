@@ -617,6 +617,34 @@ int two_pass(const conv_mcmk_desc *d, const Dims &dm, const void *I_dev, const v
     return launch_status();
 }
 
+// ------------------------------------------------------------------------------------------
+// Product buffer of conv_mcmk_kn2row_2pass_static: device memory that belongs to the library's code object, so that
+// the call needs no allocation by anyone.  Every GPU the library runs on holds its own copy (at its own address) until
+// the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the address it yields
+// for the current device is what kernels are given.
+constexpr size_t kStaticScratchBytes = CONV_MCMK_STATIC_SCRATCH_BYTES;
+}  // namespace (closed so that the array is declared at file scope)
+
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+
+int static_scratch_address(void **out)
+{
+    static std::mutex mu;
+    static void *address[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return CONV_MCMK_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!address[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return CONV_MCMK_ERR_DEVICE;
+        address[dev] = p;
+    }
+    *out = address[dev];
+    return CONV_MCMK_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -841,6 +869,20 @@ int conv_mcmk_kn2row_2pass(const conv_mcmk_desc *d, const void *I_dev, const voi
     if ((rc = common_ptr_checks(I_dev, Kp_dev, O_dev))) return rc;
     if ((rc = workspace_check(d, CONV_MCMK_KN2ROW_2PASS, ws, ws_bytes))) return rc;
     return two_pass(d, dm, I_dev, Kp_dev, O_dev, static_cast<float *>(ws), static_cast<hipStream_t>(stream));
+}
+
+int conv_mcmk_kn2row_2pass_static(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_dev, void *O_dev, void *stream)
+{
+    Dims dm;
+    int rc = validate(d, CONV_MCMK_KN2ROW_2PASS, &dm);
+    if (rc) return rc;
+    if ((rc = common_ptr_checks(I_dev, Kp_dev, O_dev))) return rc;
+    if (conv_mcmk_workspace_bytes(d, CONV_MCMK_KN2ROW_2PASS) > kStaticScratchBytes) return CONV_MCMK_ERR_WORKSPACE;
+    void *T = nullptr;
+    if ((rc = static_scratch_address(&T))) return rc;
+    // nothing in the array has to start from zero: the matrix product writes every element of its k*k*M x H*W result
+    // (or clears it with a fill kernel first, where it splits the contraction) before the post pass reads it
+    return two_pass(d, dm, I_dev, Kp_dev, O_dev, static_cast<float *>(T), static_cast<hipStream_t>(stream));
 }
 
 int conv_mcmk_im2col(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_dev, void *O_dev,
