@@ -222,6 +222,37 @@ def library_conv_ms(L, bf16=False):
     return time_calls(run, n_steps, n_warm)[1]
 
 
+SELECTOR_CASES = [          # (n, c, h, w, m, k, pad, stride): layers inside and outside the fused kernels' range
+    (1, 3, 227, 227, 96, 11, 0, 4), (1, 64, 30, 30, 64, 9, 4, 1), (1, 32, 28, 28, 96, 5, 2, 1), (2, 128, 28, 28, 128, 3, 1, 1),
+    (1, 16, 32, 32, 16, 3, 1, 1), (1, 8, 64, 64, 8, 8, 4, 3), (2, 3, 224, 224, 64, 7, 3, 2), (2, 3, 112, 112, 32, 3, 1, 1),
+]
+
+
+def selector_report():
+    """How the per-layer choice among the algorithms (conv_mcmk_select) compares with timing them all: a report, not a
+    test -- parity tests never assert on time."""
+    import torch
+    from paper_1704_04428_amd import binding as B
+    names = {v: k for k, v in B.VARIANTS.items()}
+    out = []
+    for case in SELECTOR_CASES:
+        n, c, h, w, m, k, pad, stride = case
+        d = B.desc(n, c, h, w, m, k, pad, stride)
+        I = torch.rand(n, c, h, w, device="cuda")
+        K = torch.randn(m, c, k, k, device="cuda") * 0.05
+        chosen, est = B.conv_mcmk_select(d)
+        times = {}
+        for variant in (B.KN2ROW, B.KN2ROW_2PASS, B.IM2COL, B.DIRECT):
+            if B.conv_mcmk_check(d, variant) != B.OK:
+                continue
+            plan = B.Plan(d, variant, K)
+            n_steps, n_warm = auto_counts(lambda: plan.run(I), 10.0, 20.0)
+            times[names[variant]] = round(time_calls(lambda: plan.run(I), n_steps, n_warm)[1], 5)
+        out.append({"layer": list(case), "chosen": names[chosen], "estimate_us": round(est, 1), "ms": times,
+                    "chosen_over_fastest": round(times[names[chosen]] / min(times.values()), 3)})
+    return out
+
+
 def cpu_baseline(L, I, K, budget_s=12.0, max_passes=40):
     """The oracle as it stands, timed on the host cores: whole passes over the workload until about
     `budget_s` seconds of CPU work have been spent."""
@@ -368,6 +399,8 @@ def main():
             if L.name == DEFAULT_WORKLOAD else None
         log("cfg5a_bias_relu", json.dumps(extras["cfg5a_bias_relu"]))
         result["generalisations"] = extras
+        result["selector"] = selector_report()
+        log("selector", json.dumps(result["selector"]))
     print(json.dumps(result), flush=True)
 
 

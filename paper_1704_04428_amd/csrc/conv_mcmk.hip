@@ -10,6 +10,7 @@
 #include <mutex>
 
 #include "aux_kernels.h"
+#include "selector_constants.h"
 #include "tile_dispatch.h"
 
 namespace {
@@ -227,6 +228,10 @@ long long workgroups(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c
 
 double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, int ks, bool channels_last = true)
 {
+    const bool bf16 = d->dtype == CONV_MCMK_BF16;
+    // one set of constants per operand type and layout (selector_constants.h; fitted to timings of every menu entry
+    // on random layers and on the layers of the networks the paper draws from: paper_1704_04428_amd/tuning)
+    const CostParams &P = kCost[(bf16 ? 2 : 0) + (channels_last ? 1 : 0)];
     const long long wgs = workgroups(d, dm, c);
     const int npb = ceil_div(c.th * c.tw, 16);
     const int group_waves = c.wm * c.wp;
@@ -243,10 +248,6 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
         simd_load = simd_blocks[i] > simd_load ? simd_blocks[i] : simd_load;
         simd_sum += simd_blocks[i];
     }
-    const bool bf16 = d->dtype == CONV_MCMK_BF16;
-    // the bf16 constants come in two sets: the [C][H][W] input is gathered in two-byte pairs and the [M][Q][P]
-    // output written in tile rows; channels last, both are 16-byte accesses (each set fitted to its own sweep)
-    const bool cl16 = bf16 && channels_last;
     // chunks each wave works through (the channel groups of a workgroup share them out)
     const int chunks = ceil_div(ceil_div(ceil_div(d->c, bf16 ? 32 : 16), c.csplit), c.kg);
     // fp32: 4 MFMAs of 32 cycles per tap and 16-channel chunk (1 in the lean form); bf16: 1 MFMA of 16 cycles per tap
@@ -258,6 +259,8 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
     // double-buffered halo tiles of 16 channels in 160 KB of LDS)
     int can_hold = (bf16 ? 8 : 16) / waves;        // sixteen-wave workgroups (channel groups, tile pairs): one
     if (can_hold < 1) can_hold = 1;
+    // (the four-wave bf16 shape whose waves own all thirteen blocks of a 14 x 14 tile twice over needs 300 registers)
+    if (bf16 && c.rb == 2 && c.wp == 1 && c.th * c.tw > 128) can_hold = 1;
     const int halo = ((c.th - 1) * d->stride + ks) * ((c.tw - 1) * d->stride + ks);
     if (!bf16) {
         const int fit = 163840 / (2 * c.kg * 16 * (((halo + 15) / 32) * 32 + 16) * 4);
@@ -266,72 +269,73 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
     }
     const long long held = per_cu < can_hold ? per_cu : can_hold;
     const double waves_per_simd = (double)held * waves / 4.0;
-    double pipe_use = waves_per_simd >= 2.0 ? 0.9 : 0.7;
-    // bf16: the product is four times shorter than the fp32 one while a B fragment is four times
-    // larger, so LDS reads, operand loads and the per-chunk hand-over weigh more; measured slopes over
-    // the channel count give about half of the pipe (B fragments of 1 KB per product saturate the LDS port when
-    // a wave has one row block; the reuse factors below carry the difference)
+    // a SIMD with a single resident wave cannot hide LDS and global latency
+    double pipe_use = (waves_per_simd >= 2.0 ? P.pipe_multi : P.pipe_single) * P.type_scale;
+    // bf16: the product is four times shorter than the fp32 one while a B fragment is four times larger, so LDS
+    // reads, operand loads and the per-chunk hand-over weigh more.  An A fragment (1 KB from L1/L2 per wave) is reused
+    // for the wave's position blocks, the staged tile for the workgroup's rows: few blocks per wave or few rows per
+    // workgroup leave the load path, not the matrix pipe, as the limit
     if (bf16) {
-        pipe_use *= 0.60;
-        // an A fragment (1 KB from L1/L2 per wave) is reused for the wave's position blocks, the staged
-        // tile for the workgroup's rows: few blocks per wave or few rows per workgroup leave the
-        // load path, not the matrix pipe, as the limit (fitted to the sweep of all shapes)
-        const double reuse_a = (cl16 ? 0.8 : 0.4) + 0.07 * ceil_div(npb, c.wp);
+        const double reuse_a = P.reuse_a0 + P.reuse_a1 * ceil_div(npb, c.wp);
         const double rows = 16.0 * c.wm * c.rb;
-        const double reuse_b = rows / (rows + 16.0) / 0.8;
-        pipe_use *= (reuse_a < 1.1 ? reuse_a : 1.1) * (reuse_b < 1.0 ? reuse_b : 1.0);
+        const double reuse_b = rows / (rows + 16.0) / P.reuse_b;
+        pipe_use *= (reuse_a < P.reuse_a_cap ? reuse_a : P.reuse_a_cap) * (reuse_b < 1.0 ? reuse_b : 1.0);
     }
+    // a chunk of a large kernel is many taps long, so the hand-over between chunks weighs less
+    if (ks > 3) pipe_use *= 1.0 + P.taps_gain * (1.0 - 9.0 / (ks * ks));
+    if (pipe_use > 1.0) pipe_use = 1.0;
     // a ragged deal of blocks loads one SIMD more than the others; workgroups that share a CU even that out in part
     const double blocks = (!bf16 && held >= 2) ? 0.5 * simd_load + 0.125 * simd_sum : (double)simd_load;
+    // (a block-step is one fp32 16x16x4 MFMA, 32 cycles of a SIMD's matrix pipe: 13.9 ns at 2.3 GHz)
     double us = (double)per_cu * blocks * steps * 0.0139 / pipe_use;
-    // bf16: a wave has one chunk of staging loads in flight, so a workgroup cannot finish a chunk faster than
-    // a round trip to memory allows, however little matrix work it holds
-    if (bf16 && us < ceil_div(per_cu, can_hold) * chunks * (cl16 ? 0.6 : 0.1)) us = ceil_div(per_cu, can_hold) * chunks * (cl16 ? 0.6 : 0.1);
-    // fp32 chunks are half as long; the floor shows on 1 x 1 layers with hundreds of channels on small images
-    // (workgroups that share a CU walk their chains side by side)
-    if (!bf16 && us < ceil_div(per_cu, can_hold) * chunks * 0.19) us = ceil_div(per_cu, can_hold) * chunks * 0.19;
+    // a wave has one chunk of staging loads in flight, so a workgroup cannot finish a chunk faster than a round trip to
+    // memory allows, however little matrix work it holds (workgroups that share a CU walk their chains side by side;
+    // quarter tiles stage a fifth of a 14 x 14 tile's positions per chunk, and their round trips are shorter)
+    const double floor_us = ceil_div(per_cu, can_hold) * chunks * P.floor_chunk * (c.th == 7 ? P.floor_small : 1.0);
+    if (us < floor_us) us = floor_us;
     // staging-heavy cases: a 1 x 1 kernel uses every staged value once instead of k*k times, a
     // strided tile stages four input values per output position (both measured)
     // (less so for the 16 x 16 tile, whose 256 positions per channel give every thread one position to stage)
-    if (ks == 1 && c.shape != kGemmShape && c.shape != kWideGemmShape) us *= c.th * c.tw == 256 ? (cl16 ? 1.2 : bf16 ? 1.4 : 1.1) : (cl16 ? 1.2 : bf16 ? 1.6 : 1.5);
-    if (d->stride == 2) us *= 1.25;
+    if (ks == 1 && c.shape != kGemmShape && c.shape != kWideGemmShape) us *= c.th * c.tw == 256 ? P.k1_tile256 : P.k1_other;
+    if (d->stride == 2) us *= P.stride2;
     // bf16: staging the halo tile is serial with the matrix work of a workgroup that has a CU to itself
-    if (bf16) us += (double)per_cu * chunks * halo * c.kg / waves * (0.05 / 64.0);
-    us += cl16 ? 6.0 : 5.0;          // launch, first loads, output write
+    if (bf16) us += (double)per_cu * chunks * halo * c.kg / waves * (P.stage / 64.0);
+    us += P.fixed;          // launch, first loads, output write
     // fp32: every workgroup stages its halo tile of every channel, so workgroups of few rows re-read the input once
-    // per group of rows (from L2 when the rows of one tile run side by side, 0.04 us per MB; tile rows that are no
-    // whole 64-byte lines cost a fifth more): what decides between many small and few large workgroups, and what
-    // a 1 x 1 layer on a large image is bound by (2 x 768 x 224 x 224, M 128: 16 rows per workgroup 287 us, 64 rows 212 us)
+    // per group of rows (from L2 when the rows of one tile run side by side; tile rows that are no whole 64-byte lines
+    // cost more): what decides between many small and few large workgroups, and what a 1 x 1 layer on a large image
+    // is bound by (2 x 768 x 224 x 224, M 128: 16 rows per workgroup 287 us, 64 rows 212 us)
     if (!bf16)
-        us += 0.04 * (double)wgs * halo * ((double)d->c / c.csplit) * 4.0e-6 * ((c.tw % 16 == 0 || c.tw >= 28) ? 1.0 : 1.2);
+        us += P.stage * (double)wgs * halo * ((double)d->c / c.csplit) * 4.0e-6 * ((c.tw % 16 == 0 || c.tw >= 28) ? 1.0 : P.stage_partial);
     // every further workgroup a CU works through brings its own prologue and closing write, hidden in part behind
-    // the workgroups resident beside it (fitted, like the other fp32 constants, to 2,246 timed candidates on 138 layers)
-    if (!bf16 && per_cu > 1) us += (double)(per_cu - 1) * 2.8 / can_hold;
-    // bf16: half a microsecond each, five for the sixteen-wave workgroups with channel groups, which share a CU with
-    // nobody (fitted, like the other bf16 constants, to 8,400 timed candidates on 450 layers, either layout)
-    if (bf16 && per_cu > 1)
-        us += (double)(per_cu - 1) * (cl16 ? (waves == 16 ? 4.0 : can_hold == 1 ? 2.0 : 1.0) : waves == 16 ? 3.6 : can_hold == 1 ? 0.5 : 0.6);
+    // the workgroups resident beside it
+    if (!bf16 && per_cu > 1) us += (double)(per_cu - 1) * P.extra_wg / can_hold;
+    if (bf16 && per_cu > 1) us += (double)(per_cu - 1) * (waves == 16 ? P.extra_wg_16 : can_hold == 1 ? P.extra_wg_alone : P.extra_wg);
     // [M][Q][P] output of a bf16 call: tile rows of 14 or 7 floats are partial cache lines, and with so little
-    // matrix time per output the write shows (0.2 us per MB; tiles 16 wide or whole image rows: nothing)
+    // matrix time per output the write shows (tiles 16 wide or whole image rows: nothing)
     // (rows: M, or k*k*M when the rows of a staged variant's matrix product are (tap, kernel) pairs)
     const double out_rows = (double)d->m * (dm.mb / ceil_div(d->m, 16));
     const double out_mb = (double)d->n * out_rows * dm.q * dm.p * 4.0e-6;
     const bool partial_lines = !channels_last && c.tw % 16 != 0 && c.tw < 28;
-    if (bf16 && partial_lines) us += 0.2 * out_mb;
+    if (bf16 && partial_lines) us += P.partial_out * out_mb;
+    // what of the closing write the matrix work does not hide (layers of few channels and many kernels are bound by it)
+    us += (P.out_write + (c.rb == 2 ? P.out_write_rb2 : 0.0)) * out_mb;
     // with one channel quad there is so little matrix work that the output write shows: half of it at 5 TB/s
     // when the tile rows are whole 64-byte lines, at 3.3 TB/s when they are not (fitted to the first-layer shapes)
     if (lean) us += 0.5 * 4.0 * (double)d->n * d->m * dm.q * dm.p / (c.tw % 16 == 0 ? 5.0e6 : 3.3e6);
     // the zero fill and two atomic adds per output: per MB of output ([M][Q][P]: tile rows of whole or partial lines)
     // (a split into more parts -- the flat shapes of a staged variant's matrix product -- adds its parts' worth of atomics)
-    if (c.csplit > 1) us += 3.0 + (channels_last ? (bf16 ? 3.5 : 3.125) : partial_lines ? (bf16 ? 3.5 : 2.2) : 1.5) * out_mb * (c.csplit / 2.0);
-    if (c.kg > 1) us += c.kg == 4 ? 1.5 : waves == 16 ? 0.5 : 0.8;                        // the closing exchange through LDS (quarter tiles: a seventh of the data)
+    if (c.csplit > 1) us += P.split_fixed + (partial_lines ? P.split_mb_partial : P.split_mb) * out_mb * (c.csplit / 2.0);
+    // the closing exchange of channel groups through LDS (quarter tiles: a seventh of the data)
+    if (c.kg > 1) us += c.kg == 4 ? P.kg4 : waves == 16 ? P.kg2_16 : P.kg2;
     return us;
 }
 
 // The candidate the cost estimate prefers for the fused kernel (or the one CONV_MCMK_TILE forces:
 // tuning aid, menu index = shape + 7 * (csplit - 1) for the seven common shapes, then
 // 14 + further shape + 8 * (csplit - 1) for the eight further shapes: bf16 with two row blocks per wave, quarter tiles,
-// tile pairs, quarter tiles with two channel groups).
+// tile pairs, quarter tiles with two channel groups; then 30 + later shape + count * (csplit - 1) for the shapes added
+// since: the bf16 four-wave workgroups).
 Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, bool epilogue, int force, bool gemm = false);
 
 // The tile a staged variant's matrix product runs on unless one is forced: the flat shape (64 or 128 rows x 224
@@ -407,27 +411,32 @@ Candidate choose_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_la
 // gemm: the layer is the matrix product of a staged variant seen as a 1 x 1 convolution (d->k == 1, no padding, unit
 // stride; the channels are the contraction index, the plane is the patch matrix's or the two-pass product's).  The
 // whole menu applies, and after it come the two flat shapes (1 x 224 columns of the plane taken as one row, 32-channel
-// chunks), each with the channels unsplit and split two, four and eight ways: indices 30 .. 37.
+// chunks), each with the channels unsplit and split two, four and eight ways: indices 100 .. 107.
 Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, bool epilogue, int force, bool gemm)
 {
     Candidate best{};
     double best_cost = -1.0;
-    const int menu_len = kConvShapes + kWideConvShapes;
     // (the flat shapes also with the contraction split four and eight ways: a staged variant's product over C k k
     // channels on a small plane has few tiles, and unlike the fused kernel's two-way split more than two partial sums
     // meet at the atomics, so the last bits of such a result depend on the order they arrive in)
-    for (int pass = 0, index = 0; pass < (gemm ? 3 : 2); ++pass)       // common shapes, then the wide ones, then the flat ones
-    for (int cs = 1; cs <= (pass == 2 ? 8 : 2); cs *= 2)
-        for (int pos = pass == 0 ? 0 : pass == 1 ? kConvShapes : menu_len; pos < (pass == 0 ? kConvShapes : pass == 1 ? menu_len : menu_len + 2);
-             ++pos, ++index) {
-            const int sh = pos < kConvShapes ? pos : pos < menu_len ? kWideConvShape[pos - kConvShapes] : pos == menu_len ? kGemmShape : kWideGemmShape;
+    // Menu passes and the index their first entry has: the seven common shapes (0), the eight further ones (14), the
+    // shapes added after those (30), and, for a matrix product only, the two flat shapes (100).
+    struct Pass { const int *shapes; int count, first_index, max_split; };
+    static const int kCommon[kConvShapes] = {0, 1, 2, 3, 4, 5, 6};
+    static const int kFlat[2] = {kGemmShape, kWideGemmShape};
+    const Pass passes[4] = {{kCommon, kConvShapes, 0, 2}, {kWideConvShape, kWideConvShapes, 14, 2},
+                            {kLaterConvShape, kLaterConvShapes, 30, 2}, {kFlat, 2, 100, 8}};
+    for (int pass = 0; pass < (gemm ? 4 : 3); ++pass)
+    for (int cs = 1, index = passes[pass].first_index; cs <= passes[pass].max_split; cs *= 2)
+        for (int pos = 0; pos < passes[pass].count; ++pos, ++index) {
+            const int sh = passes[pass].shapes[pos];
             const Candidate c = candidate(sh, cs);
             if (sh == kWideGemmShape && d->dtype != CONV_MCMK_BF16) continue;
             // two row blocks per wave: bf16 operands, unit stride
             if (c.rb > 1 && (d->dtype != CONV_MCMK_BF16 || d->stride > 1 || d->k > 3)) continue;
             if (c.th == 7 && (d->stride > 1 || d->k > 5)) continue;
             // the 14 x 28 pairs under sixteen waves: fp32 operands, unit stride (excluded below), kernel sides up to 3
-            if (sh >= kPairTileShape && (d->dtype == CONV_MCMK_BF16 || d->k > 3)) continue;
+            if (sh >= kPairTileShape && sh <= kPairTileShape + 2 && (d->dtype == CONV_MCMK_BF16 || d->k > 3)) continue;
             // the two-group pair is not built for 2 x 2 kernels, nor for channels-last operands (measured slower there
             // than single tiles: the 16-byte gathers of eight waves fill a 30-column tile less evenly)
             if (sh == kPairTileShape + 1 && (d->k == 2 || channels_last)) continue;    // quarter tiles: unit stride, kernel sides up to 5
@@ -439,7 +448,7 @@ Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_la
             // candidate on any 1 x 1 layer timed, either precision)
             // (a staged variant's product contracts over C k k: thousands of channels on the deep layers, and
             // there the groups are what fills the chip)
-            if (c.kg > 1 && d->k == 1 && !(gemm && d->c >= 1024) && force != index) continue;
+            if (c.kg > 1 && d->k == 1 && (d->c < 256 || d->dtype == CONV_MCMK_BF16) && force != index) continue;
             if (d->stride > 1 && sh >= kStridedShapes) continue;       // strided input tiles: 14 x 14 outputs only
             if (epilogue && cs > 1) continue;                          // partial sums cannot take the epilogue
             // strided bf16 tiles gathered from [C][H][W] with a kernel side of 5 or more exist for the

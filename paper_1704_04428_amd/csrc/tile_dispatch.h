@@ -39,6 +39,11 @@ constexpr TileShapeDesc kTileShapes[] = {
     // quarter tiles with two channel groups of four waves: the split of the channel sum for single small images with
     // hundreds of channels, without the zero fill and the atomics of the two-workgroup split
     {7, 7, 1, 4, 2, 1},
+    // bf16, two row blocks per wave, FOUR waves (128 rows x 112 positions = 7 blocks, all owned by every wave): a
+    // workgroup is one wave per SIMD and needs under 256 registers, so two of them share a compute unit, each behind
+    // its own barrier -- when one waits for its staged chunk the other has the matrix pipe.  8 x 14 for images whose
+    // sides are multiples of 8 and 14 (56 x 56), 4 x 28 for 28-wide ones.
+    {8, 14, 4, 1, 1, 2}, {4, 28, 4, 1, 1, 2},
 };
 constexpr int kConvShapes = 7;
 constexpr int kGemmShape = 7;
@@ -48,6 +53,8 @@ constexpr int kMaxKernelSide = 7;      // kernel sides 1..7 are instantiated
 constexpr int kWideConvShapes = 8;
 constexpr int kWideConvShape[kWideConvShapes] = {8, 9, 10, 12, 13, 14, 15, 16};
 constexpr int kWideGemmShape = 11;     // ... and the plain-GEMM shape
+constexpr int kLaterConvShapes = 2;    // shapes added after those (their menu indices start at 30)
+constexpr int kLaterConvShape[kLaterConvShapes] = {17, 18};
 constexpr int kPairTileShape = 14;     // the 14 x 28 shapes: this one and the next (two channel groups)
 
 struct TileRequest {

@@ -140,6 +140,8 @@ int MCMK_FN(const TileRequest &rq)
         case 9: return launch_shape<14, 14, 2, 4, 16, true, 1, 1, 2>(rq);
         case 10: return launch_shape<14, 14, 4, 1, 16, true, 1, 1, 2>(rq);
         case 12: return launch_shape<4, 56, 4, 2, 16, true, 1, 1, 2>(rq);
+        case 17: return launch_shape<8, 14, 4, 1, 16, true, 1, 1, 2>(rq);
+        case 18: return launch_shape<4, 28, 4, 1, 16, true, 1, 1, 2>(rq);
 #if MCMK_KS == 1
         case 11: return launch_shape<1, 224, 4, 2, 32, true, 1, 1, 2>(rq);
 #endif
@@ -175,6 +177,8 @@ int MCMK_FN(const TileRequest &rq)
     case 9: return launch_shape<14, 14, 2, 4, 16, false, 1, 1, 2>(rq);
     case 10: return launch_shape<14, 14, 4, 1, 16, false, 1, 1, 2>(rq);     // a wave owns every position block
     case 12: return launch_shape<4, 56, 4, 2, 16, false, 1, 1, 2>(rq);      // whole image rows
+    case 17: return launch_shape<8, 14, 4, 1, 16, false, 1, 1, 2>(rq);      // four waves: two workgroups per compute unit
+    case 18: return launch_shape<4, 28, 4, 1, 16, false, 1, 1, 2>(rq);
 #if MCMK_KS == 1
     case 11: return launch_shape<1, 224, 4, 2, 32, false, 1, 1, 2>(rq);
 #endif

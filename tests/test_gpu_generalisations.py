@@ -197,7 +197,7 @@ def test_one_by_one_entry_point_refuses_larger_kernels():
 ])
 def test_selected_variant_is_correct(case):
     """conv_mcmk_select + Plan.auto: the chosen variant runs and gives the oracle's result.  (How close the choice
-    is to the fastest variant is a timing question: bench.py --selector reports it.)"""
+    is to the fastest variant is a timing question: the `selector` entry of bench.py's output reports it.)"""
     import torch
     announce("select", case)
     n, c, h, w, m, k, pad, stride = case

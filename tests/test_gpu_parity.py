@@ -273,7 +273,7 @@ def test_every_tile_shape_of_the_menu(k, pad, dtype, monkeypatch):
     K = wl.normal(601 + k, m * c * k * k, 0.5).reshape(m, c, k, k)
     ref, absref = oracle.mcmk(I, K, pad)
     tol = TOL_BF16 if dtype == B.BF16 else TOL_F32
-    for index in range(30):
+    for index in range(34):
         for variant in (B.KN2ROW, B.KN2COL):
             announce("menu", "k", k, "dtype", dtype, "tile", index, "variant", variant)
             B.conv_mcmk_force_tile(index)
@@ -287,7 +287,7 @@ def test_every_tile_shape_of_the_menu(k, pad, dtype, monkeypatch):
 def test_every_tile_shape_of_the_staged_variants_matrix_product(case, dtype):
     """The matrix product of im2col, im2row and the two-pass variant (sections II-B, III-A) runs on the same tile
     kernels as a 1 x 1 convolution over the patch matrix / the input, with the tile shape picked from the fused
-    kernel's menu plus the flat shapes (38 entries); force every entry, so that each instantiation is checked with
+    kernel's menu (34 entries) plus the flat shapes (8 entries, from index 100); force every entry, so that each instantiation is checked with
     rows that are (tap, kernel) pairs, with the channel split and with channel groups."""
     from gpu_util import TOL_BF16
     n, c, h, w, m, k, pad, stride = case
@@ -295,7 +295,7 @@ def test_every_tile_shape_of_the_staged_variants_matrix_product(case, dtype):
     K = wl.normal(701 + k, m * c * k * k, 0.5).reshape(m, c, k, k)
     ref, absref = oracle.mcmk(I, K, pad, stride)
     tol = TOL_BF16 if dtype == B.BF16 else TOL_F32
-    for index in list(range(38)) + [-1]:
+    for index in list(range(34)) + list(range(100, 108)) + [-1]:
         for variant in (B.IM2COL, B.KN2ROW_2PASS, B.IM2ROW):
             announce("gemm menu", case, "dtype", dtype, "tile", index, "variant", variant)
             B.conv_mcmk_force_gemm_tile(index)
