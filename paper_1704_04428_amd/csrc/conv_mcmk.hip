@@ -345,28 +345,39 @@ Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_la
 // are what the kernel sustained on the benchmark layers; timings of every menu entry there put this rule within a
 // tenth of the best entry (the 2-D tiles of the fused kernel stage too little per barrier for a product whose every
 // value is used once, and the estimate that serves the fused kernel misjudges them by up to 40 % here).
+double flat_gemm_us(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, int shape, int cs)
+{
+    const bool bf16 = d->dtype == CONV_MCMK_BF16;
+    const long long cols = (long long)dm.q * dm.p;
+    const TileShapeDesc &t = kTileShapes[shape];
+    const long long w = (long long)d->n * ceil_div(cols, t.tw) * ceil_div(dm.mb, t.wm * t.rb) * cs;
+    const double flop = 2.0 * d->n * (dm.mb * 16.0) * cols * d->c;
+    const double out_mb = (double)d->n * (dm.mb * 16.0) * cols * 4.0e-6;
+    // fraction of the matrix peak the kernel sustains: two workgroups per unit, one, or a partly idle chip
+    // (bf16 with two row blocks per wave: a fifth more, measured on the two-pass products)
+    const double full = bf16 ? (t.rb == 2 ? 0.17 : 0.14) : 0.62, single = bf16 ? 0.09 : 0.50;
+    const double eff = w >= 448 ? full : w >= kNumCU ? single : single * (double)w / kNumCU;
+    double us = flop / ((bf16 ? 2500.0e6 : 157.3e6) * eff);
+    // a product with a short contraction is bound by reading its right operand and writing its result (4 TB/s)
+    const double moved_mb = (double)d->n * d->c * cols * (bf16 ? 2.0e-6 : 4.0e-6) + out_mb;
+    if (us < moved_mb / 4.0) us = moved_mb / 4.0;
+    if (cs > 1) us += 3.0 + (channels_last ? 3.1 : 1.6) * out_mb * (cs / 2.0);
+    return us;
+}
+
 Candidate flat_gemm_candidate(const conv_mcmk_desc *d, const Dims &dm, bool channels_last)
 {
     const bool bf16 = d->dtype == CONV_MCMK_BF16;
     const long long cols = (long long)dm.q * dm.p;
     const int chunks = ceil_div(d->c, 32);
-    auto wgs = [&](int shape) {
-        const TileShapeDesc &t = kTileShapes[shape];
-        return (long long)d->n * ceil_div(cols, t.tw) * ceil_div(dm.mb, t.wm * t.rb);
-    };
     // bf16: two row blocks per wave (half the LDS reads per product) where that alone fills the chip twice over
-    if (bf16 && wgs(kWideGemmShape) >= 2 * kNumCU) return candidate(kWideGemmShape, 1);
-    const double flop = 2.0 * d->n * (dm.mb * 16.0) * cols * d->c;
-    const double out_mb = (double)d->n * (dm.mb * 16.0) * cols * 4.0e-6;
+    const TileShapeDesc &wide = kTileShapes[kWideGemmShape];
+    if (bf16 && (long long)d->n * ceil_div(cols, wide.tw) * ceil_div(dm.mb, wide.wm * wide.rb) >= 2 * kNumCU)
+        return candidate(kWideGemmShape, 1);
     int best = 1;
     double best_us = 0.0;
     for (int cs = 1; cs <= 8 && (cs == 1 || chunks / cs >= 2); cs *= 2) {
-        const long long w = wgs(kGemmShape) * cs;
-        // fraction of the matrix peak the kernel sustains: two workgroups per unit, one, or a partly idle chip
-        const double full = bf16 ? 0.14 : 0.62, single = bf16 ? 0.09 : 0.50;
-        const double eff = w >= 448 ? full : w >= kNumCU ? single : single * (double)w / kNumCU;
-        double us = flop / ((bf16 ? 2500.0e6 : 157.3e6) * eff);
-        if (cs > 1) us += 3.0 + (channels_last ? 3.1 : 1.6) * out_mb * (cs / 2.0);
+        const double us = flat_gemm_us(d, dm, channels_last, kGemmShape, cs);
         if (cs == 1 || us < best_us) { best = cs; best_us = us; }
     }
     return candidate(kGemmShape, best);
@@ -477,7 +488,7 @@ Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_la
 // ------------------------------------------------------------------------------------------
 // Estimated run time in microseconds of a whole variant (the per-layer choice among algorithms the
 // paper's conclusion calls for).  Pieces: the tile-kernel estimate above for the matrix work; the
-// memory-bound passes at the 3.5 TB/s they were measured to sustain plus a launch; the direct loop
+// memory-bound passes at the 6 TB/s they were measured to sustain plus a launch; the direct loop
 // nest at its measured 3 TFLOP/s.
 // The matrix product of a staged variant as the tile kernels see it: a 1 x 1 convolution of `kc` channels over a
 // ph x pw plane per image (im2col / im2row: the patch matrix, plane = the output's; two-pass: the input itself), rows =
@@ -500,19 +511,17 @@ double gemm_cost(const conv_mcmk_desc *d, long long kc, int ph, int pw, int row_
 {
     const GemmView v = gemm_view(d, kc, ph, pw, row_groups);
     const Candidate c = choose_fused(&v.d, v.dm, channels_last, false, true);
-    if (c.shape == kGemmShape || c.shape == kWideGemmShape) {
-        conv_mcmk_desc flat = v.d;
-        flat.h = 1;  flat.w = ph * pw;
-        const Dims fdm{1, ph * pw, v.dm.mb, 1};
-        // (deeper chunks, but a staged tile serves one tap, not k*k: about 1.2 x the fused kernel's time per MFMA)
-        return 1.2 * tile_cost(&flat, fdm, c, 1, channels_last);
-    }
+    // the flat shapes: the rates the kernel was measured to sustain, plus a launch; a forced 2-D tile: the fused
+    // kernel's estimate for a 1 x 1 layer
+    if (c.shape == kGemmShape || c.shape == kWideGemmShape) return flat_gemm_us(&v.d, v.dm, channels_last, c.shape, c.csplit) + 5.0;
     return tile_cost(&v.d, v.dm, c, 1, channels_last);
 }
 
 // a memory-bound pass before or after the matrix kernel: its bytes, its launch, and the drain / fill
 // between two dependent kernels
-double stream_cost(double bytes) { return bytes / 3.5e6 + 12.0; }
+// (the streaming forms for unit stride and kernel sides 3 and 5 sustain 6 TB/s; the general kernels, which also pay
+// 64-bit index arithmetic per item, 3.5 TB/s and a longer tail)
+double stream_cost(double bytes, bool streaming_form) { return streaming_form ? bytes / 6.0e6 + 4.0 : bytes / 3.5e6 + 12.0; }
 
 double variant_cost(const conv_mcmk_desc *d, const Dims &dm, int variant)
 {
@@ -526,11 +535,11 @@ double variant_cost(const conv_mcmk_desc *d, const Dims &dm, int variant)
     case CONV_MCMK_KN2ROW_2PASS: {
         const double planes = (double)d->n * d->m * d->h * d->w;
         return gemm_cost(d, d->c, d->h, d->w, dm.taps) +
-               stream_cost(4.0 * (dm.taps * planes + (double)d->n * d->m * dm.q * dm.p));
+               stream_cost(4.0 * (dm.taps * planes + (double)d->n * d->m * dm.q * dm.p), d->stride == 1 && (d->k == 3 || d->k == 5));
     }
     case CONV_MCMK_IM2COL:
     case CONV_MCMK_IM2ROW:
-        return stream_cost(elt * (in_elems + patch_elems)) +
+        return stream_cost(elt * (in_elems + patch_elems), variant == CONV_MCMK_IM2ROW || (d->stride == 1 && (d->k == 3 || d->k == 5))) +
                gemm_cost(d, (long long)d->c * dm.taps, dm.q, dm.p, 1, variant == CONV_MCMK_IM2ROW);
     default: {
         // one thread per output walks its C*k*k terms one after the other (0.12 us each when the chip
