@@ -37,7 +37,10 @@ CLOCK_RAMP_MS = 150.0
 MEASURED_TRAFFIC_BYTES = {
     # profiles/kn2row_tile_f32_cfg5a_hbm_traffic.txt
     ("cfg5a_vgg_deep56", "f32", "kn2row fused f32: tile 14x28, waves 4x4, row blocks 1, channel groups 1, channel split 1, "
-                                "256 workgroups"): 74_260_000,
+                                "256 workgroups"): 74_316_000,
+    # profiles/cfg4_hbm_traffic_all_variants.txt
+    ("cfg4_vgg_early", "f32", "kn2row fused f32: tile 14x14, waves 4x2, row blocks 1, channel groups 1, channel split 1, "
+                              "256 workgroups"): 27_964_000,
 }
 
 

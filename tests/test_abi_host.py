@@ -224,6 +224,36 @@ def test_plan_selection_for_benchmark_layers(lib, monkeypatch):
     assert "channel groups 1" in B.conv_mcmk_describe_plan(B.desc(1, 8, 10, 10, 8, 5, 2), B.KN2ROW)
 
 
+def test_image_size_limit_of_the_32_bit_offsets(lib):
+    """The tile kernels address one image through 32-bit byte offsets and mark "outside the image" with an offset of
+    2 GiB, to which a staging slot's channel (below 32) and the first chunk beyond the data (below C + 32) are still
+    added: (C + 64) H W must stay below 2^29 elements, for every variant (the staged ones run their matrix product on
+    the same kernels), and likewise (C k k + 64) Q P for the patch matrices."""
+    at_limit = dict(n=1, c=64, h=2048, w=2048, m=1, k=3, pad=1)            # (64 + 64) * 2^22 == 2^29
+    below = dict(at_limit, h=2047)
+    for variant in (B.KN2ROW, B.KN2COL, B.KN2ROW_2PASS, B.DIRECT):
+        assert B.conv_mcmk_check(B.desc(**at_limit), variant) == B.ERR_SHAPE, variant
+        assert B.conv_mcmk_check(B.desc(**below), variant) == B.OK, variant
+    patch_at_limit = dict(n=1, c=64, h=916, w=916, m=1, k=3, pad=1)        # (576 + 64) * 916^2 >= 2^29
+    patch_below = dict(patch_at_limit, h=915)
+    assert (576 + 64) * 916 * 916 >= 2 ** 29 > (576 + 64) * 915 * 916
+    for variant in (B.IM2COL, B.IM2ROW):
+        assert B.conv_mcmk_check(B.desc(**patch_at_limit), variant) == B.ERR_SHAPE, variant
+        assert B.conv_mcmk_check(B.desc(**patch_below), variant) == B.OK, variant
+    assert B.conv_mcmk_check(B.desc(**patch_at_limit), B.KN2ROW) == B.OK
+
+
+def test_output_dims_entry_point(lib):
+    """conv_mcmk_output_dims is where callers get Q and P from (the binding computes no sizes of its own)."""
+    assert B.conv_mcmk_output_dims(B.desc(1, 3, 224, 224, 8, 7, 3, 2)) == (112, 112)
+    assert B.conv_mcmk_output_dims(B.desc(2, 5, 9, 11, 7, 3, 0)) == (7, 9)
+    assert B.conv_mcmk_output_dims(B.desc(1, 1, 5, 5, 1, 2, 1, 3)) == (2, 2)
+    with pytest.raises(B.ConvMcmkError) as e:
+        B.conv_mcmk_output_dims(B.desc(1, 1, 2, 2, 1, 5, 0))
+    assert e.value.code == B.ERR_SHAPE
+    assert lib.conv_mcmk_output_dims(None, None, None) == B.ERR_NULL
+
+
 def test_kernel_register_budget():
     """The compiler's per-kernel report of the last build: no loop spills to scratch, and the 8-wave
     tile kernels stay within 128 vector registers (two workgroups per compute unit need that)."""
