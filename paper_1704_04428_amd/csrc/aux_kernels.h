@@ -193,6 +193,45 @@ __global__ __launch_bounds__(256) void im2row_build_kernel(const T *__restrict__
     }
 }
 
+// The same rows for the common case (unit stride, kernel side KS known at compile time), arranged like
+// im2col_build_fast_kernel: a thread owns one channel vector of one output position and copies it for all KS*KS taps,
+// every load issued before the first store (KS*KS loads in flight per thread instead of one, and one index
+// decomposition per KS*KS stores); a wave's stores of one tap are one contiguous run of the row.
+template <typename T, int VEC, int KS>
+__global__ __launch_bounds__(256) void im2row_build_fast_kernel(const T *__restrict__ I, T *__restrict__ rows,
+                                                                int n, int c, int h, int w, int pad, int q, int p)
+{
+    typedef T vec_t __attribute__((ext_vector_type(VEC)));
+    const unsigned cv = (unsigned)c / VEC;
+    const unsigned per_image = (unsigned)q * p * cv;
+    const unsigned row_elems = (unsigned)(KS * KS) * c;                   // elements of one patch row
+    for (unsigned in = blockIdx.y; in < (unsigned)n; in += gridDim.y) {
+        const T *In = I + (size_t)in * h * w * c;
+        T *Rn = rows + (size_t)in * q * p * row_elems;
+        for (unsigned e = blockIdx.x * 256u + threadIdx.x; e < per_image; e += gridDim.x * 256u) {
+            const unsigned ic = e % cv, pos = e / cv;
+            const int op = (int)(pos % (unsigned)p), oq = (int)(pos / (unsigned)p);
+            vec_t v[KS][KS];
+#pragma unroll
+            for (int i = 0; i < KS; ++i)
+#pragma unroll
+                for (int j = 0; j < KS; ++j) {
+                    const int y = oq - pad + i, x = op - pad + j;
+#pragma unroll
+                    for (int u = 0; u < VEC; ++u) v[i][j][u] = T(0);
+                    if ((unsigned)y < (unsigned)h && (unsigned)x < (unsigned)w)
+                        v[i][j] = *reinterpret_cast<const vec_t *>(In + ((size_t)y * w + x) * c + (size_t)ic * VEC);
+                }
+            T *dst = Rn + (size_t)pos * row_elems + (size_t)ic * VEC;
+#pragma unroll
+            for (int i = 0; i < KS; ++i)
+#pragma unroll
+                for (int j = 0; j < KS; ++j)
+                    __builtin_nontemporal_store(v[i][j], reinterpret_cast<vec_t *>(dst + (size_t)(i * KS + j) * c));
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Shift-add post pass of section III-A: O[n][m][q][p] = sum over taps of T[n][t*M+m][s*q+di][s*p+dj]
 // (s = stride, 1 in the paper), offsets taken in the 2-D plane; positions outside the H x W plane are discarded.

@@ -958,13 +958,25 @@ int conv_mcmk_im2row(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool bf16 = d->dtype == CONV_MCMK_BF16;
     const int vec = bf16 ? 8 : 4;
-    const dim3 grid(stream_grid((size_t)dm.q * dm.p * dm.taps * (d->c / vec), 1), d->n < 65535 ? d->n : 65535), block(256);
-    if (bf16)
-        hipLaunchKernelGGL((im2row_build_kernel<uint16_t, 8>), grid, block, 0, st, static_cast<const uint16_t *>(I_dev),
-                           static_cast<uint16_t *>(ws), d->n, d->c, d->h, d->w, d->k, d->pad, d->stride, dm.q, dm.p);
-    else
-        hipLaunchKernelGGL((im2row_build_kernel<float, 4>), grid, block, 0, st, static_cast<const float *>(I_dev),
-                           static_cast<float *>(ws), d->n, d->c, d->h, d->w, d->k, d->pad, d->stride, dm.q, dm.p);
+    const int images = d->n < 65535 ? d->n : 65535;
+    if (d->stride == 1 && (d->k == 3 || d->k == 5)) {
+        // the common case: all k*k taps of a channel vector per thread
+        const dim3 grid(stream_grid((size_t)dm.q * dm.p * (d->c / vec), 1), images), block(256);
+#define MCMK_IM2ROW_FAST(T, V, KS)                                                                            \
+    hipLaunchKernelGGL((im2row_build_fast_kernel<T, V, KS>), grid, block, 0, st, static_cast<const T *>(I_dev), \
+                       static_cast<T *>(ws), d->n, d->c, d->h, d->w, d->pad, dm.q, dm.p)
+        if (bf16) { if (d->k == 3) MCMK_IM2ROW_FAST(uint16_t, 8, 3); else MCMK_IM2ROW_FAST(uint16_t, 8, 5); }
+        else      { if (d->k == 3) MCMK_IM2ROW_FAST(float, 4, 3);    else MCMK_IM2ROW_FAST(float, 4, 5); }
+#undef MCMK_IM2ROW_FAST
+    } else {
+        const dim3 grid(stream_grid((size_t)dm.q * dm.p * dm.taps * (d->c / vec), 1), images), block(256);
+        if (bf16)
+            hipLaunchKernelGGL((im2row_build_kernel<uint16_t, 8>), grid, block, 0, st, static_cast<const uint16_t *>(I_dev),
+                               static_cast<uint16_t *>(ws), d->n, d->c, d->h, d->w, d->k, d->pad, d->stride, dm.q, dm.p);
+        else
+            hipLaunchKernelGGL((im2row_build_kernel<float, 4>), grid, block, 0, st, static_cast<const float *>(I_dev),
+                               static_cast<float *>(ws), d->n, d->c, d->h, d->w, d->k, d->pad, d->stride, dm.q, dm.p);
+    }
     if ((rc = launch_status())) return rc;
     // O[n][q*P+p][m] = rows[n][q*P+p][:] . Khat[:][m]: the channels-last GEMM
     return launch_gemm(d, ws, Kp_dev, static_cast<float *>(O_dev), (long long)d->c * dm.taps, dm.q, dm.p, 1, st, true);

@@ -11,7 +11,7 @@ from oracle import steps
 from paper_1704_04428_amd import binding as B
 from paper_1704_04428_amd import workloads as wl
 
-from gpu_util import TOL_F32, announce, assert_within_bound, run_variant
+from gpu_util import TOL_F32, Guarded, announce, assert_within_bound, run_variant
 
 pytestmark = pytest.mark.gpu
 
@@ -416,3 +416,35 @@ def test_calls_can_be_captured_into_a_graph(case):
             assert torch.equal(plan.out, want), f"replay {rep} differs from the eager result"
     ref, absref = oracle.mcmk(I2, K, pad)
     assert_within_bound(plan.out.cpu().numpy(), ref, absref, TOL_F32, f"graph replay {case}")
+
+
+def test_machine_rate_probes():
+    """The benchmark's two probe kernels: the copy moves exactly the bytes it is told to (and nothing beyond them),
+    the register-only matrix-core loop writes one finite value per lane; bad arguments are return codes."""
+    import torch
+    announce("probes")
+    nbytes = 3 * 4096 + 16 * 5                                   # not a multiple of the workgroup's 4 KiB
+    src = Guarded(nbytes)
+    dst = Guarded(nbytes)
+    src.payload.copy_(torch.arange(nbytes, device="cuda", dtype=torch.int64).to(torch.uint8))
+    B.conv_mcmk_probe_copy(src.payload, dst.payload, nbytes)
+    torch.cuda.synchronize()
+    assert torch.equal(src.payload, dst.payload) and dst.intact() and src.intact()
+    for dtype in (B.F32, B.BF16):
+        sink = Guarded(8 * 256 * 4)
+        B.conv_mcmk_probe_mfma(dtype, 8, 10, sink.payload)
+        torch.cuda.synchronize()
+        vals = sink.payload.view(torch.float32)
+        assert sink.intact() and bool(torch.isfinite(vals).all()) and float(vals.abs().max()) > 0.0
+    with pytest.raises(B.ConvMcmkError) as e:
+        B.conv_mcmk_probe_copy(src.payload, dst.payload, 24)     # not a multiple of 16
+    assert e.value.code == B.ERR_SHAPE
+    with pytest.raises(B.ConvMcmkError) as e:
+        B.conv_mcmk_probe_mfma(7, 8, 10, dst.payload)
+    assert e.value.code == B.ERR_UNSUPPORTED
+    with pytest.raises(B.ConvMcmkError) as e:
+        B.conv_mcmk_probe_mfma(B.F32, 0, 10, dst.payload)
+    assert e.value.code == B.ERR_SHAPE
+    with pytest.raises(B.ConvMcmkError) as e:
+        B.conv_mcmk_probe_copy(None, dst.payload, 16)
+    assert e.value.code == B.ERR_NULL
