@@ -361,7 +361,9 @@ double flat_gemm_us(const conv_mcmk_desc *d, const Dims &dm, bool channels_last,
     // a product with a short contraction is bound by reading its right operand and writing its result (4 TB/s)
     const double moved_mb = (double)d->n * d->c * cols * (bf16 ? 2.0e-6 : 4.0e-6) + out_mb;
     if (us < moved_mb / 4.0) us = moved_mb / 4.0;
-    if (cs > 1) us += 3.0 + (channels_last ? 3.1 : 1.6) * out_mb * (cs / 2.0);
+    // (channels last, a lane's four rows are 16 bytes of one position: four scattered atomics where [M][Q][P] output has
+    // runs of sixteen -- measured three times the cost per MB: cfg5c's im2row 150 us split four ways, 181 us split eight)
+    if (cs > 1) us += 3.0 + (channels_last ? 9.0 : 1.6) * out_mb * (cs / 2.0);
     return us;
 }
 
@@ -507,6 +509,23 @@ GemmView gemm_view(const conv_mcmk_desc *d, long long kc, int ph, int pw, int ro
     return v;
 }
 
+// im2row's product: channels last, the patch rows of all images are one [N Q P] x [C k k] matrix and the outputs one
+// [N Q P] x [M] matrix, so the batch folds into the plane (one image of N Q P positions) and small planes fill whole
+// 224-column tiles -- unless a 2-D tile is forced, which wants the plane's own shape, or the folded plane would pass
+// the 32-bit offsets of one image.
+void im2row_plane(const conv_mcmk_desc *d, const Dims &dm, conv_mcmk_desc *view, int *ph, int *pw)
+{
+    *view = *d;
+    *ph = dm.q;
+    *pw = dm.p;
+    const long long positions = (long long)d->n * dm.q * dm.p;
+    if (forced_index(g_force_gemm_tile, "CONV_MCMK_GEMM_TILE") < 0 && ((long long)d->c * dm.taps + 64) * positions < (1LL << 29)) {
+        view->n = 1;
+        *ph = 1;
+        *pw = (int)positions;
+    }
+}
+
 double gemm_cost(const conv_mcmk_desc *d, long long kc, int ph, int pw, int row_groups, bool channels_last = false)
 {
     const GemmView v = gemm_view(d, kc, ph, pw, row_groups);
@@ -539,8 +558,14 @@ double variant_cost(const conv_mcmk_desc *d, const Dims &dm, int variant)
     }
     case CONV_MCMK_IM2COL:
     case CONV_MCMK_IM2ROW:
-        return stream_cost(elt * (in_elems + patch_elems), variant == CONV_MCMK_IM2ROW || (d->stride == 1 && (d->k == 3 || d->k == 5))) +
-               gemm_cost(d, (long long)d->c * dm.taps, dm.q, dm.p, 1, variant == CONV_MCMK_IM2ROW);
+    {
+        const double build = stream_cost(elt * (in_elems + patch_elems), variant == CONV_MCMK_IM2ROW || (d->stride == 1 && (d->k == 3 || d->k == 5)));
+        if (variant == CONV_MCMK_IM2COL) return build + gemm_cost(d, (long long)d->c * dm.taps, dm.q, dm.p, 1, false);
+        conv_mcmk_desc folded;
+        int ph, pw;
+        im2row_plane(d, dm, &folded, &ph, &pw);
+        return build + gemm_cost(&folded, (long long)d->c * dm.taps, ph, pw, 1, true);
+    }
     default: {
         // one thread per output walks its C*k*k terms one after the other (0.12 us each when the chip
         // is not full); a full chip sustains 3 TFLOP/s
@@ -761,7 +786,18 @@ int conv_mcmk_describe_plan(const conv_mcmk_desc *d, int variant, char *buf, siz
                  variant_cost(d, dm, variant));
         break;
     case CONV_MCMK_IM2ROW:
-        gemm_text((long long)d->c * dm.taps, dm.q, dm.p, 1, true, tile, sizeof(tile));
+        {
+            conv_mcmk_desc folded;
+            int ph, pw;
+            im2row_plane(d, dm, &folded, &ph, &pw);
+            const GemmView v = gemm_view(&folded, (long long)d->c * dm.taps, ph, pw, 1);
+            const Candidate c = choose_fused(&v.d, v.dm, true, false, true);
+            const bool flat = c.shape == kGemmShape || c.shape == kWideGemmShape;
+            const long long cols = flat ? ceil_div((long long)ph * pw, c.tw) : (long long)ceil_div(pw, c.tw) * ceil_div(ph, c.th);
+            snprintf(tile, sizeof(tile), "tile %dx%d%s, waves %dx%d, row blocks %d, channel groups %d, channel split %d, %lld workgroups",
+                     c.th, c.tw, flat ? (folded.n == 1 && d->n > 1 ? " over the flattened planes of the batch" : " over the flattened plane") : "",
+                     c.wm, c.wp, c.rb, c.kg, c.csplit, (long long)folded.n * cols * ceil_div(v.dm.mb, c.wm * c.rb) * c.csplit);
+        }
         snprintf(buf, n, "im2row %s: patch matrix [%d x %d] per image (channels last), GEMM [%d x %d].[%d x %d] (%s), est %.1f us",
                  type, dm.q * dm.p, d->c * dm.taps, dm.q * dm.p, d->c * dm.taps, d->c * dm.taps, d->m, tile,
                  variant_cost(d, dm, variant));
@@ -979,7 +1015,10 @@ int conv_mcmk_im2row(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_
     }
     if ((rc = launch_status())) return rc;
     // O[n][q*P+p][m] = rows[n][q*P+p][:] . Khat[:][m]: the channels-last GEMM
-    return launch_gemm(d, ws, Kp_dev, static_cast<float *>(O_dev), (long long)d->c * dm.taps, dm.q, dm.p, 1, st, true);
+    conv_mcmk_desc folded;
+    int ph, pw;
+    im2row_plane(d, dm, &folded, &ph, &pw);
+    return launch_gemm(&folded, ws, Kp_dev, static_cast<float *>(O_dev), (long long)d->c * dm.taps, ph, pw, 1, st, true);
 }
 
 int conv_mcmk_direct(const conv_mcmk_desc *d, const void *I_dev, const void *K_dev, void *O_dev,

@@ -262,10 +262,11 @@ def test_runtime_errors_through_binding():
 @pytest.mark.parametrize("dtype", [B.F32, B.BF16])
 @pytest.mark.parametrize("k,pad", [(1, 0), (2, 1), (3, 1), (4, 1), (5, 2), (6, 3), (7, 3)])
 def test_every_tile_shape_of_the_menu(k, pad, dtype, monkeypatch):
-    """The selector only ever launches the shape it prefers; force each of the 30 menu entries
-    (7 common tile / wave shapes, then 4 bf16-only shapes with two row blocks per wave, the quarter tiles, the two
-    fp32-only pairs of tiles under sixteen waves and the fp32-only quarter tiles with two channel groups, each with channel split 1 and 2; entries the operand type or kernel side does not have fall back to the selector) so every
-    instantiation is checked."""
+    """The selector only ever launches the shape it prefers; force each of the 34 menu entries (7 common tile / wave
+    shapes; then 4 bf16-only shapes with two row blocks per wave, the quarter tiles, the two fp32-only pairs of tiles
+    under sixteen waves and the fp32-only quarter tiles with two channel groups; then the two bf16-only four-wave
+    shapes; each with channel split 1 and 2; entries the operand type or kernel side does not have fall back to the
+    selector) so every instantiation is checked."""
     from gpu_util import TOL_BF16
     case = (2, 72, 33, 30, 80, k, pad)        # 5 (fp32) / 3 (bf16) channel chunks: an uneven split
     n, c, h, w, m, _, _ = case
