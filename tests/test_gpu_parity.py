@@ -449,3 +449,44 @@ def test_machine_rate_probes():
     with pytest.raises(B.ConvMcmkError) as e:
         B.conv_mcmk_probe_copy(None, dst.payload, 16)
     assert e.value.code == B.ERR_NULL
+
+
+@pytest.mark.parametrize("k", [3, 5])
+@pytest.mark.parametrize("w", [16, 12, 10, 9, 1])          # output widths that are multiples of 8, 4, 2, odd, and a single column
+def test_streaming_forms_of_the_builds_and_the_post_pass(k, w):
+    """Unit stride with kernel side 3 or 5 takes the streaming forms of the patch-matrix builds (section II-B) and of
+    the shift-add post pass (section III-A): vector widths 8 / 4 / 2 / 1 by output width, every padding from none to
+    k - 1 (vectors that hang over either end of a row, rows outside the image, the first and the last element of the
+    whole product), fp32 and bf16.  The workspaces must BE the paper's matrices, bit for bit, and on integer data the
+    two-pass output must equal the oracle exactly."""
+    n, c, h, m = 2, 8, 7, 5
+    for pad in range(0, k):
+        if h + 2 * pad < k or w + 2 * pad < k:
+            continue
+        win = w - 2 * pad + k - 1                           # input width that gives output width w
+        if win < 1:
+            continue
+        announce("streaming forms", "k", k, "out width", w, "pad", pad)
+        I = wl.small_integers(7000 + 10 * k + pad, n * c * h * win, 0, 8).reshape(n, c, h, win)
+        K = wl.small_integers(7001 + 10 * k + pad, m * c * k * k, -4, 4).reshape(m, c, k, k)
+        ref, _ = oracle.mcmk(I, K, pad)
+        q, p = ref.shape[2], ref.shape[3]
+        assert p == w
+        got, ws = run_variant(B.KN2ROW_2PASS, I, K, pad, return_ws=True)
+        np.testing.assert_array_equal(got.astype(np.float64), ref)
+        T = ws.view(np.float32).reshape(n, k * k * m, h * win)
+        for i in range(n):
+            np.testing.assert_array_equal(T[i].astype(np.float64), steps.kn2row_gemm(I[i], K))
+        for dtype in (B.F32, B.BF16):
+            got, ws = run_variant(B.IM2COL, I, K, pad, dtype=dtype, return_ws=True)
+            np.testing.assert_array_equal(got.astype(np.float64), ref)          # small integers are exact in bf16 too
+            cols = ws.view(np.uint16 if dtype == B.BF16 else np.float32).reshape(n, c * k * k, q * p)
+            for i in range(n):
+                want = steps.input_patch_matrix(I[i], k, pad).astype(np.float32)
+                np.testing.assert_array_equal(cols[i], steps.round_to_bf16_bits(want).reshape(want.shape) if dtype == B.BF16 else want)
+            got, ws = run_variant(B.IM2ROW, I, K, pad, dtype=dtype, return_ws=True)
+            np.testing.assert_array_equal(got.astype(np.float64), ref)
+            rows = ws.view(np.uint16 if dtype == B.BF16 else np.float32).reshape(n, q * p, k * k * c)
+            for i in range(n):
+                want = steps.input_patch_matrix_rows(np.ascontiguousarray(I[i].transpose(1, 2, 0)), k, pad).astype(np.float32)
+                np.testing.assert_array_equal(rows[i], steps.round_to_bf16_bits(want).reshape(want.shape) if dtype == B.BF16 else want)
