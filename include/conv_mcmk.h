@@ -108,7 +108,13 @@ int conv_mcmk_describe_plan(const conv_mcmk_desc *desc, int variant, char *buf, 
  *   IM2COL:       N * C*k*k * Q*P elements of the input's type -- the input-patch-matrix of
  *                 section II-B, per image Ihat[(c*k + i)*k + j][q*P + p] (k*k times the input).
  *   IM2ROW:       the same number of elements, per image rows[q*P + p][(i*k + j)*C + c].
- * After a 2PASS / IM2COL call the workspace holds exactly those matrices.
+ * After a 2PASS / IM2COL / IM2ROW call the workspace starts with exactly those matrices.
+ * IM2COL and IM2ROW ask for more than their matrix when the matrix product that follows splits its contraction
+ * C*k*k into 2, 4 or 8 parts (deep contractions with small outputs, which would otherwise leave most of the chip
+ * idle): behind the matrix, at the next multiple of 256 bytes, each part then stores a copy of the result (N*M*Q*P
+ * floats rounded up to a multiple of 4), and a last pass adds the copies in a fixed order.  A workspace that holds
+ * the matrix but not the copies is accepted: the parts then add into the zeroed output with atomics, which is slower
+ * and, beyond two parts, not bit-reproducible from call to call.
  */
 size_t conv_mcmk_workspace_bytes(const conv_mcmk_desc *desc, int variant);
 
@@ -157,14 +163,17 @@ int conv_mcmk_run(const conv_mcmk_desc *desc, int variant, const void *I_dev, co
  *   Kp_dev  kernel: the packed form from conv_mcmk_prepack(desc, <this variant>) --
  *           except conv_mcmk_direct, which takes the plain float K[M][C][k][k]
  *   O_dev   output, float
- *   ws, ws_bytes  scratch of at least conv_mcmk_workspace_bytes(); may be NULL / 0 when that is 0
+ *   ws, ws_bytes  scratch of at least conv_mcmk_workspace_bytes() (at least the matrix named there: see the note
+ *           on IM2COL / IM2ROW); may be NULL / 0 when that is 0
  * conv_mcmk_kn2row implements k = 1 .. 7 and stride 1 or 2 (otherwise CONV_MCMK_ERR_UNSUPPORTED; the
  * other variants take any k >= 1 and any stride >= 1).  conv_mcmk_direct implements CONV_MCMK_F32 only.
  * With a stride the two-pass variant still forms all k*k*M x H*W products (the GEMM of section III-A
  * has no notion of an output position) and subsamples in the post pass; im2col and im2row build
  * only the patches that are used.
  * Results are bit-reproducible from call to call: where conv_mcmk_kn2row splits the channels over two
- * workgroups it adds exactly two partial sums into a zeroed output, which is order-independent.
+ * workgroups it adds exactly two partial sums into a zeroed output, which is order-independent, and the deeper
+ * splits of the im2col / im2row product add their parts' copies in a fixed order (given the workspace
+ * conv_mcmk_workspace_bytes() asks for).
  */
 int conv_mcmk_kn2row(const conv_mcmk_desc *desc, const void *I_dev, const void *Kp_dev, void *O_dev,
                      void *ws, size_t ws_bytes, void *stream);
@@ -247,8 +256,9 @@ int conv_mcmk_cvt_f32_bf16(const void *src_dev, void *dst_dev, size_t count, voi
  * Tuning aids (host only, process-wide, thread-safe; no part of the method).  The fused kernels and the
  * matrix product of the staged variants each pick a tile shape from a menu by a cost estimate;
  * conv_mcmk_force_tile / conv_mcmk_force_gemm_tile make every later call take menu entry `index` instead
- * (for an entry the layer's operand type, kernel side or stride does not have, the estimate still chooses); a
- * negative index gives the choice back to the estimate.  The environment variables CONV_MCMK_TILE / CONV_MCMK_GEMM_TILE set
+ * (for an entry the layer's operand type, kernel side or stride does not have -- or an index beyond the menu -- the
+ * estimate still chooses, among the menu's entries: while an index is set, a 1 x 1 layer is not run as a plain matrix
+ * product on the flat tile shape); a negative index gives the choice back to the estimate.  The environment variables CONV_MCMK_TILE / CONV_MCMK_GEMM_TILE set
  * the initial value; they are read once, when the library is first used.
  */
 void conv_mcmk_force_tile(int index);

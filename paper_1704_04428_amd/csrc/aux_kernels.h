@@ -380,6 +380,36 @@ __global__ void fill_zero_kernel(float *__restrict__ dst, size_t count)
 }
 
 // ---------------------------------------------------------------------------------------------
+// Add up the PARTS copies of a result that the parts of a split contraction stored one after the other
+// (copy i starts stride * i floats into src; stride a multiple of 4, both pointers 16-byte aligned):
+// dst[e] = ((src[0][e] + src[1][e]) + src[2][e]) + ...  -- always in this order, so the sum does not depend on
+// which workgroup finished first.  One 16-byte item per thread, every load issued before the first add.
+template <int PARTS>
+__global__ __launch_bounds__(256) void sum_parts_kernel(const float *__restrict__ src, float *__restrict__ dst,
+                                                        size_t count, size_t stride)
+{
+    typedef float vec_t __attribute__((ext_vector_type(4)));
+    const size_t vec = count / 4;
+    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (e < vec) {
+        vec_t v[PARTS];
+#pragma unroll
+        for (int i = 0; i < PARTS; ++i) v[i] = __builtin_nontemporal_load(reinterpret_cast<const vec_t *>(src + (size_t)i * stride) + e);
+        vec_t sum = v[0];
+#pragma unroll
+        for (int i = 1; i < PARTS; ++i) sum += v[i];
+        __builtin_nontemporal_store(sum, reinterpret_cast<vec_t *>(dst) + e);
+    }
+    if (blockIdx.x == 0 && threadIdx.x < count - vec * 4) {
+        const size_t t = vec * 4 + threadIdx.x;
+        float sum = src[t];
+#pragma unroll
+        for (int i = 1; i < PARTS; ++i) sum += src[(size_t)i * stride + t];
+        dst[t] = sum;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Measurement aids: the machine rates the benchmark compares the kernels with.
 //
 // Register-only matrix-core loop: 16 independent accumulators per wave, operands fixed in registers, no memory

@@ -175,12 +175,16 @@ bool lean_applies(const conv_mcmk_desc *d, int ks, int shape, int csplit, bool c
            ((stride == 1 && (shape == 0 || shape == 3 || shape == 4)) || (stride == 2 && (shape == 0 || shape == 1)));
 }
 
+// Floats between the copies of a result that the parts of a split contraction store: the result, rounded up to whole
+// 16-byte items.
+size_t partial_floats(size_t total) { return (total + 3) / 4 * 4; }
+
 // One launch of the tile kernel: a convolution (ks x ks taps, row_groups = 1) or a plain GEMM
 // (ks = 1 over a 1 x cols image, row_groups row planes of m rows each).
 int launch_tile(const conv_mcmk_desc *d, const Dims &dm, int ks, int shape, int csplit, const void *in,
                 const void *apk, float *out, int in_c, int in_h, int in_w, int out_q, int out_p, int pad,
                 int row_groups, hipStream_t st, bool channels_last = false, int stride = 1,
-                const Epilogue &ep = Epilogue())
+                const Epilogue &ep = Epilogue(), float *partials = nullptr)
 {
     TileRequest rq;
     TileArgs &a = rq.args;
@@ -201,10 +205,24 @@ int launch_tile(const conv_mcmk_desc *d, const Dims &dm, int ks, int shape, int 
     rq.stride = stride;
     rq.lean = in_c == d->c && lean_applies(d, ks, shape, csplit, channels_last, stride, row_groups);
     rq.stream = st;
+    a.part_stride = 0;
+    const size_t total = (size_t)a.n * row_groups * d->m * out_q * out_p;
+    if (csplit > 1 && partials && (csplit == 2 || csplit == 4 || csplit == 8)) {
+        // every part stores its sums into a copy of its own (partial_floats() each), and a streaming pass adds the
+        // copies in a fixed order: no zero fill, no atomics, the same bits on every run
+        a.out = partials;
+        a.part_stride = (long long)partial_floats(total);
+        if (int rc = run_tile(d->dtype, ks, rq)) return rc;
+        const dim3 grid(stream_grid(total / 4 + 1, 1)), block(256);
+        const size_t stride = (size_t)a.part_stride;
+        if (csplit == 2) hipLaunchKernelGGL(sum_parts_kernel<2>, grid, block, 0, st, partials, out, total, stride);
+        else if (csplit == 4) hipLaunchKernelGGL(sum_parts_kernel<4>, grid, block, 0, st, partials, out, total, stride);
+        else hipLaunchKernelGGL(sum_parts_kernel<8>, grid, block, 0, st, partials, out, total, stride);
+        return launch_status();
+    }
     if (csplit > 1) {
         // partial sums are added into the output, so it starts from zero (a fill kernel, not a
         // memset node, so the call can be captured into a graph)
-        const size_t total = (size_t)a.n * row_groups * d->m * out_q * out_p;
         hipLaunchKernelGGL(fill_zero_kernel, dim3(grid_for(total / 4 + 1, 256)), dim3(256), 0, st, out, total);
         if (int rc = launch_status()) return rc;
     }
@@ -338,56 +356,67 @@ double tile_cost(const conv_mcmk_desc *d, const Dims &dm, const Candidate &c, in
 // since: the bf16 four-wave workgroups).
 Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, bool epilogue, int force, bool gemm = false);
 
-// The tile a staged variant's matrix product runs on unless one is forced: the flat shape (64 or 128 rows x 224
-// columns of the plane taken as one row, 32-channel chunks), with the contraction split 1, 2, 4 or 8 ways.  A split
-// buys workgroups for a product with few tiles (two per compute unit hide each other's staging; below one per unit
-// the chip is idle in proportion) and pays a zero fill plus one atomic add per part and output element.  The rates
-// are what the kernel sustained on the benchmark layers; timings of every menu entry there put this rule within a
-// tenth of the best entry (the 2-D tiles of the fused kernel stage too little per barrier for a product whose every
-// value is used once, and the estimate that serves the fused kernel misjudges them by up to 40 % here).
-double flat_gemm_us(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, int shape, int cs)
+constexpr int kGemmAtomics = 1, kGemmCopies = 2;   // how the parts of a split matrix product meet (choose_fused)
+
+// The tile a staged variant's matrix product runs on unless one is forced: a flat shape (64 rows, or for bf16 also 128
+// rows with two row blocks per wave, x 224 columns of the plane taken as one row, 32-channel chunks), with the
+// contraction split 1, 2, 4 or 8 ways.  A split buys workgroups for a product with few tiles (two per compute unit hide
+// each other's staging; below one per unit the chip is idle in proportion) and pays for the way its parts meet: a copy
+// of the result per part plus a streaming pass that adds the copies (im2col, im2row: room in their workspace), or a
+// zero fill plus one atomic add per part and output element.  The rates are what the kernel sustained when every
+// shape and split was timed on the benchmark layers' three staged variants, both precisions (the pick then loses 1 %
+// on average and 13 % at worst against the fastest entry; the 2-D tiles of the fused kernel stage too little per
+// barrier for a product whose every value is used once, and were never the fastest there).
+double flat_gemm_us(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, int shape, int cs, bool copies)
 {
     const bool bf16 = d->dtype == CONV_MCMK_BF16;
     const long long cols = (long long)dm.q * dm.p;
     const TileShapeDesc &t = kTileShapes[shape];
-    const long long w = (long long)d->n * ceil_div(cols, t.tw) * ceil_div(dm.mb, t.wm * t.rb) * cs;
+    const long long col_tiles = ceil_div(cols, t.tw);
+    const long long w = (long long)d->n * col_tiles * ceil_div(dm.mb, t.wm * t.rb) * cs;
     const double flop = 2.0 * d->n * (dm.mb * 16.0) * cols * d->c;
     const double out_mb = (double)d->n * (dm.mb * 16.0) * cols * 4.0e-6;
-    // fraction of the matrix peak the kernel sustains: two workgroups per unit, one, or a partly idle chip
-    // (bf16 with two row blocks per wave: a fifth more, measured on the two-pass products)
-    const double full = bf16 ? (t.rb == 2 ? 0.17 : 0.14) : 0.62, single = bf16 ? 0.09 : 0.50;
+    // Fraction of the matrix peak the kernel sustains with two workgroups per compute unit (full) and with one (single).
+    // bf16 with one row block per wave reads a B fragment from LDS per product and is bound by that; two row blocks per
+    // wave halve the reads but need the second workgroup to cover their latency.  Channels last, the staging gather and
+    // its transposing LDS stores cost a fifth to a third (im2row's products).
+    double full, single;
+    if (!bf16)           { full = channels_last ? 0.54 : 0.66;   single = channels_last ? 0.50 : 0.60; }
+    else if (t.rb == 2)  { full = channels_last ? 0.26 : 0.40;   single = channels_last ? 0.15 : 0.18; }
+    else                 { full = channels_last ? 0.125 : 0.17;  single = channels_last ? 0.08 : 0.09; }
     const double eff = w >= 448 ? full : w >= kNumCU ? single : single * (double)w / kNumCU;
-    double us = flop / ((bf16 ? 2500.0e6 : 157.3e6) * eff);
-    // a product with a short contraction is bound by reading its right operand and writing its result (4 TB/s)
-    const double moved_mb = (double)d->n * d->c * cols * (bf16 ? 2.0e-6 : 4.0e-6) + out_mb;
-    if (us < moved_mb / 4.0) us = moved_mb / 4.0;
-    // (channels last, a lane's four rows are 16 bytes of one position: four scattered atomics where [M][Q][P] output has
-    // runs of sixteen -- measured three times the cost per MB: cfg5c's im2row 150 us split four ways, 181 us split eight)
-    if (cs > 1) us += 3.0 + (channels_last ? 9.0 : 1.6) * out_mb * (cs / 2.0);
+    const double compute = flop / ((bf16 ? 2500.0e6 : 157.3e6) * eff);
+    // reading the right operand and writing the result (every part's copy of it), at 3.5 TB/s: what bounds a product
+    // with a short contraction (the two-pass form's, whose result is k k times the output)
+    const double moved_mb = (double)d->n * d->c * cols * (bf16 ? 2.0e-6 : 4.0e-6) + out_mb * (copies && cs > 1 ? cs : 1);
+    const double memory = moved_mb / 3.5;
+    double us = (compute > memory ? compute : memory) + 0.1 * (compute > memory ? memory : compute);
+    // the parts' meeting: the pass that reads the copies and writes their sum (4.5 TB/s), or the zero fill and the
+    // atomics (channels last, a lane's four rows are 16 bytes of one position: four scattered atomics where [M][Q][P]
+    // output has runs of sixteen -- measured at several times the cost per MB)
+    if (cs > 1) us += copies ? 3.0 + (cs + 1.0) * out_mb / 4.5 : 3.0 + (channels_last ? 9.0 : 1.6) * out_mb * (cs / 2.0);
     return us;
 }
 
-Candidate flat_gemm_candidate(const conv_mcmk_desc *d, const Dims &dm, bool channels_last)
+Candidate flat_gemm_candidate(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, bool copies)
 {
-    const bool bf16 = d->dtype == CONV_MCMK_BF16;
-    const long long cols = (long long)dm.q * dm.p;
     const int chunks = ceil_div(d->c, 32);
-    // bf16: two row blocks per wave (half the LDS reads per product) where that alone fills the chip twice over
-    const TileShapeDesc &wide = kTileShapes[kWideGemmShape];
-    if (bf16 && (long long)d->n * ceil_div(cols, wide.tw) * ceil_div(dm.mb, wide.wm * wide.rb) >= 2 * kNumCU)
-        return candidate(kWideGemmShape, 1);
-    int best = 1;
-    double best_us = 0.0;
-    for (int cs = 1; cs <= 8 && (cs == 1 || chunks / cs >= 2); cs *= 2) {
-        const double us = flat_gemm_us(d, dm, channels_last, kGemmShape, cs);
-        if (cs == 1 || us < best_us) { best = cs; best_us = us; }
-    }
-    return candidate(kGemmShape, best);
+    const int shapes[2] = {kGemmShape, kWideGemmShape};
+    Candidate best = candidate(kGemmShape, 1);
+    double best_us = -1.0;
+    for (int s = 0; s < (d->dtype == CONV_MCMK_BF16 ? 2 : 1); ++s)
+        for (int cs = 1; cs <= 8 && (cs == 1 || chunks / cs >= 2); cs *= 2) {
+            const double us = flat_gemm_us(d, dm, channels_last, shapes[s], cs, copies);
+            if (best_us < 0.0 || us < best_us) { best = candidate(shapes[s], cs); best_us = us; }
+        }
+    return best;
 }
 
 // The search walks the whole menu, a few microseconds of host time -- as long as the smallest layers
 // run on the GPU -- so the last few answers are remembered (per layer, layout, epilogue and override).
-Candidate choose_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, bool epilogue = false, bool gemm = false)
+// gemm: 0 a convolution; 1 the matrix product of a staged variant whose split parts add into the result with
+// atomics; 2 one whose parts each store a copy of the result (kGemmCopies).
+Candidate choose_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, bool epilogue = false, int gemm = 0)
 {
     const int force = gemm ? forced_index(g_force_gemm_tile, "CONV_MCMK_GEMM_TILE") : forced_index(g_force_tile, "CONV_MCMK_TILE");
     struct Key {
@@ -397,7 +426,7 @@ Candidate choose_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_la
     Key key;
     memset(&key, 0, sizeof(key));
     key.d = *d;
-    key.flags = (channels_last ? 1 : 0) | (epilogue ? 2 : 0) | (gemm ? 4 : 0);
+    key.flags = (channels_last ? 1 : 0) | (epilogue ? 2 : 0) | (gemm << 2);
     key.forced = force;
     key.mb = dm.mb;                       // a matrix product's rows may be (tap, kernel) pairs
     constexpr int kSlots = 32;
@@ -410,7 +439,8 @@ Candidate choose_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_la
         for (int i = 0; i < used; ++i)
             if (memcmp(&keys[i], &key, sizeof(Key)) == 0) return vals[i];
     }
-    const Candidate best = (gemm && force < 0) ? flat_gemm_candidate(d, dm, channels_last) : search_fused(d, dm, channels_last, epilogue, force, gemm);
+    const Candidate best = (gemm && force < 0) ? flat_gemm_candidate(d, dm, channels_last, gemm == kGemmCopies)
+                                               : search_fused(d, dm, channels_last, epilogue, force, gemm != 0);
     {
         std::lock_guard<std::mutex> lock(mu);
         keys[next] = key;
@@ -526,14 +556,50 @@ void im2row_plane(const conv_mcmk_desc *d, const Dims &dm, conv_mcmk_desc *view,
     }
 }
 
-double gemm_cost(const conv_mcmk_desc *d, long long kc, int ph, int pw, int row_groups, bool channels_last = false)
+double gemm_cost(const conv_mcmk_desc *d, long long kc, int ph, int pw, int row_groups, bool channels_last = false, int mode = kGemmAtomics)
 {
     const GemmView v = gemm_view(d, kc, ph, pw, row_groups);
-    const Candidate c = choose_fused(&v.d, v.dm, channels_last, false, true);
+    const Candidate c = choose_fused(&v.d, v.dm, channels_last, false, mode);
     // the flat shapes: the rates the kernel was measured to sustain, plus a launch; a forced 2-D tile: the fused
     // kernel's estimate for a 1 x 1 layer
-    if (c.shape == kGemmShape || c.shape == kWideGemmShape) return flat_gemm_us(&v.d, v.dm, channels_last, c.shape, c.csplit) + 5.0;
+    if (c.shape == kGemmShape || c.shape == kWideGemmShape) return flat_gemm_us(&v.d, v.dm, channels_last, c.shape, c.csplit, mode == kGemmCopies) + 5.0;
     return tile_cost(&v.d, v.dm, c, 1, channels_last);
+}
+
+// How a fused call runs.  A 1 x 1 kernel without padding or stride makes the layer a plain matrix product over the
+// plane (section III-A), with no tile edges inside the image: where the flat shape's estimate beats the best 2-D
+// tile's by a tenth, the call runs as that product.  ([C][H][W] input only: with channels last the flat shape measured
+// 3 - 8 % slower than the tiles on the layers where its estimate won.)  The product may split its contraction two ways
+// at most, as the tiles do: two parts at the atomics keep the result independent of their order.
+struct FusedPlan {
+    Candidate c;
+    double cost;
+    bool as_product;
+    conv_mcmk_desc view;   // as_product: the layer the product's launch sees ...
+    int ph, pw;            // ... and its plane
+};
+
+FusedPlan plan_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, bool epilogue)
+{
+    FusedPlan f;
+    f.c = choose_fused(d, dm, channels_last, epilogue);
+    f.cost = tile_cost(d, dm, f.c, d->k, channels_last);
+    f.as_product = false;
+    f.view = *d;  f.ph = d->h;  f.pw = d->w;
+    if (d->k != 1 || d->pad != 0 || d->stride != 1 || channels_last) return f;
+    if (forced_index(g_force_tile, "CONV_MCMK_TILE") >= 0 || forced_index(g_force_gemm_tile, "CONV_MCMK_GEMM_TILE") >= 0) return f;
+    const conv_mcmk_desc view = *d;
+    const int ph = d->h, pw = d->w;
+    if ((long long)ph * pw >= (1LL << 31)) return f;
+    const GemmView v = gemm_view(&view, d->c, ph, pw, 1);
+    const Candidate g = choose_fused(&v.d, v.dm, channels_last, false, kGemmAtomics);
+    if ((g.shape != kGemmShape && g.shape != kWideGemmShape) || g.csplit > (epilogue ? 1 : 2)) return f;
+    const double cost = flat_gemm_us(&v.d, v.dm, channels_last, g.shape, g.csplit, false) + 5.0;
+    if (cost < 0.9 * f.cost) {
+        f.c = g;  f.cost = cost;  f.as_product = true;
+        f.view = view;  f.ph = ph;  f.pw = pw;
+    }
+    return f;
 }
 
 // a memory-bound pass before or after the matrix kernel: its bytes, its launch, and the drain / fill
@@ -550,7 +616,7 @@ double variant_cost(const conv_mcmk_desc *d, const Dims &dm, int variant)
     switch (variant) {
     case CONV_MCMK_KN2ROW:
     case CONV_MCMK_KN2COL:
-        return tile_cost(d, dm, choose_fused(d, dm, variant == CONV_MCMK_KN2COL), d->k, variant == CONV_MCMK_KN2COL);
+        return plan_fused(d, dm, variant == CONV_MCMK_KN2COL, false).cost;
     case CONV_MCMK_KN2ROW_2PASS: {
         const double planes = (double)d->n * d->m * d->h * d->w;
         return gemm_cost(d, d->c, d->h, d->w, dm.taps) +
@@ -560,11 +626,11 @@ double variant_cost(const conv_mcmk_desc *d, const Dims &dm, int variant)
     case CONV_MCMK_IM2ROW:
     {
         const double build = stream_cost(elt * (in_elems + patch_elems), variant == CONV_MCMK_IM2ROW || (d->stride == 1 && (d->k == 3 || d->k == 5)));
-        if (variant == CONV_MCMK_IM2COL) return build + gemm_cost(d, (long long)d->c * dm.taps, dm.q, dm.p, 1, false);
+        if (variant == CONV_MCMK_IM2COL) return build + gemm_cost(d, (long long)d->c * dm.taps, dm.q, dm.p, 1, false, kGemmCopies);
         conv_mcmk_desc folded;
         int ph, pw;
         im2row_plane(d, dm, &folded, &ph, &pw);
-        return build + gemm_cost(&folded, (long long)d->c * dm.taps, ph, pw, 1, true);
+        return build + gemm_cost(&folded, (long long)d->c * dm.taps, ph, pw, 1, true, kGemmCopies);
     }
     default: {
         // one thread per output walks its C*k*k terms one after the other (0.12 us each when the chip
@@ -576,10 +642,16 @@ double variant_cost(const conv_mcmk_desc *d, const Dims &dm, int variant)
     }
 }
 
+int launch_product(const conv_mcmk_desc *d, const Candidate &c, const void *bmat, const void *apk, float *cmat, long long kc,
+                   int ph, int pw, int row_groups, hipStream_t st, bool channels_last, const Epilogue &ep, float *partials);
+
 int launch_fused(const conv_mcmk_desc *d, const Dims &dm, const void *in, const void *apk, float *out,
                  hipStream_t st, bool channels_last, const Epilogue &ep = Epilogue())
 {
-    const Candidate best = choose_fused(d, dm, channels_last, ep.any());
+    const FusedPlan plan = plan_fused(d, dm, channels_last, ep.any());
+    if (plan.as_product)
+        return launch_product(&plan.view, plan.c, in, apk, out, d->c, plan.ph, plan.pw, 1, st, channels_last, ep, nullptr);
+    const Candidate &best = plan.c;
     return launch_tile(d, dm, d->k, best.shape, best.csplit, in, apk, out, d->c, d->h, d->w, dm.q, dm.p, d->pad, 1, st,
                        channels_last, d->stride, ep);
 }
@@ -587,17 +659,31 @@ int launch_fused(const conv_mcmk_desc *d, const Dims &dm, const void *in, const 
 // Plain matrix product [row_groups M x kc] . [kc x ph pw] per image on the tile kernels: a 1 x 1 "convolution" over
 // the ph x pw plane, with the tile shape (2-D tiles, channel groups, channel split, or the flat 1 x 224 shape over the
 // plane taken as one row) chosen by the same estimate that serves the fused kernel.
+// mode kGemmCopies: `spare` (spare_bytes of device memory, 16-byte aligned, or null) takes one copy of the result per
+// part of a split contraction; a buffer too small for them sends the parts back to atomics on a zeroed result.
 int launch_gemm(const conv_mcmk_desc *d, const void *bmat, const void *apk, float *cmat,
-                long long kc, int ph, int pw, int row_groups, hipStream_t st, bool channels_last = false)
+                long long kc, int ph, int pw, int row_groups, hipStream_t st, bool channels_last = false,
+                int mode = kGemmAtomics, void *spare = nullptr, size_t spare_bytes = 0)
 {
     if ((long long)ph * pw >= (1LL << 31) || kc >= (1LL << 31)) return CONV_MCMK_ERR_SHAPE;
     const GemmView v = gemm_view(d, kc, ph, pw, row_groups);
-    const Candidate c = choose_fused(&v.d, v.dm, channels_last, false, true);
+    const Candidate c = choose_fused(&v.d, v.dm, channels_last, false, mode);
+    const size_t result = (size_t)d->n * row_groups * d->m * ph * pw;
+    float *partials = nullptr;
+    if (mode == kGemmCopies && c.csplit > 1 && spare && spare_bytes >= partial_floats(result) * sizeof(float) * c.csplit)
+        partials = static_cast<float *>(spare);
+    return launch_product(d, c, bmat, apk, cmat, kc, ph, pw, row_groups, st, channels_last, Epilogue(), partials);
+}
+
+// The launch of a matrix product on candidate c: the flat shapes see the plane as one row of ph pw columns.
+int launch_product(const conv_mcmk_desc *d, const Candidate &c, const void *bmat, const void *apk, float *cmat, long long kc,
+                   int ph, int pw, int row_groups, hipStream_t st, bool channels_last, const Epilogue &ep, float *partials)
+{
     const bool flat = c.shape == kGemmShape || c.shape == kWideGemmShape;
     const int h = flat ? 1 : ph, w = flat ? ph * pw : pw;
-    Dims dm = v.dm;
-    dm.mb = ceil_div(d->m, 16);                  // launch_tile takes the blocks of one row group
-    return launch_tile(d, dm, 1, c.shape, c.csplit, bmat, apk, cmat, (int)kc, h, w, h, w, 0, row_groups, st, channels_last);
+    const Dims dm{ph, pw, ceil_div(d->m, 16), 1};          // launch_tile takes the blocks of one row group
+    return launch_tile(d, dm, 1, c.shape, c.csplit, bmat, apk, cmat, (int)kc, h, w, h, w, 0, row_groups, st, channels_last, 1,
+                       ep, partials);
 }
 
 int common_ptr_checks(const void *I, const void *K, const void *O)
@@ -607,9 +693,41 @@ int common_ptr_checks(const void *I, const void *K, const void *O)
     return CONV_MCMK_OK;
 }
 
+// The matrix a staged variant builds or fills: the part of its workspace it cannot do without.
+size_t workspace_matrix_bytes(const conv_mcmk_desc *d, const Dims &dm, int variant)
+{
+    const size_t elt = d->dtype == CONV_MCMK_BF16 ? 2 : 4;
+    switch (variant) {
+    case CONV_MCMK_KN2ROW_2PASS: return (size_t)d->n * dm.taps * d->m * d->h * d->w * sizeof(float);
+    case CONV_MCMK_IM2COL:
+    case CONV_MCMK_IM2ROW: return (size_t)d->n * d->c * dm.taps * dm.q * dm.p * elt;
+    default: return 0;
+    }
+}
+
+// Where the copies of the result start behind that matrix, and how many bytes they take: one copy per part when the
+// product of im2col / im2row splits its contraction, none otherwise.
+size_t workspace_copies_offset(size_t matrix_bytes) { return (matrix_bytes + 255) / 256 * 256; }
+
+size_t workspace_copies_bytes(const conv_mcmk_desc *d, const Dims &dm, int variant)
+{
+    if (variant != CONV_MCMK_IM2COL && variant != CONV_MCMK_IM2ROW) return 0;
+    conv_mcmk_desc view = *d;
+    int ph = dm.q, pw = dm.p;
+    if (variant == CONV_MCMK_IM2ROW) im2row_plane(d, dm, &view, &ph, &pw);
+    const long long kc = (long long)d->c * dm.taps;
+    if ((long long)ph * pw >= (1LL << 31) || kc >= (1LL << 31)) return 0;
+    const GemmView v = gemm_view(&view, kc, ph, pw, 1);
+    const Candidate c = choose_fused(&v.d, v.dm, variant == CONV_MCMK_IM2ROW, false, kGemmCopies);
+    if (c.csplit < 2) return 0;
+    return partial_floats((size_t)d->n * d->m * dm.q * dm.p) * sizeof(float) * c.csplit;
+}
+
 int workspace_check(const conv_mcmk_desc *d, int variant, const void *ws, size_t ws_bytes)
 {
-    const size_t need = conv_mcmk_workspace_bytes(d, variant);
+    Dims dm;
+    if (int rc = validate(d, variant, &dm)) return rc;
+    const size_t need = workspace_matrix_bytes(d, dm, variant);
     if (need == 0) return CONV_MCMK_OK;
     if (!ws || ws_bytes < need) return CONV_MCMK_ERR_WORKSPACE;
     if (misaligned(ws)) return CONV_MCMK_ERR_ALIGN;
@@ -753,9 +871,9 @@ int conv_mcmk_describe_plan(const conv_mcmk_desc *d, int variant, char *buf, siz
     if (!buf || n == 0) return CONV_MCMK_ERR_NULL;
     const char *type = d->dtype == CONV_MCMK_BF16 ? "bf16" : "f32";
     // the tile the matrix product of a staged variant would run on
-    auto gemm_text = [&](long long kc, int ph, int pw, int row_groups, bool cl, char *out, size_t len) {
+    auto gemm_text = [&](long long kc, int ph, int pw, int row_groups, bool cl, int mode, char *out, size_t len) {
         const GemmView v = gemm_view(d, kc, ph, pw, row_groups);
-        const Candidate c = choose_fused(&v.d, v.dm, cl, false, true);
+        const Candidate c = choose_fused(&v.d, v.dm, cl, false, mode);
         const bool flat = c.shape == kGemmShape || c.shape == kWideGemmShape;
         const long long cols = flat ? ceil_div((long long)ph * pw, c.tw) : (long long)ceil_div(pw, c.tw) * ceil_div(ph, c.th);
         snprintf(out, len, "tile %dx%d%s, waves %dx%d, row blocks %d, channel groups %d, channel split %d, %lld workgroups",
@@ -766,21 +884,25 @@ int conv_mcmk_describe_plan(const conv_mcmk_desc *d, int variant, char *buf, siz
     switch (variant) {
     case CONV_MCMK_KN2ROW:
     case CONV_MCMK_KN2COL: {
-        const Candidate c = choose_fused(d, dm, variant == CONV_MCMK_KN2COL);
-        const long long wgs = (long long)d->n * ceil_div(dm.p, c.tw) * ceil_div(dm.q, c.th) * ceil_div(dm.mb, c.wm * c.rb) * c.csplit;
-        const bool lean = lean_applies(d, d->k, c.shape, c.csplit, variant == CONV_MCMK_KN2COL, d->stride, 1);
-        snprintf(buf, n, "%s fused %s: tile %dx%d, waves %dx%d, row blocks %d, channel groups %d, channel split %d, %lld workgroups%s, est %.1f us",
-                 variant == CONV_MCMK_KN2COL ? "kn2col" : "kn2row", type, c.th, c.tw, c.wm, c.wp, c.rb, c.kg, c.csplit, wgs,
-                 lean ? ", one channel quad" : "", tile_cost(d, dm, c, d->k, variant == CONV_MCMK_KN2COL));
+        const FusedPlan plan = plan_fused(d, dm, variant == CONV_MCMK_KN2COL, false);
+        const Candidate &c = plan.c;
+        const long long wgs = plan.as_product
+            ? (long long)plan.view.n * ceil_div((long long)plan.ph * plan.pw, c.tw) * ceil_div(dm.mb, c.wm * c.rb) * c.csplit
+            : (long long)d->n * ceil_div(dm.p, c.tw) * ceil_div(dm.q, c.th) * ceil_div(dm.mb, c.wm * c.rb) * c.csplit;
+        const bool lean = !plan.as_product && lean_applies(d, d->k, c.shape, c.csplit, variant == CONV_MCMK_KN2COL, d->stride, 1);
+        snprintf(buf, n, "%s fused %s: tile %dx%d%s, waves %dx%d, row blocks %d, channel groups %d, channel split %d, %lld workgroups%s, est %.1f us",
+                 variant == CONV_MCMK_KN2COL ? "kn2col" : "kn2row", type, c.th, c.tw,
+                 !plan.as_product ? "" : plan.view.n == 1 && d->n > 1 ? " over the flattened planes of the batch" : " over the flattened plane",
+                 c.wm, c.wp, c.rb, c.kg, c.csplit, wgs, lean ? ", one channel quad" : "", plan.cost);
         break;
     }
     case CONV_MCMK_KN2ROW_2PASS:
-        gemm_text(d->c, d->h, d->w, dm.taps, false, tile, sizeof(tile));
+        gemm_text(d->c, d->h, d->w, dm.taps, false, kGemmAtomics, tile, sizeof(tile));
         snprintf(buf, n, "kn2row two-pass %s: GEMM [%d x %d].[%d x %d] per image (%s), then shift-add, est %.1f us",
                  type, dm.taps * d->m, d->c, d->c, d->h * d->w, tile, variant_cost(d, dm, variant));
         break;
     case CONV_MCMK_IM2COL:
-        gemm_text((long long)d->c * dm.taps, dm.q, dm.p, 1, false, tile, sizeof(tile));
+        gemm_text((long long)d->c * dm.taps, dm.q, dm.p, 1, false, kGemmCopies, tile, sizeof(tile));
         snprintf(buf, n, "im2col %s: patch matrix [%d x %d] per image, GEMM [%d x %d].[%d x %d] (%s), est %.1f us",
                  type, d->c * dm.taps, dm.q * dm.p, d->m, d->c * dm.taps, d->c * dm.taps, dm.q * dm.p, tile,
                  variant_cost(d, dm, variant));
@@ -791,7 +913,7 @@ int conv_mcmk_describe_plan(const conv_mcmk_desc *d, int variant, char *buf, siz
             int ph, pw;
             im2row_plane(d, dm, &folded, &ph, &pw);
             const GemmView v = gemm_view(&folded, (long long)d->c * dm.taps, ph, pw, 1);
-            const Candidate c = choose_fused(&v.d, v.dm, true, false, true);
+            const Candidate c = choose_fused(&v.d, v.dm, true, false, kGemmCopies);
             const bool flat = c.shape == kGemmShape || c.shape == kWideGemmShape;
             const long long cols = flat ? ceil_div((long long)ph * pw, c.tw) : (long long)ceil_div(pw, c.tw) * ceil_div(ph, c.th);
             snprintf(tile, sizeof(tile), "tile %dx%d%s, waves %dx%d, row blocks %d, channel groups %d, channel split %d, %lld workgroups",
@@ -814,13 +936,9 @@ size_t conv_mcmk_workspace_bytes(const conv_mcmk_desc *d, int variant)
 {
     Dims dm;
     if (validate(d, variant, &dm) != CONV_MCMK_OK) return 0;
-    const size_t elt = d->dtype == CONV_MCMK_BF16 ? 2 : 4;
-    switch (variant) {
-    case CONV_MCMK_KN2ROW_2PASS: return (size_t)d->n * dm.taps * d->m * d->h * d->w * sizeof(float);
-    case CONV_MCMK_IM2COL:
-    case CONV_MCMK_IM2ROW: return (size_t)d->n * d->c * dm.taps * dm.q * dm.p * elt;
-    default: return 0;
-    }
+    const size_t matrix = workspace_matrix_bytes(d, dm, variant);
+    const size_t copies = workspace_copies_bytes(d, dm, variant);
+    return copies ? workspace_copies_offset(matrix) + copies : matrix;
 }
 
 size_t conv_mcmk_packed_kernel_bytes(const conv_mcmk_desc *d, int variant)
@@ -907,10 +1025,8 @@ int conv_mcmk_1x1(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_dev
     if (d->k != 1) return CONV_MCMK_ERR_UNSUPPORTED;
     if ((rc = common_ptr_checks(I_dev, Kp_dev, O_dev))) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    // without padding or stride the image is just H*W columns of the matrix [C x HW] (section III-A):
-    // a plain GEMM with no tile edges inside the image
-    if (d->pad == 0 && d->stride == 1)
-        return launch_gemm(d, I_dev, Kp_dev, static_cast<float *>(O_dev), d->c, d->h, d->w, 1, st);
+    // without padding or stride the image is just H*W columns of the matrix [C x HW] (section III-A): the fused
+    // path runs it as a plain product with no tile edges inside the image where that is the faster of the two
     return launch_fused(d, dm, I_dev, Kp_dev, static_cast<float *>(O_dev), st, false);
 }
 
@@ -980,7 +1096,9 @@ int conv_mcmk_im2col(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_
 #undef MCMK_IM2COL
     }
     if ((rc = launch_status())) return rc;
-    return launch_gemm(d, ws, Kp_dev, static_cast<float *>(O_dev), (long long)d->c * dm.taps, dm.q, dm.p, 1, st);
+    const size_t copies_at = workspace_copies_offset(workspace_matrix_bytes(d, dm, CONV_MCMK_IM2COL));
+    return launch_gemm(d, ws, Kp_dev, static_cast<float *>(O_dev), (long long)d->c * dm.taps, dm.q, dm.p, 1, st, false, kGemmCopies,
+                       ws_bytes > copies_at ? static_cast<char *>(ws) + copies_at : nullptr, ws_bytes > copies_at ? ws_bytes - copies_at : 0);
 }
 
 int conv_mcmk_im2row(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_dev, void *O_dev,
@@ -1018,7 +1136,9 @@ int conv_mcmk_im2row(const conv_mcmk_desc *d, const void *I_dev, const void *Kp_
     conv_mcmk_desc folded;
     int ph, pw;
     im2row_plane(d, dm, &folded, &ph, &pw);
-    return launch_gemm(&folded, ws, Kp_dev, static_cast<float *>(O_dev), (long long)d->c * dm.taps, ph, pw, 1, st, true);
+    const size_t copies_at = workspace_copies_offset(workspace_matrix_bytes(d, dm, CONV_MCMK_IM2ROW));
+    return launch_gemm(&folded, ws, Kp_dev, static_cast<float *>(O_dev), (long long)d->c * dm.taps, ph, pw, 1, st, true, kGemmCopies,
+                       ws_bytes > copies_at ? static_cast<char *>(ws) + copies_at : nullptr, ws_bytes > copies_at ? ws_bytes - copies_at : 0);
 }
 
 int conv_mcmk_direct(const conv_mcmk_desc *d, const void *I_dev, const void *K_dev, void *O_dev,

@@ -46,6 +46,9 @@ struct TileArgs {
     int row_tiles;        // ceil(row_groups*mb_per_group / WM)
     int csplit;           // 1, or 2: two workgroups share a tile, each takes half the chunks and
                           // adds its partial sums into a zeroed output (a + b is order-independent)
+    long long part_stride; // 0: the parts of a split add into `out` with atomics.  Otherwise part i stores its sums
+                          // plainly into the copy of the output that starts part_stride * i floats into `out`
+                          // (the caller adds the copies up in a fixed order afterwards: no zero fill, no atomics)
     const float *bias;    // [row_groups * m] added to every output of its row, or nullptr (csplit == 1 only)
     int relu;             // nonzero: negative results are stored as zero (csplit == 1 only)
 };
@@ -295,10 +298,11 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
         AFrag f;
 #pragma unroll
         for (int qq = 0; qq < NQ; ++qq) {
-            // a chunk may reach past the last packed group: read the last one and zero it
+            // a chunk may reach past the last packed group: read the last one again (it is zeroed where it is used:
+            // a select here, on the value just asked for, makes the wave wait for the load on the spot, and with
+            // it for every staging load issued before it)
             const int g16 = min(c0 + qq, a.cg - 1);
-            const f32x4 v = apk[((tap * a.mb_per_group + mbi) * a.cg + g16) * 64 + lane];
-            f.q[qq] = (NQ == 1 || c0 + qq < a.cg) ? v : f32x4{0.f, 0.f, 0.f, 0.f};
+            f.q[qq] = apk[((tap * a.mb_per_group + mbi) * a.cg + g16) * 64 + lane];
         }
         return f;
     };
@@ -339,7 +343,12 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
         for (int b = 0; b < NB; ++b) bq[0][b] = bsrc[b_off[b]];
 #pragma unroll
         for (int t = 0; t < T; ++t) {
-            const AFrag a_cur = a_queue[0];
+            AFrag a_cur = a_queue[0];
+            if constexpr (NQ > 1) {
+#pragma unroll
+                for (int qq = 1; qq < NQ; ++qq)
+                    if (chunk * NQ + qq >= a.cg) a_cur.q[qq] = f32x4{0.f, 0.f, 0.f, 0.f};   // wave-uniform
+            }
 #pragma unroll
             for (int d = 0; d + 1 < kDepth; ++d) a_queue[d] = a_queue[d + 1];
             a_queue[kDepth - 1] = load_a(chunk + KG * ((t + kDepth) / T), (t + kDepth) % T);
@@ -412,7 +421,8 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
     if (!rb_valid) return;
     const size_t oplane = (size_t)a.q * a.p;
     const int out_rows = a.row_groups * a.m;
-    float *out_img = a.out + (size_t)img * out_rows * oplane;
+    float *out_img = a.out + (size_t)part * (size_t)a.part_stride + (size_t)img * out_rows * oplane;
+    const bool plain = a.csplit == 1 || a.part_stride != 0;       // this workgroup owns what it writes
     if (a.bias != nullptr || a.relu) {
         // layer epilogue on the finished sums: per-row offset, then the rectifier
         const int mrow0 = mbi * 16 + 4 * (lane >> 4);
@@ -440,13 +450,13 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
         if constexpr (CL) {
             // channels last: the lane's four rows are four consecutive floats of one output position
             float *dst = out_img + ((size_t)y * a.p + x) * out_rows + (size_t)grp * a.m + mrow0;
-            if (a.csplit == 1 && (out_rows & 3) == 0 && mrow0 + 3 < a.m) {
+            if (plain && (out_rows & 3) == 0 && mrow0 + 3 < a.m) {
                 *reinterpret_cast<f32x4 *>(dst) = acc[b];
             } else {
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     if (mrow0 + v >= a.m) continue;
-                    if (a.csplit == 1) dst[v] = acc[b][v];
+                    if (plain) dst[v] = acc[b][v];
                     else unsafeAtomicAdd(dst + v, acc[b][v]);
                 }
             }
@@ -456,7 +466,7 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
                 const int mrow = mrow0 + v;
                 if (mrow >= a.m) continue;
                 float *dst = out_img + (size_t)(grp * a.m + mrow) * oplane + (size_t)y * a.p + x;
-                if (a.csplit == 1) *dst = acc[b][v];
+                if (plain) *dst = acc[b][v];
                 else unsafeAtomicAdd(dst, acc[b][v]);      // hardware fp32 add at the L2
             }
         }

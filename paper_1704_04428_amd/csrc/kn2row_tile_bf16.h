@@ -371,7 +371,8 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_bf16(const Tile
 
     const size_t oplane = (size_t)a.q * a.p;
     const int out_rows = a.row_groups * a.m;
-    float *out_img = a.out + (size_t)img * out_rows * oplane;
+    float *out_img = a.out + (size_t)part * (size_t)a.part_stride + (size_t)img * out_rows * oplane;
+    const bool plain = a.csplit == 1 || a.part_stride != 0;       // this workgroup owns what it writes
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
         if (!rb_valid[r]) continue;
@@ -400,13 +401,13 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_bf16(const Tile
             if (pp >= TH * TW || y >= a.q || x >= a.p) continue;
             if constexpr (CL) {
                 float *dst = out_img + ((size_t)y * a.p + x) * out_rows + (size_t)grp[r] * a.m + mrow0;
-                if (a.csplit == 1 && (out_rows & 3) == 0 && mrow0 + 3 < a.m) {
+                if (plain && (out_rows & 3) == 0 && mrow0 + 3 < a.m) {
                     *reinterpret_cast<f32x4 *>(dst) = acc[r][b];
                 } else {
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         if (mrow0 + v >= a.m) continue;
-                        if (a.csplit == 1) dst[v] = acc[r][b][v];
+                        if (plain) dst[v] = acc[r][b][v];
                         else unsafeAtomicAdd(dst + v, acc[r][b][v]);
                     }
                 }
@@ -416,7 +417,7 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_bf16(const Tile
                     const int mrow = mrow0 + v;
                     if (mrow >= a.m) continue;
                     float *dst = out_img + (size_t)(grp[r] * a.m + mrow) * oplane + (size_t)y * a.p + x;
-                    if (a.csplit == 1) *dst = acc[r][b][v];
+                    if (plain) *dst = acc[r][b][v];
                     else unsafeAtomicAdd(dst, acc[r][b][v]);
                 }
             }

@@ -9,7 +9,7 @@ import argparse
 import json
 
 from paper_1704_04428_amd import binding as B
-from paper_1704_04428_amd.tuning.sweep_tiles import MENU_INDICES, plan_key
+from paper_1704_04428_amd.tuning.sweep_tiles import MENU_INDICES, MENU_ONLY, plan_key
 
 VARIANTS = {"kn2row": B.KN2ROW, "kn2col": B.KN2COL}
 DTYPES = {"f32": B.F32, "bf16": B.BF16}
@@ -18,8 +18,11 @@ DTYPES = {"f32": B.F32, "bf16": B.BF16}
 def pick(row):
     n, c, h, m, k = row["layer"]
     d = B.desc(n, c, h, h, m, k, k // 2, 1, DTYPES[row["dtype"]])
-    B.conv_mcmk_force_tile(-1)
-    return plan_key(B.conv_mcmk_describe_plan(d, VARIANTS[row["variant"]]))
+    B.conv_mcmk_force_tile(MENU_ONLY)
+    try:
+        return plan_key(B.conv_mcmk_describe_plan(d, VARIANTS[row["variant"]]))
+    finally:
+        B.conv_mcmk_force_tile(-1)
 
 
 def estimates(row):

@@ -23,6 +23,9 @@ import sys
 import numpy as np
 
 MENU_INDICES = list(range(34))
+# An index that names no menu entry leaves the choice to the estimate, among the menu's entries alone: a 1 x 1 layer
+# is then not run as a plain matrix product on the flat shape, which these tables do not time.
+MENU_ONLY = 1 << 20
 
 
 def plan_key(text: str) -> str:

@@ -32,7 +32,7 @@ class Guarded:
         return bool((head == CANARY).all().item()) and bool((tail == CANARY).all().item())
 
 
-def run_variant(variant, I, K, pad, dtype=B.F32, return_ws=False, stride=1, epilogue=None, one_by_one=False):
+def run_variant(variant, I, K, pad, dtype=B.F32, return_ws=False, stride=1, epilogue=None, one_by_one=False, matrix_only=False):
     """I [N][C][H][W] float32 numpy, K [M][C][k][k] float32 numpy -> O float32 numpy via the C ABI.
     epilogue = (bias [M] float32 numpy or None, relu) routes the call through the *_bias_relu entry
     point of the variant (kn2row / kn2col); one_by_one = True through conv_mcmk_1x1."""
@@ -62,6 +62,13 @@ def run_variant(variant, I, K, pad, dtype=B.F32, return_ws=False, stride=1, epil
         kern = kp.payload
     out = Guarded(n * m * q * p * 4)
     ws_bytes = B.conv_mcmk_workspace_bytes(d, variant)
+    # the matrix a staged variant keeps in its workspace; im2col / im2row may ask for room behind it (copies of the
+    # result for the parts of a split contraction) and must also run, on atomics, when given the matrix alone
+    matrix_bytes = {B.KN2ROW_2PASS: n * k * k * m * h * w * 4, B.IM2COL: n * c * k * k * q * p * (2 if dtype == B.BF16 else 4),
+                    B.IM2ROW: n * c * k * k * q * p * (2 if dtype == B.BF16 else 4)}.get(variant, 0)
+    assert ws_bytes >= matrix_bytes
+    if matrix_only:
+        ws_bytes = matrix_bytes
     ws = Guarded(ws_bytes) if ws_bytes else None
     if epilogue is not None:
         bias, relu = epilogue
@@ -84,7 +91,7 @@ def run_variant(variant, I, K, pad, dtype=B.F32, return_ws=False, stride=1, epil
     else:
         O = out.payload.view(torch.float32).reshape(n, m, q, p).cpu().numpy()
     if return_ws:
-        return O, (ws.payload.cpu().numpy() if ws is not None else None)
+        return O, (ws.payload[:matrix_bytes].cpu().numpy() if ws is not None else None)
     return O
 
 

@@ -94,15 +94,22 @@ def test_check_rejects_bad_descriptors(lib):
 def test_sizes(lib):
     d = B.desc(2, 20, 9, 11, 35, 3, 1)
     q, p = 9, 11
+
+    def patch_workspace(desc, variant, matrix_bytes, result_floats):
+        # the patch matrix, alone or followed (at the next multiple of 256 bytes) by 2, 4 or 8 copies of the result
+        total = B.conv_mcmk_workspace_bytes(desc, variant)
+        copies = (result_floats + 3) // 4 * 4 * 4
+        assert total in [matrix_bytes] + [(matrix_bytes + 255) // 256 * 256 + parts * copies for parts in (2, 4, 8)]
+        return total
     assert B.conv_mcmk_workspace_bytes(d, B.KN2ROW) == 0
     assert B.conv_mcmk_workspace_bytes(d, B.DIRECT) == 0
     assert B.conv_mcmk_workspace_bytes(d, B.KN2ROW_2PASS) == 2 * 9 * 35 * 9 * 11 * 4     # k^2 x the output
-    assert B.conv_mcmk_workspace_bytes(d, B.IM2COL) == 2 * 20 * 9 * q * p * 4             # k^2 x the input
+    patch_workspace(d, B.IM2COL, 2 * 20 * 9 * q * p * 4, 2 * 35 * q * p)                  # k^2 x the input
     # stride 2: Q = floor((9 + 2 - 3) / 2) + 1 = 5, P = floor((11 + 2 - 3) / 2) + 1 = 6; the patch matrix shrinks,
     # the two-pass product (all H x W positions of every tap) does not
     ds = B.desc(2, 20, 9, 11, 35, 3, 1, 2)
-    assert B.conv_mcmk_workspace_bytes(ds, B.IM2COL) == 2 * 20 * 9 * 5 * 6 * 4
-    assert B.conv_mcmk_workspace_bytes(ds, B.IM2ROW) == 2 * 20 * 9 * 5 * 6 * 4
+    patch_workspace(ds, B.IM2COL, 2 * 20 * 9 * 5 * 6 * 4, 2 * 35 * 5 * 6)
+    patch_workspace(ds, B.IM2ROW, 2 * 20 * 9 * 5 * 6 * 4, 2 * 35 * 5 * 6)
     assert B.conv_mcmk_workspace_bytes(ds, B.KN2ROW_2PASS) == 2 * 9 * 35 * 9 * 11 * 4
     assert B.conv_mcmk_packed_kernel_bytes(ds, B.KN2ROW) == B.conv_mcmk_packed_kernel_bytes(d, B.KN2ROW)
     mb, cg = 3, 2      # ceil(35/16), ceil(20/16)
@@ -110,7 +117,7 @@ def test_sizes(lib):
     assert B.conv_mcmk_packed_kernel_bytes(d, B.KN2ROW_2PASS) == 9 * mb * cg * 256 * 4
     assert B.conv_mcmk_packed_kernel_bytes(d, B.KN2COL) == 9 * mb * cg * 256 * 4
     assert B.conv_mcmk_workspace_bytes(d, B.KN2COL) == 0
-    assert B.conv_mcmk_workspace_bytes(d, B.IM2ROW) == B.conv_mcmk_workspace_bytes(d, B.IM2COL)
+    patch_workspace(d, B.IM2ROW, 2 * 20 * 9 * q * p * 4, 2 * 35 * q * p)
     assert B.conv_mcmk_packed_kernel_bytes(d, B.IM2ROW) == B.conv_mcmk_packed_kernel_bytes(d, B.IM2COL)
     assert B.conv_mcmk_check(B.desc(2, 21, 9, 11, 35, 3, 1), B.IM2ROW) == B.ERR_UNSUPPORTED      # channel vectors
     assert B.conv_mcmk_packed_kernel_bytes(d, B.IM2COL) == mb * 12 * 256 * 4              # ceil(180/16) = 12
@@ -120,7 +127,7 @@ def test_sizes(lib):
     db = B.desc(2, 20, 9, 11, 35, 3, 1, 1, B.BF16)
     assert B.conv_mcmk_packed_kernel_bytes(db, B.KN2ROW) == 9 * mb * 1 * 512 * 2
     assert B.conv_mcmk_packed_kernel_bytes(db, B.IM2COL) == mb * 6 * 512 * 2                  # ceil(180/32) = 6
-    assert B.conv_mcmk_workspace_bytes(db, B.IM2COL) == 2 * 20 * 9 * q * p * 2
+    patch_workspace(db, B.IM2COL, 2 * 20 * 9 * q * p * 2, 2 * 35 * q * p)
     assert B.conv_mcmk_workspace_bytes(db, B.KN2ROW_2PASS) == 2 * 9 * 35 * 9 * 11 * 4
     assert B.conv_mcmk_check(db, B.DIRECT) == B.ERR_UNSUPPORTED
 

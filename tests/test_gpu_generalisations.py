@@ -174,6 +174,32 @@ def test_one_by_one_entry_point(dtype, case):
             assert_within_bound(got.reshape(n, m, h * w), prod, absref.reshape(n, m, h * w), TOL_F32, "1x1 as a product")
 
 
+@pytest.mark.parametrize("variant", [B.KN2ROW, B.KN2COL], ids=["kn2row", "kn2col"])
+@pytest.mark.parametrize("dtype,case", [(B.F32, (8, 48, 40, 40, 256, 1, 0, 1)), (B.F32, (6, 40, 50, 30, 200, 1, 0, 1)),
+                                        (B.BF16, (8, 256, 40, 40, 512, 1, 0, 1))])
+def test_one_by_one_layers_run_as_a_plain_product(dtype, case, variant):
+    """Large 1 x 1 layers without padding or stride, [C][H][W] input: the fused call runs on the flat tile shape over
+    the flattened plane, and the plan text says so (channels last: the 2-D tiles, same checks).  Plain, with the
+    epilogue, and on exact integer data."""
+    announce("1x1 as a product", dtype, case, variant)
+    n, c, h, w, m = case[:5]
+    plan = B.conv_mcmk_describe_plan(B.desc(*case[:7], case[7], dtype), variant)
+    assert ("flattened plane" in plan) == (variant == B.KN2ROW), plan
+    I, K = _inputs(case, 3600 + sum(case))
+    ref, absref = oracle.mcmk(I, K, 0)
+    tol = TOL_BF16 if dtype == B.BF16 else TOL_F32
+    assert_within_bound(run_variant(variant, I, K, 0, dtype=dtype), ref, absref, tol, f"1x1 product {case}")
+    if variant == B.KN2ROW:
+        assert_within_bound(run_variant(variant, I, K, 0, dtype=dtype, one_by_one=True), ref, absref, tol, f"1x1 entry {case}")
+    bias = wl.uniform(3699, m, -0.5, 0.5)
+    got = run_variant(variant, I, K, 0, dtype=dtype, epilogue=(bias, True))
+    assert_within_bound(got, oracle.bias_relu(ref, bias, True), absref + np.abs(bias).reshape(1, -1, 1, 1), tol, f"1x1 product + epilogue {case}")
+    assert got.min() >= 0.0 and (got == 0.0).any() and (got > 0.0).any()
+    Ii = wl.small_integers(3601, n * c * h * w, 0, 8).reshape(n, c, h, w)
+    Ki = wl.small_integers(3602, m * c, -4, 4).reshape(m, c, 1, 1)
+    np.testing.assert_array_equal(run_variant(variant, Ii, Ki, 0, dtype=dtype).astype(np.float64), oracle.mcmk(Ii, Ki, 0)[0])
+
+
 def test_one_by_one_entry_point_refuses_larger_kernels():
     import torch
     d = B.desc(1, 4, 8, 8, 4, 3, 1)

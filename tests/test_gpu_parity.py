@@ -11,7 +11,7 @@ from oracle import steps
 from paper_1704_04428_amd import binding as B
 from paper_1704_04428_amd import workloads as wl
 
-from gpu_util import TOL_F32, Guarded, announce, assert_within_bound, run_variant
+from gpu_util import TOL_BF16, TOL_F32, Guarded, announce, assert_within_bound, run_variant
 
 pytestmark = pytest.mark.gpu
 
@@ -490,3 +490,36 @@ def test_streaming_forms_of_the_builds_and_the_post_pass(k, w):
             for i in range(n):
                 want = steps.input_patch_matrix_rows(np.ascontiguousarray(I[i].transpose(1, 2, 0)), k, pad).astype(np.float32)
                 np.testing.assert_array_equal(rows[i], steps.round_to_bf16_bits(want).reshape(want.shape) if dtype == B.BF16 else want)
+
+
+@pytest.mark.parametrize("variant", [B.IM2COL, B.IM2ROW], ids=["im2col", "im2row"])
+@pytest.mark.parametrize("dtype", [B.F32, B.BF16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("case", [(2, 64, 7, 7, 48, 3, 1), (1, 96, 13, 13, 40, 5, 2), (3, 128, 6, 10, 35, 3, 0)])
+def test_split_products_meet_in_copies_or_in_atomics(case, dtype, variant):
+    """A deep contraction with a small result is split into parts.  With the workspace the library asks for, each part
+    stores a copy of the result and a last pass adds the copies in a fixed order (the same bits on every call);
+    with room for the patch matrix alone the parts add into the zeroed output with atomics.  Small integers make
+    every sum exact, so both ways must equal the oracle bit for bit."""
+    announce("split-product", case, dtype, variant)
+    n, c, h, w, m, k, pad = case
+    d = B.desc(n, c, h, w, m, k, pad, 1, dtype)
+    plan = B.conv_mcmk_describe_plan(d, variant)
+    parts = int(plan.split("channel split ")[1].split(",")[0])
+    assert parts > 1 or dtype == B.BF16, plan    # the cases are here to cover the split (fp32 splits all of them)
+    matrix = n * c * k * k * ((h + 2 * pad - k) + 1) * ((w + 2 * pad - k) + 1) * (2 if dtype == B.BF16 else 4)
+    copies = (n * m * ((h + 2 * pad - k) + 1) * ((w + 2 * pad - k) + 1) + 3) // 4 * 16
+    assert B.conv_mcmk_workspace_bytes(d, variant) == (matrix if parts == 1 else (matrix + 255) // 256 * 256 + parts * copies)
+    I = wl.small_integers(9100 + c, n * c * h * w, 0, 8).reshape(n, c, h, w)
+    K = wl.small_integers(9101 + c, m * c * k * k, -4, 4).reshape(m, c, k, k)
+    ref, _ = oracle.mcmk(I, K, pad)
+    np.testing.assert_array_equal(run_variant(variant, I, K, pad, dtype=dtype).astype(np.float64), ref)
+    np.testing.assert_array_equal(run_variant(variant, I, K, pad, dtype=dtype, matrix_only=True).astype(np.float64), ref)
+    # inexact sums: the copies are added in a fixed order, so two calls agree in every bit; both ways stay in the bound
+    If, Kf = _inputs(case, 9200 + c)
+    ref, absref = oracle.mcmk(If, Kf, pad)
+    tol = TOL_BF16 if dtype == B.BF16 else TOL_F32
+    first = run_variant(variant, If, Kf, pad, dtype=dtype)
+    second = run_variant(variant, If, Kf, pad, dtype=dtype)
+    np.testing.assert_array_equal(first.view(np.uint32), second.view(np.uint32))
+    assert_within_bound(first, ref, absref, tol, "copies")
+    assert_within_bound(run_variant(variant, If, Kf, pad, dtype=dtype, matrix_only=True), ref, absref, tol, "atomics")
