@@ -376,10 +376,13 @@ double flat_gemm_us(const conv_mcmk_desc *d, const Dims &dm, bool channels_last,
     const long long w = (long long)d->n * col_tiles * ceil_div(dm.mb, t.wm * t.rb) * cs;
     const double flop = 2.0 * d->n * (dm.mb * 16.0) * cols * d->c;
     const double out_mb = (double)d->n * (dm.mb * 16.0) * cols * 4.0e-6;
-    // Fraction of the matrix peak the kernel sustains with two workgroups per compute unit (full) and with one (single).
-    // bf16 with one row block per wave reads a B fragment from LDS per product and is bound by that; two row blocks per
-    // wave halve the reads but need the second workgroup to cover their latency.  Channels last, the staging gather and
-    // its transposing LDS stores cost a fifth to a third (im2row's products).
+    // Fraction of the matrix peak to count with two workgroups per compute unit (full) and with one (single).  These
+    // are fitted to the time of whole calls, in which the tail of one kernel overlaps the head of the next, together
+    // with the cost of the parts' meeting below: for bf16 with two row blocks per wave they are not the kernel's own
+    // rate (0.19 - 0.24 of the peak in a trace: cfg5b's product split four ways, 62 us).  bf16 with one row block per
+    // wave reads a B fragment from LDS per product and is bound by that; two row blocks per wave halve the reads but
+    // need the second workgroup to cover their latency.  Channels last, the staging gather and its transposing LDS
+    // stores cost a fifth to a third (im2row's products).
     double full, single;
     if (!bf16)           { full = channels_last ? 0.54 : 0.66;   single = channels_last ? 0.50 : 0.60; }
     else if (t.rb == 2)  { full = channels_last ? 0.26 : 0.40;   single = channels_last ? 0.15 : 0.18; }
@@ -391,7 +394,7 @@ double flat_gemm_us(const conv_mcmk_desc *d, const Dims &dm, bool channels_last,
     const double moved_mb = (double)d->n * d->c * cols * (bf16 ? 2.0e-6 : 4.0e-6) + out_mb * (copies && cs > 1 ? cs : 1);
     const double memory = moved_mb / 3.5;
     double us = (compute > memory ? compute : memory) + 0.1 * (compute > memory ? memory : compute);
-    // the parts' meeting: the pass that reads the copies and writes their sum (4.5 TB/s), or the zero fill and the
+    // the parts' meeting: the pass that reads the copies and writes their sum (counted at 4.5 TB/s), or the zero fill and the
     // atomics (channels last, a lane's four rows are 16 bytes of one position: four scattered atomics where [M][Q][P]
     // output has runs of sixteen -- measured at several times the cost per MB)
     if (cs > 1) us += copies ? 3.0 + (cs + 1.0) * out_mb / 4.5 : 3.0 + (channels_last ? 9.0 : 1.6) * out_mb * (cs / 2.0);
