@@ -31,6 +31,23 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kXcds = 8;   // accelerator complex dies on MI355X
 
+// Division of a workgroup index by a launch constant: the host turns the divisor d into a multiplier and a shift,
+// floor(n / d) == (n * mul) >> shift for every n below 2^31 (mul = ceil(2^shift / d), shift = 31 + ceil(log2 d): the
+// error of the rounded-up reciprocal, below d / 2^shift per unit of n, stays under 1 / d).  Three scalar instructions
+// where the compiler's division by a runtime value is thirty-odd dependent ones.
+struct FastDiv {
+    uint32_t mul, shift;
+};
+
+inline FastDiv make_fast_div(uint32_t d)
+{
+    uint32_t l = 0;
+    while ((1ull << l) < d) ++l;
+    return FastDiv{(uint32_t)((((uint64_t)1 << (31 + l)) + d - 1) / d), 31 + l};
+}
+
+__device__ inline uint32_t fast_div(uint32_t n, const FastDiv &f) { return (uint32_t)(((uint64_t)n * f.mul) >> f.shift); }
+
 struct TileArgs {
     const float *in;      // [n][c][h][w]
     const float *apk;     // packed A: [taps][mb_per_tap][cg][64][4]
@@ -44,6 +61,7 @@ struct TileArgs {
     int cg;               // 16-channel groups (= ceil(c/16)) == number of chunks
     int tiles_x, tiles_y; // spatial tiles per image
     int row_tiles;        // ceil(row_groups*mb_per_group / WM)
+    FastDiv div_row_tiles, div_tiles_x, div_tiles_y;   // the reciprocals of the three counts above (set by the launcher)
     int csplit;           // 1, or 2: two workgroups share a tile, each takes half the chunks and
                           // adds its partial sums into a zeroed output (a + b is order-independent)
     long long part_stride; // 0: the parts of a split add into `out` with atomics.  Otherwise part i stores its sums
@@ -140,16 +158,18 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
         const int per_xcd = gridDim.x / kXcds;
         if (bid < per_xcd * kXcds) bid = (bid % kXcds) * per_xcd + bid / kXcds;
     }
-    // (unsigned: a division by a launch constant is thirty-odd dependent scalar instructions, and the signed
-    // form adds the sign handling on top)
+    // (a division by a launch constant is thirty-odd dependent scalar instructions: the counts come with their
+    // reciprocals, and the number of parts is a power of two)
     unsigned ubid = (unsigned)bid;
     int part = 0;
-    if (a.csplit > 1) { part = (int)(ubid % (unsigned)a.csplit);  ubid /= (unsigned)a.csplit; }
-    const int rt = (int)(ubid % (unsigned)a.row_tiles);  ubid /= (unsigned)a.row_tiles;
-    const int tx = (int)(ubid % (unsigned)a.tiles_x);    ubid /= (unsigned)a.tiles_x;
-    const int ty = (int)(ubid % (unsigned)a.tiles_y);    ubid /= (unsigned)a.tiles_y;
-    bid = (int)ubid;
-    const int img = bid;
+    if (a.csplit > 1) { part = (int)(ubid & (unsigned)(a.csplit - 1));  ubid >>= __builtin_ctz((unsigned)a.csplit); }
+    unsigned quot = fast_div(ubid, a.div_row_tiles);
+    const int rt = (int)(ubid - quot * (unsigned)a.row_tiles);  ubid = quot;
+    quot = fast_div(ubid, a.div_tiles_x);
+    const int tx = (int)(ubid - quot * (unsigned)a.tiles_x);    ubid = quot;
+    quot = fast_div(ubid, a.div_tiles_y);
+    const int ty = (int)(ubid - quot * (unsigned)a.tiles_y);    ubid = quot;
+    const int img = (int)ubid;
     const int x0 = tx * TW, y0 = ty * TH;                         // first output position of the tile
     const int ix0 = x0 * ST - a.pad, iy0 = y0 * ST - a.pad;       // input position under halo-tile element (0, 0)
 

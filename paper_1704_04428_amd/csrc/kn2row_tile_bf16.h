@@ -96,16 +96,18 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_bf16(const Tile
         const int per_xcd = gridDim.x / kXcds;
         if (bid < per_xcd * kXcds) bid = (bid % kXcds) * per_xcd + bid / kXcds;
     }
-    // (unsigned: a division by a launch constant is thirty-odd dependent scalar instructions, and the signed
-    // form adds the sign handling on top)
+    // (a division by a launch constant is thirty-odd dependent scalar instructions: the counts come with their
+    // reciprocals, and the number of parts is a power of two)
     unsigned ubid = (unsigned)bid;
     int part = 0;
-    if (a.csplit > 1) { part = (int)(ubid % (unsigned)a.csplit);  ubid /= (unsigned)a.csplit; }
-    const int rt = (int)(ubid % (unsigned)a.row_tiles);  ubid /= (unsigned)a.row_tiles;
-    const int tx = (int)(ubid % (unsigned)a.tiles_x);    ubid /= (unsigned)a.tiles_x;
-    const int ty = (int)(ubid % (unsigned)a.tiles_y);    ubid /= (unsigned)a.tiles_y;
-    bid = (int)ubid;
-    const int img = bid;
+    if (a.csplit > 1) { part = (int)(ubid & (unsigned)(a.csplit - 1));  ubid >>= __builtin_ctz((unsigned)a.csplit); }
+    unsigned quot = fast_div(ubid, a.div_row_tiles);
+    const int rt = (int)(ubid - quot * (unsigned)a.row_tiles);  ubid = quot;
+    quot = fast_div(ubid, a.div_tiles_x);
+    const int tx = (int)(ubid - quot * (unsigned)a.tiles_x);    ubid = quot;
+    quot = fast_div(ubid, a.div_tiles_y);
+    const int ty = (int)(ubid - quot * (unsigned)a.tiles_y);    ubid = quot;
+    const int img = (int)ubid;
     const int x0 = tx * TW, y0 = ty * TH;                         // first output position of the tile
     const int ix0 = x0 * ST - a.pad, iy0 = y0 * ST - a.pad;       // input position under halo-tile element (0, 0)
 

@@ -24,8 +24,11 @@ int launch_shape(const TileRequest &rq)
     a.tiles_x = (a.p + TW - 1) / TW;
     a.tiles_y = (a.q + TH - 1) / TH;
     a.row_tiles = (a.row_groups * a.mb_per_group + WM * RB - 1) / (WM * RB);
+    a.div_row_tiles = make_fast_div((uint32_t)a.row_tiles);
+    a.div_tiles_x = make_fast_div((uint32_t)a.tiles_x);
+    a.div_tiles_y = make_fast_div((uint32_t)a.tiles_y);
     const long long blocks = (long long)a.n * a.tiles_x * a.tiles_y * a.row_tiles * a.csplit;
-    if (blocks < 1 || blocks >= (1LL << 31)) return 3;
+    if (blocks < 1 || blocks >= (1LL << 31) || (a.csplit & (a.csplit - 1)) != 0) return 3;
 #if MCMK_BF16
     using S = TileShapeBf16<MCMK_KS, TH, TW, WM, WP, ST, KG>;
     constexpr size_t kLds = S::kLdsBytes;            // every channel group has its own pair of buffers
