@@ -312,3 +312,32 @@ def test_variant_selection(lib, monkeypatch):
     null = ctypes.c_void_p(0)
     assert lib.conv_mcmk_run(ctypes.byref(big), 17, null, null, null, null, 0, null) == B.ERR_UNSUPPORTED
     assert lib.conv_mcmk_run(ctypes.byref(big), B.IM2COL, null, null, null, null, 0, null) == B.ERR_NULL
+
+
+def test_patch_workspace_follows_the_split_of_the_product(lib):
+    """im2col / im2row ask for their patch matrix and, where the plan splits the contraction of their matrix product,
+    for one copy of the result per part behind it (at the next multiple of 256 bytes); the two-pass form and the fused
+    variants never ask for copies.  Host logic only: sizes against the plan text, over a few hundred layers."""
+    import numpy as np
+    rng = np.random.default_rng(77)
+    seen_split = seen_plain = 0
+    for _ in range(300):
+        n = int(rng.choice([1, 2, 8])); c = int(rng.choice([8, 16, 64, 96, 256, 512])); m = int(rng.choice([16, 35, 64, 256, 512]))
+        h = int(rng.choice([7, 13, 14, 28, 56])); w = int(rng.choice([7, 14, 27, 56])); k = int(rng.choice([1, 3, 5])); pad = k // 2
+        for dtype, elt in ((B.F32, 4), (B.BF16, 2)):
+            d = B.desc(n, c, h, w, m, k, pad, 1, dtype)
+            for variant in (B.IM2COL, B.IM2ROW):
+                if B.conv_mcmk_check(d, variant) != B.OK:
+                    continue
+                plan = B.conv_mcmk_describe_plan(d, variant)
+                parts = int(plan.split("channel split ")[1].split(",")[0])
+                matrix = n * c * k * k * h * w * elt
+                copies = (n * m * h * w + 3) // 4 * 16
+                want = matrix if parts == 1 else (matrix + 255) // 256 * 256 + parts * copies
+                assert B.conv_mcmk_workspace_bytes(d, variant) == want, (plan, want)
+                seen_split += parts > 1
+                seen_plain += parts == 1
+            if B.conv_mcmk_check(d, B.KN2ROW_2PASS) == B.OK:
+                assert B.conv_mcmk_workspace_bytes(d, B.KN2ROW_2PASS) == n * k * k * m * h * w * 4
+            assert B.conv_mcmk_workspace_bytes(d, B.KN2ROW) == 0
+    assert seen_split > 50 and seen_plain > 50, (seen_split, seen_plain)
