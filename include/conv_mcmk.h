@@ -110,7 +110,7 @@ int conv_mcmk_describe_plan(const conv_mcmk_desc *desc, int variant, char *buf, 
  *   IM2ROW:       the same number of elements, per image rows[q*P + p][(i*k + j)*C + c].
  * After a 2PASS / IM2COL / IM2ROW call the workspace starts with exactly those matrices.
  * IM2COL and IM2ROW ask for more than their matrix when the matrix product that follows splits its contraction
- * C*k*k into 2, 4 or 8 parts (deep contractions with small outputs, which would otherwise leave most of the chip
+ * C*k*k into 2, 4, 8 or 16 parts (deep contractions with small outputs, which would otherwise leave most of the chip
  * idle): behind the matrix, at the next multiple of 256 bytes, each part then stores a copy of the result (N*M*Q*P
  * floats rounded up to a multiple of 4), and a last pass adds the copies in a fixed order.  A workspace that holds
  * the matrix but not the copies is accepted: the parts then add into the zeroed output with atomics, which is slower

@@ -122,7 +122,7 @@ int grid_for(size_t total, int block)
 // Tile-shape menu for the fused kernel and the cost estimate that picks from it.
 struct Candidate {
     int shape;     // index into kTileShapes
-    int csplit;    // 1 or 2 (the flat shapes of a staged variant's matrix product: also 4 and 8)
+    int csplit;    // 1 or 2 (the flat shapes of a staged variant's matrix product: also 4, 8 and 16)
     int th, tw, wm, wp, kg, rb;
 };
 
@@ -207,7 +207,7 @@ int launch_tile(const conv_mcmk_desc *d, const Dims &dm, int ks, int shape, int 
     rq.stream = st;
     a.part_stride = 0;
     const size_t total = (size_t)a.n * row_groups * d->m * out_q * out_p;
-    if (csplit > 1 && partials && (csplit == 2 || csplit == 4 || csplit == 8)) {
+    if (csplit > 1 && partials && (csplit == 2 || csplit == 4 || csplit == 8 || csplit == 16)) {
         // every part stores its sums into a copy of its own (partial_floats() each), and a streaming pass adds the
         // copies in a fixed order: no zero fill, no atomics, the same bits on every run
         a.out = partials;
@@ -217,7 +217,8 @@ int launch_tile(const conv_mcmk_desc *d, const Dims &dm, int ks, int shape, int 
         const size_t stride = (size_t)a.part_stride;
         if (csplit == 2) hipLaunchKernelGGL(sum_parts_kernel<2>, grid, block, 0, st, partials, out, total, stride);
         else if (csplit == 4) hipLaunchKernelGGL(sum_parts_kernel<4>, grid, block, 0, st, partials, out, total, stride);
-        else hipLaunchKernelGGL(sum_parts_kernel<8>, grid, block, 0, st, partials, out, total, stride);
+        else if (csplit == 8) hipLaunchKernelGGL(sum_parts_kernel<8>, grid, block, 0, st, partials, out, total, stride);
+        else hipLaunchKernelGGL(sum_parts_kernel<16>, grid, block, 0, st, partials, out, total, stride);
         return launch_status();
     }
     if (csplit > 1) {
@@ -360,7 +361,7 @@ constexpr int kGemmAtomics = 1, kGemmCopies = 2;   // how the parts of a split m
 
 // The tile a staged variant's matrix product runs on unless one is forced: a flat shape (64 rows, or for bf16 also 128
 // rows with two row blocks per wave, x 224 columns of the plane taken as one row, 32-channel chunks), with the
-// contraction split 1, 2, 4 or 8 ways.  A split buys workgroups for a product with few tiles (two per compute unit hide
+// contraction split 1, 2, 4, 8 or 16 ways.  A split buys workgroups for a product with few tiles (two per compute unit hide
 // each other's staging; below one per unit the chip is idle in proportion) and pays for the way its parts meet: a copy
 // of the result per part plus a streaming pass that adds the copies (im2col, im2row: room in their workspace), or a
 // zero fill plus one atomic add per part and output element.  The rates are what the kernel sustained when every
@@ -374,7 +375,9 @@ double flat_gemm_us(const conv_mcmk_desc *d, const Dims &dm, bool channels_last,
     const TileShapeDesc &t = kTileShapes[shape];
     const long long col_tiles = ceil_div(cols, t.tw);
     const long long w = (long long)d->n * col_tiles * ceil_div(dm.mb, t.wm * t.rb) * cs;
-    const double flop = 2.0 * d->n * (dm.mb * 16.0) * cols * d->c;
+    // (the rows a workgroup's waves cover whether the product has them or not: 64, or 128 with two row blocks per wave)
+    const double rows = 16.0 * t.wm * t.rb * ceil_div(dm.mb, t.wm * t.rb);
+    const double flop = 2.0 * d->n * rows * cols * d->c;
     const double out_mb = (double)d->n * (dm.mb * 16.0) * cols * 4.0e-6;
     // Fraction of the matrix peak to count with two workgroups per compute unit (full) and with one (single).  These
     // are fitted to the time of whole calls, in which the tail of one kernel overlaps the head of the next, together
@@ -408,7 +411,7 @@ Candidate flat_gemm_candidate(const conv_mcmk_desc *d, const Dims &dm, bool chan
     Candidate best = candidate(kGemmShape, 1);
     double best_us = -1.0;
     for (int s = 0; s < (d->dtype == CONV_MCMK_BF16 ? 2 : 1); ++s)
-        for (int cs = 1; cs <= 8 && (cs == 1 || chunks / cs >= 2); cs *= 2) {
+        for (int cs = 1; cs <= 16 && (cs == 1 || chunks >= cs); cs *= 2) {       // every part has a chunk to work on
             const double us = flat_gemm_us(d, dm, channels_last, shapes[s], cs, copies);
             if (best_us < 0.0 || us < best_us) { best = candidate(shapes[s], cs); best_us = us; }
         }
@@ -457,12 +460,12 @@ Candidate choose_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_la
 // gemm: the layer is the matrix product of a staged variant seen as a 1 x 1 convolution (d->k == 1, no padding, unit
 // stride; the channels are the contraction index, the plane is the patch matrix's or the two-pass product's).  The
 // whole menu applies, and after it come the two flat shapes (1 x 224 columns of the plane taken as one row, 32-channel
-// chunks), each with the channels unsplit and split two, four and eight ways: indices 100 .. 107.
+// chunks), each with the channels unsplit and split two, four, eight and sixteen ways: indices 100 .. 109.
 Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_last, bool epilogue, int force, bool gemm)
 {
     Candidate best{};
     double best_cost = -1.0;
-    // (the flat shapes also with the contraction split four and eight ways: a staged variant's product over C k k
+    // (the flat shapes also with the contraction split four, eight and sixteen ways: a staged variant's product over C k k
     // channels on a small plane has few tiles, and unlike the fused kernel's two-way split more than two partial sums
     // meet at the atomics, so the last bits of such a result depend on the order they arrive in)
     // Menu passes and the index their first entry has: the seven common shapes (0), the eight further ones (14), the
@@ -471,7 +474,7 @@ Candidate search_fused(const conv_mcmk_desc *d, const Dims &dm, bool channels_la
     static const int kCommon[kConvShapes] = {0, 1, 2, 3, 4, 5, 6};
     static const int kFlat[2] = {kGemmShape, kWideGemmShape};
     const Pass passes[4] = {{kCommon, kConvShapes, 0, 2}, {kWideConvShape, kWideConvShapes, 14, 2},
-                            {kLaterConvShape, kLaterConvShapes, 30, 2}, {kFlat, 2, 100, 8}};
+                            {kLaterConvShape, kLaterConvShapes, 30, 2}, {kFlat, 2, 100, 16}};
     for (int pass = 0; pass < (gemm ? 4 : 3); ++pass)
     for (int cs = 1, index = passes[pass].first_index; cs <= passes[pass].max_split; cs *= 2)
         for (int pos = 0; pos < passes[pass].count; ++pos, ++index) {

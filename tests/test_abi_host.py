@@ -96,10 +96,10 @@ def test_sizes(lib):
     q, p = 9, 11
 
     def patch_workspace(desc, variant, matrix_bytes, result_floats):
-        # the patch matrix, alone or followed (at the next multiple of 256 bytes) by 2, 4 or 8 copies of the result
+        # the patch matrix, alone or followed (at the next multiple of 256 bytes) by 2, 4, 8 or 16 copies of the result
         total = B.conv_mcmk_workspace_bytes(desc, variant)
         copies = (result_floats + 3) // 4 * 4 * 4
-        assert total in [matrix_bytes] + [(matrix_bytes + 255) // 256 * 256 + parts * copies for parts in (2, 4, 8)]
+        assert total in [matrix_bytes] + [(matrix_bytes + 255) // 256 * 256 + parts * copies for parts in (2, 4, 8, 16)]
         return total
     assert B.conv_mcmk_workspace_bytes(d, B.KN2ROW) == 0
     assert B.conv_mcmk_workspace_bytes(d, B.DIRECT) == 0
