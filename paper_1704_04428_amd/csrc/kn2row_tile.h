@@ -71,7 +71,7 @@ struct TileArgs {
     int relu;             // nonzero: negative results are stored as zero (csplit == 1 only)
 };
 
-template <int KS, int TH, int TW, int WM, int WP, int CCH = 16, int KG = 1, int ST = 1, int VQL = CCH / 4>
+template <int KS, int TH, int TW, int WM, int WP, int CCH = 16, int KG = 1, int ST = 1, int VQL = CCH / 4, bool CL = false>
 struct TileShape {
     static constexpr int kCC = CCH;                      // channels per chunk, a multiple of 16
     static constexpr int kSC = 4 * VQL;                  // channels of a chunk that are staged and multiplied
@@ -93,7 +93,14 @@ struct TileShape {
     // fragment touches start 16 banks apart.  Stride 2: the 16 positions of a fragment sit on every
     // second bank, and an odd channel stride puts the next channel on the banks between them.
     static constexpr int kCHS = ST == 1 ? ((kPosStage + 15) / 32) * 32 + 16 : (kPosStage | 1);
-    static constexpr int kBuf = kSC * kCHS;              // words per LDS buffer
+    // Channels-last input at unit stride keeps the tile position-major instead: the staged channels of one position
+    // side by side (what a 16-byte load of four channels brings is one 16-byte LDS store), positions kPS words apart.
+    // kPS = channels + 4: a multiple of 4 for the 16-byte stores, and 4 (mod 16) so that the 16 consecutive positions
+    // of a B fragment fall on every fourth bank, its four channels on the banks between: two lanes per bank, the least
+    // 64 lanes can have.
+    static constexpr bool kPosMajor = CL && ST == 1;
+    static constexpr int kPS = kSC + 4;
+    static constexpr int kBuf = kPosMajor ? kPos * kPS : kSC * kCHS;   // words per LDS buffer
     static constexpr int kNPB = (TH * TW + 15) / 16;     // 16-position blocks per tile
     static constexpr int kPBW = (kNPB + WP - 1) / WP;    // blocks per wave
     static constexpr int kSlots = (kSC * kPosStage + kGroupThreads - 1) / kGroupThreads;
@@ -124,12 +131,14 @@ struct TileShape {
 template <int KS, int TH, int TW, int WM, int WP, int CCH = 16, bool CL = false, int KG = 1, int ST = 1, int VQL = CCH / 4>
 __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileArgs a)
 {
-    using S = TileShape<KS, TH, TW, WM, WP, CCH, KG, ST, VQL>;
+    using S = TileShape<KS, TH, TW, WM, WP, CCH, KG, ST, VQL, CL>;
     static_assert(VQL == CCH / 4 || (!CL && KG == 1 && CCH == 16), "the lean form exists for [C][H][W] input without channel groups");
     static_assert(CCH % 16 == 0, "a chunk is a whole number of packed 16-channel groups");
     constexpr int NQ = CCH / 16;                   // packed A vectors per tap and chunk
     constexpr int CC = S::kCC, SC = S::kSC, NT = S::kGroupThreads, WT = S::kWT, POS = S::kPos, POSS = S::kPosStage, CHS = S::kCHS;
     constexpr int PBW = S::kPBW, NPB = S::kNPB, SLOTS = S::kSlots, BUF = S::kBuf, NBUF = S::kNBuf;
+    constexpr bool PM = S::kPosMajor;              // position-major tile (channels last, unit stride)
+    constexpr int PS = S::kPS;
     // position blocks are dealt evenly to the WP waves: the first REM waves own PBW blocks, the
     // others PBW-1 (all own PBW when the split is exact)
     constexpr int REM = NPB % WP;
@@ -223,14 +232,21 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
     // lanes can have), and the next 64 items are the next two quads of the same positions.
     // Offsets are recomputed per chunk (an opaque copy of tid keeps the compiler from
     // hoisting them into more live registers).
+    // (With the position-major tile of unit stride the quads of one position are neighbouring lanes instead: a wave's
+    // load is whole 64- or 128-byte runs of memory, and its store one 16-byte write per lane.)
     constexpr int QPC = CC / 4;                                   // channel quads per chunk
     constexpr int QH = QPC / 2 > 0 ? QPC / 2 : 1;                 // 64-item groups per 32 positions
-    constexpr int VITEMS = 64 * QH * ((POS + 31) / 32);
+    constexpr int VITEMS = PM ? POS * QPC : 64 * QH * ((POS + 31) / 32);
     constexpr int VSLOTS = (VITEMS + NT - 1) / NT;                // items per thread
     auto cl_item = [](int e, int &quad, int &pos) {
-        const int grp64 = e >> 6, l = e & 63;
-        quad = (l & 1) + 2 * (grp64 % QH);
-        pos = 32 * (grp64 / QH) + (l >> 1);
+        if constexpr (PM) {
+            quad = e % QPC;
+            pos = e / QPC;
+        } else {
+            const int grp64 = e >> 6, l = e & 63;
+            quad = (l & 1) + 2 * (grp64 % QH);
+            pos = 32 * (grp64 / QH) + (l >> 1);
+        }
     };
     constexpr int NSTAGE = CL ? 4 * VSLOTS : SLOTS;
     float stage[NSTAGE];
@@ -273,9 +289,14 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
                 int quad, pos;
                 cl_item(t + s * NT, quad, pos);
                 if (pos < POS) {
+                    if constexpr (PM) {
+                        *reinterpret_cast<f32x4 *>(buf + pos * PS + quad * 4) =
+                            f32x4{stage[4 * s], stage[4 * s + 1], stage[4 * s + 2], stage[4 * s + 3]};
+                    } else {
 #pragma unroll
-                    for (int u = 0; u < 4; ++u)
-                        buf[(quad * 4 + u) * CHS + (pos / WT) * WT + (pos % WT)] = stage[4 * s + u];
+                        for (int u = 0; u < 4; ++u)
+                            buf[(quad * 4 + u) * CHS + (pos / WT) * WT + (pos % WT)] = stage[4 * s + u];
+                    }
                 }
             }
         } else {
@@ -295,7 +316,7 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
     for (int b = 0; b < PBW; ++b) {
         int pp = (first_pb + b) * 16 + (lane & 15);
         if (pp >= TH * TW) pp = 0;
-        b_off[b] = (lane >> 4) * CHS + (pp / TW) * ST * WT + (pp % TW) * ST;
+        b_off[b] = PM ? (lane >> 4) + ((pp / TW) * WT + (pp % TW)) * PS : (lane >> 4) * CHS + (pp / TW) * ST * WT + (pp % TW) * ST;
     }
 
     // ---- A fragments: one f32x4 per lane per tap covers a 16-channel chunk.  They are fetched
@@ -380,7 +401,8 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
                 if (g + 1 < G) {
 #pragma unroll
                     for (int b = 0; b < NB; ++b)
-                        bq[(g + 1) & 1][b] = bsrc[b_off[b] + (4 * v1) * CHS + (t1 / KS) * WT + (t1 % KS)];
+                        bq[(g + 1) & 1][b] = PM ? bsrc[b_off[b] + 4 * v1 + ((t1 / KS) * WT + (t1 % KS)) * PS]
+                                                : bsrc[b_off[b] + (4 * v1) * CHS + (t1 / KS) * WT + (t1 % KS)];
                 }
 #pragma unroll
                 for (int b = 0; b < NB; ++b)

@@ -49,7 +49,8 @@ int launch_shape(const TileRequest &rq)
     hipLaunchKernelGGL((kn2row_tile_bf16<MCMK_KS, TH, TW, WM, WP, CL, ST, RB, KG>), dim3((unsigned)blocks), dim3(S::kThreads * KG),
                        kLds, rq.stream, a);
 #else
-    using S = TileShape<MCMK_KS, TH, TW, WM, WP, CCH, KG, ST, VQL>;
+    using S = TileShape<MCMK_KS, TH, TW, WM, WP, CCH, KG, ST, VQL, CL>;
+    static_assert(S::kLdsBytes <= 160 * 1024, "the tile does not fit the LDS of a compute unit");
     if (S::kLdsBytes > 65536) {
         // more than 64 KiB of dynamic LDS has to be allowed per kernel, once per device (two threads that both find
         // the flag clear both set the attribute, which is harmless; the flag itself is read and written atomically)
