@@ -387,7 +387,7 @@ double flat_gemm_us(const conv_mcmk_desc *d, const Dims &dm, bool channels_last,
     // need the second workgroup to cover their latency.  Channels last, the staging gather and its transposing LDS
     // stores cost a fifth to a third (im2row's products).
     double full, single;
-    if (!bf16)           { full = channels_last ? 0.54 : 0.66;   single = channels_last ? 0.50 : 0.60; }
+    if (!bf16)           { full = channels_last ? 0.55 : 0.69;   single = channels_last ? 0.50 : 0.60; }
     else if (t.rb == 2)  { full = channels_last ? 0.26 : 0.40;   single = channels_last ? 0.15 : 0.18; }
     else                 { full = channels_last ? 0.125 : 0.17;  single = channels_last ? 0.08 : 0.09; }
     const double eff = w >= 448 ? full : w >= kNumCU ? single : single * (double)w / kNumCU;

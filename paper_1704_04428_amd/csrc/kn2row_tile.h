@@ -128,9 +128,14 @@ struct TileShape {
 // VQL: channel quads of a chunk that are staged and multiplied: all CCH / 4 of them, or 1 for layers of up to
 //      four channels (an RGB first layer), whose single chunk would otherwise be three quarters zeros: a
 //      quarter of the loads, the LDS and the products.  The packed kernel is the same.
-template <int KS, int TH, int TW, int WM, int WP, int CCH = 16, bool CL = false, int KG = 1, int ST = 1, int VQL = CCH / 4>
+// V4: the flat plain-product shape (1 x 224 positions, 32-channel chunks, 512 threads) on a plane whose length is a
+//     multiple of 4: a tile row is then whole aligned 16-byte vectors of memory, so a thread stages four 16-byte
+//     loads and four 16-byte LDS stores per chunk where the element-wise plan takes fourteen of each.
+template <int KS, int TH, int TW, int WM, int WP, int CCH = 16, bool CL = false, int KG = 1, int ST = 1, int VQL = CCH / 4, bool V4 = false>
 __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileArgs a)
 {
+    static_assert(!V4 || (!CL && KS == 1 && TH == 1 && TW == 224 && KG == 1 && ST == 1 && CCH == 32 && VQL == 8 && WM * WP == 8),
+                  "the vector staging plan is built for the flat shape");
     using S = TileShape<KS, TH, TW, WM, WP, CCH, KG, ST, VQL, CL>;
     static_assert(VQL == CCH / 4 || (!CL && KG == 1 && CCH == 16), "the lean form exists for [C][H][W] input without channel groups");
     static_assert(CCH % 16 == 0, "a chunk is a whole number of packed 16-channel groups");
@@ -248,8 +253,14 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
             pos = 32 * (grp64 / QH) + (l >> 1);
         }
     };
-    constexpr int NSTAGE = CL ? 4 * VSLOTS : SLOTS;
+    constexpr int NSTAGE = V4 ? 16 : CL ? 4 * VSLOTS : SLOTS;
     float stage[NSTAGE];
+    // vector plan: 64 lanes per channel row (56 vectors in use), 8 channel rows per pass, 4 passes per chunk
+    const int v4_p = tid & 63, v4_ch = tid >> 6;
+    const bool v4_used = v4_p < TW / 4;
+    const uint32_t v4_goff = (V4 && v4_used && x0 + 4 * v4_p < a.w)
+        ? ((uint32_t)v4_ch * (uint32_t)plane + (uint32_t)(x0 + 4 * v4_p)) * (uint32_t)sizeof(float) : 0x80000000u;
+    const int v4_loff = v4_ch * CHS + 4 * v4_p;
     auto load_chunk = [&](int chunk) {
         if constexpr (CL) {
             int t = tid;
@@ -265,6 +276,15 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
                 const uint32_t base = (uint32_t)((((size_t)gy * a.w + gx) * a.c + ch) * sizeof(float));
                 const f32x4 v = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
                     in_rsrc, (int)((ok && ch < a.c) ? base : 0x80000000u), 0, 0));
+#pragma unroll
+                for (int u = 0; u < 4; ++u) stage[4 * s + u] = v[u];
+            }
+        } else if constexpr (V4) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const f32x4 v = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
+                    in_rsrc, (int)(v4_goff + (uint32_t)(8 * s) * (uint32_t)(plane * sizeof(float)) +
+                                   (uint32_t)min(chunk, chunks_total) * chunk_bytes), 0, 0));
 #pragma unroll
                 for (int u = 0; u < 4; ++u) stage[4 * s + u] = v[u];
             }
@@ -298,6 +318,13 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_f32(const TileA
                             buf[(quad * 4 + u) * CHS + (pos / WT) * WT + (pos % WT)] = stage[4 * s + u];
                     }
                 }
+            }
+        } else if constexpr (V4) {
+            if (v4_used) {
+#pragma unroll
+                for (int s = 0; s < 4; ++s)
+                    *reinterpret_cast<f32x4 *>(buf + v4_loff + 8 * s * CHS) =
+                        f32x4{stage[4 * s], stage[4 * s + 1], stage[4 * s + 2], stage[4 * s + 3]};
             }
         } else {
 #pragma unroll

@@ -17,7 +17,7 @@
 namespace mcmk {
 namespace {
 
-template <int TH, int TW, int WM, int WP, int CCH = 16, bool CL = false, int KG = 1, int ST = 1, int RB = 1, int VQL = CCH / 4>
+template <int TH, int TW, int WM, int WP, int CCH = 16, bool CL = false, int KG = 1, int ST = 1, int RB = 1, int VQL = CCH / 4, bool V4 = false>
 int launch_shape(const TileRequest &rq)
 {
     TileArgs a = rq.args;
@@ -58,13 +58,13 @@ int launch_shape(const TileRequest &rq)
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 1;
         if (!allowed[dev].load(std::memory_order_acquire)) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&kn2row_tile_f32<MCMK_KS, TH, TW, WM, WP, CCH, CL, KG, ST, VQL>),
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&kn2row_tile_f32<MCMK_KS, TH, TW, WM, WP, CCH, CL, KG, ST, VQL, V4>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::kLdsBytes) != hipSuccess)
                 return 1;
             allowed[dev].store(true, std::memory_order_release);
         }
     }
-    hipLaunchKernelGGL((kn2row_tile_f32<MCMK_KS, TH, TW, WM, WP, CCH, CL, KG, ST, VQL>), dim3((unsigned)blocks), dim3(S::kThreads),
+    hipLaunchKernelGGL((kn2row_tile_f32<MCMK_KS, TH, TW, WM, WP, CCH, CL, KG, ST, VQL, V4>), dim3((unsigned)blocks), dim3(S::kThreads),
                        S::kLdsBytes, rq.stream, a);
 #endif
     return hipGetLastError() == hipSuccess ? 0 : 1;
@@ -164,7 +164,13 @@ int MCMK_FN(const TileRequest &rq)
     case 6: return launch_shape<14, 14, 1, 4, 16, false, 4>(rq);   // four channel groups in the workgroup
 #endif
 #if MCMK_KS == 1
-    case 7: return launch_shape<1, 224, 4, 2, 32>(rq);     // plain GEMM: deeper chunks, fewer barriers
+    case 7:                                                // plain GEMM: deeper chunks, fewer barriers
+#if !MCMK_BF16
+        // a plane of whole 16-byte vectors (the operand itself is 16-byte aligned): the vector staging plan
+        if (rq.args.h == 1 && rq.args.w % 4 == 0 && (reinterpret_cast<uintptr_t>(rq.args.in) & 15u) == 0)
+            return launch_shape<1, 224, 4, 2, 32, false, 1, 1, 1, 8, true>(rq);
+#endif
+        return launch_shape<1, 224, 4, 2, 32>(rq);
 #endif
 #if MCMK_KS <= 5
     case 13: return launch_shape<7, 7, 1, 4>(rq);                           // quarter tiles for small images

@@ -272,7 +272,7 @@ def test_kernel_register_budget():
     # kernels that sit at the 256-register limit; anything beyond 64 bytes per lane means a loop is spilling
     spilling = {k: v for k, v in usage.items() if v.get("ScratchSize", 0) > 64}
     assert not spilling, spilling
-    wide = [v for k, v in usage.items() if "kn2row_tile_f32ILi3ELi14ELi14ELi4ELi2ELi16E" in k and k.endswith("Li1ELi1ELi4EEEvNS_8TileArgsE")]
+    wide = [v for k, v in usage.items() if "kn2row_tile_f32ILi3ELi14ELi14ELi4ELi2ELi16E" in k and k.endswith("Li1ELi1ELi4ELb0EEEvNS_8TileArgsE")]
     assert len(wide) == 2                                   # unit stride, one channel group, all four channel quads: NCHW and channels-last
     assert all(v["VGPRs"] + v.get("AGPRs", 0) <= 128 for v in wide), wide
 
