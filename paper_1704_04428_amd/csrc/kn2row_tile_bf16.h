@@ -153,6 +153,13 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_bf16(const Tile
         const_cast<uint16_t *>(in_img), 0, (int)((size_t)a.c * plane * sizeof(uint16_t)), 0x00020000);
     const uint32_t plane_bytes = (uint32_t)(plane * sizeof(uint16_t));
     const uint32_t chunk_bytes = (uint32_t)CC * plane_bytes;
+    const int nchunks = a.cg;
+    // this part's share of the chunks (nchunks * csplit stays far below 2^31: no 64-bit division)
+    const int chunk_lo = a.csplit > 1 ? (int)((unsigned)(nchunks * part) / (unsigned)a.csplit) : 0;
+    const int chunk_hi = a.csplit > 1 ? (int)((unsigned)(nchunks * (part + 1)) / (unsigned)a.csplit) : nchunks;
+    // a chunk index at or beyond chunk_hi (the prefetch past the end, or the step a channel group sits out when the
+    // chunks do not divide among the groups) is staged as zeros: its offset is moved beyond the data
+    auto staged_chunk = [&](int chunk) { return chunk < chunk_hi ? chunk : a.cg; };
     constexpr int NSEL = CL ? 1 : PSLOTS;
     uint32_t g_off[NSEL];    // byte offset of the slot's dword in the first channel of its octet, chunk 0, or 2 GiB
     uint32_t sel_a[NSEL];    // permute selector for the first column of the pair, ...
@@ -207,7 +214,7 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_bf16(const Tile
                 const int r = pos / WT, col = pos % WT;
                 const int gy = iy0 + r, gx = ix0 + col;
                 const int ch = chunk * CC + oct * 8;
-                const bool ok = e < S::kItems && gy >= 0 && gy < a.h && gx >= 0 && gx < a.w && ch < a.c;
+                const bool ok = e < S::kItems && gy >= 0 && gy < a.h && gx >= 0 && gx < a.w && ch < a.c && chunk < chunk_hi;
                 const uint32_t off = ok ? (uint32_t)((((size_t)gy * a.w + gx) * a.c + ch) * sizeof(uint16_t)) : 0x80000000u;
                 stage_cl[s] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(in_rsrc, (int)off, 0, 0));
             }
@@ -217,7 +224,7 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_bf16(const Tile
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
                     stage[s][e] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(
-                        in_rsrc, (int)(g_off[s] + (uint32_t)e * plane_bytes + (uint32_t)min(chunk, a.cg) * chunk_bytes), 0, 0);
+                        in_rsrc, (int)(g_off[s] + (uint32_t)e * plane_bytes + (uint32_t)staged_chunk(chunk) * chunk_bytes), 0, 0);
         }
     };
     auto store_chunk = [&](unsigned char *buf) {
@@ -265,10 +272,6 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_bf16(const Tile
     constexpr int T = KS * KS;
     constexpr int D = KS;
     static_assert(T % D == 0, "ring slots must be static");
-    const int nchunks = a.cg;
-    // this part's share of the chunks (nchunks * csplit stays far below 2^31: no 64-bit division)
-    const int chunk_lo = a.csplit > 1 ? (int)((unsigned)(nchunks * part) / (unsigned)a.csplit) : 0;
-    const int chunk_hi = a.csplit > 1 ? (int)((unsigned)(nchunks * (part + 1)) / (unsigned)a.csplit) : nchunks;
     const u32x4 *apk = reinterpret_cast<const u32x4 *>(a.apk);
     struct AFrag { u32x4 r[RB]; };
     auto load_a = [&](int chunk, int t) {
@@ -308,6 +311,7 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_bf16(const Tile
         constexpr int kAhead = NF > kWant ? kWant : NF - 1;
         constexpr int R = kAhead + 1;
         const unsigned char *bsrc = lds_raw + (step & 1) * BUF;
+        const uint32_t a_keep = (KG > 1 && chunk >= chunk_hi) ? 0u : ~0u;          // wave-uniform
         auto read_frag = [&](int s) {
             const int t = s / NB, b = s % NB;
             return *reinterpret_cast<const u32x4 *>(bsrc + b_off[b] + (t / KS) * RSB + (t % KS) * 16);
@@ -317,7 +321,13 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_bf16(const Tile
         for (int s = 0; s < kAhead; ++s) ring[s % R] = read_frag(s);
 #pragma unroll
         for (int t = 0; t < T; ++t) {
-            const AFrag a_cur = a_ring[t % D];
+            AFrag a_cur = a_ring[t % D];
+            if constexpr (KG > 1) {
+                // the step a group sits out: its A fragments count as zeros (and so was its chunk staged), so the
+                // products add nothing and no branch around the chunk's work stands between a load and its use
+#pragma unroll
+                for (int r = 0; r < RB; ++r) a_cur.r[r] &= a_keep;
+            }
             a_ring[t % D] = load_a(chunk + KG * ((t + D) / T), (t + D) % T);
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
@@ -336,15 +346,34 @@ __global__ __launch_bounds__(64 * WM * WP * KG) void kn2row_tile_bf16(const Tile
     };
 
     const int nsteps = (chunk_hi - chunk_lo + KG - 1) / KG;       // the same for every group: barriers match
-    for (int step = 0; step < nsteps; ++step) {
-        const int chunk = chunk_first + step * KG;
-        load_chunk(chunk + KG);
-        if (KG == 1 || chunk < chunk_hi) {                        // wave-uniform
-            if (kRagged && nb_wave != PBW) compute_chunk(std::integral_constant<int, kRagged ? PBW - 1 : PBW>{}, chunk, step);
-            else compute_chunk(std::integral_constant<int, PBW>{}, chunk, step);
+    // The wave's share of the position blocks (PBW, or PBW - 1 for the ragged last shares) picks one of two copies of the
+    // whole loop, not of a chunk's work inside one loop, and a channel group works through the step it sits out with
+    // zeros instead of branching around it: where two paths meet again the compiler pins the A ring and the
+    // accumulators to fixed registers with copies, and a copy of a register that a load issued two products ago is
+    // still filling waits for that load -- once per chunk, with one or two waves per SIMD to cover it.  (The fp32
+    // kernel keeps the choice inside its loop: with four waves per SIMD the wait costs it nothing, and the same
+    // change measured 3 - 4 % slower on its channel-group shapes.)
+    auto run_steps = [&](auto nb_tag) {
+        for (int step = 0; step < nsteps; ++step) {
+            const int chunk = chunk_first + step * KG;
+            load_chunk(chunk + KG);
+            if constexpr (decltype(nb_tag)::value < 0) {
+                if (kRagged && nb_wave != PBW) compute_chunk(std::integral_constant<int, kRagged ? PBW - 1 : PBW>{}, chunk, step);
+                else compute_chunk(std::integral_constant<int, PBW>{}, chunk, step);
+            } else {
+                compute_chunk(nb_tag, chunk, step);
+            }
+            store_chunk(lds_raw + ((step + 1) & 1) * BUF);
+            __syncthreads();
         }
-        store_chunk(lds_raw + ((step + 1) & 1) * BUF);
-        __syncthreads();
+    };
+    if constexpr (ST == 1) {
+        if (kRagged && nb_wave != PBW) run_steps(std::integral_constant<int, kRagged ? PBW - 1 : PBW>{});
+        else run_steps(std::integral_constant<int, PBW>{});
+    } else {
+        // (the strided kernels keep the choice inside the loop: with two copies of their larger loop the compiler
+        // spilled the 1 x 4 wave layouts to scratch)
+        run_steps(std::integral_constant<int, -1>{});
     }
 
     // ---- add the channel groups' partial sums: groups 1.. park theirs in LDS (the staging buffers
