@@ -175,7 +175,7 @@ def test_one_by_one_entry_point(dtype, case):
 
 
 @pytest.mark.parametrize("variant", [B.KN2ROW, B.KN2COL], ids=["kn2row", "kn2col"])
-@pytest.mark.parametrize("dtype,case", [(B.F32, (8, 48, 40, 40, 256, 1, 0, 1)), (B.F32, (6, 40, 50, 30, 200, 1, 0, 1)),
+@pytest.mark.parametrize("dtype,case", [(B.F32, (8, 48, 40, 40, 256, 1, 0, 1)), (B.F32, (8, 128, 50, 30, 500, 1, 0, 1)), (B.F32, (8, 128, 51, 29, 500, 1, 0, 1)),
                                         (B.BF16, (8, 256, 40, 40, 512, 1, 0, 1))])
 def test_one_by_one_layers_run_as_a_plain_product(dtype, case, variant):
     """Large 1 x 1 layers without padding or stride, [C][H][W] input: the fused call runs on the flat tile shape over
